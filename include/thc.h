@@ -1,0 +1,144 @@
+/*
+ * thc.h - C ABI of the MI355X (gfx950) library for the all-reduce-compatible
+ * gradient quantization path of the paper's THC case study:
+ *
+ *   partial rotation (randomized Hadamard transform of every 2^l' chunk)
+ *     -> per-chunk range shared by all workers
+ *     -> stochastic rounding onto a 2^bits-point grid
+ *     -> exact integer summation of the workers' payloads
+ *     -> dequantize + inverse rotation.
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers unless the comment says HOST.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and never synchronise.
+ *   - The caller owns every buffer.  Unless an entry point says otherwise the
+ *     library allocates nothing and keeps no state between calls.
+ *   - Inputs and outputs of one call must not overlap.
+ *   - n is the number of gradient coordinates of ONE worker, c = 2^chunk_log2 the
+ *     chunk length (1 <= chunk_log2 <= 14), chunks = ceil(n / c).  Coordinates
+ *     with index >= n inside the last chunk are zeros on input and are not
+ *     written on output of length n.
+ *   - n == 0 is a successful no-op.
+ *   - Arguments are checked on the host before any HIP call; a bad argument
+ *     returns a negative thc_status and enqueues nothing.  A failed launch
+ *     returns THC_ERR_HIP.
+ *   - Gradient, y and output pointers must be aligned to their element size;
+ *     payload and sums pointers to 16 bytes (THC_ERR_ALIGN otherwise).
+ *   - Non-finite gradient values are not detected: the scale and payload of the
+ *     chunk that holds them are unspecified, other chunks are unaffected.
+ *
+ * Random streams (the paper names no generator; both are Philox4x32-10, key =
+ * (low, high) 32 bits of `seed`, g the coordinate's index within the call):
+ *   sign of coordinate g : bit (g mod 32) of word ((g div 32) mod 4) of the
+ *       block with counter (lo32(g div 128), hi32(g div 128), 0, 0x5349474E);
+ *       the same for every worker.
+ *   rounding byte r_g    : byte (g mod 16) (little-endian through words 0..3) of
+ *       the block with counter (lo32(g div 16), hi32(g div 16), worker,
+ *       0x524F554E); u_g = (r_g + 0.5) / 256.
+ */
+#ifndef THC_H_
+#define THC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { THC_F32 = 0, THC_BF16 = 1 } thc_dtype;
+
+typedef enum {
+    THC_OK = 0,
+    THC_ERR_NULL = -1,    /* a required pointer is NULL */
+    THC_ERR_BITS = -2,    /* bits not in {2, 4, 8} */
+    THC_ERR_CHUNK = -3,   /* chunk_log2 outside [1, 14] */
+    THC_ERR_WORKERS = -4, /* W == 0 or W * (2^bits - 1) > 65535 */
+    THC_ERR_DTYPE = -5,   /* dtype not THC_F32 / THC_BF16 */
+    THC_ERR_SIZE = -6,    /* a size overflows or exceeds a stated maximum */
+    THC_ERR_HIP = -7,     /* a HIP call failed; see hipGetLastError */
+    THC_ERR_ALIGN = -8    /* a pointer is not aligned as required */
+} thc_status;
+
+/* Text for a status code.  Static storage, never NULL. */
+const char* thc_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int thc_version(void);
+
+/* Random bits consumed per coordinate by the stochastic rounding (8). */
+uint32_t thc_rounding_bits(void);
+
+/* ceil(n / 2^chunk_log2): the number of independently rotated chunks ("Partial
+ * rotation").  0 if chunk_log2 is out of range. */
+uint64_t thc_num_chunks(uint64_t n, uint32_t chunk_log2);
+
+/* Bytes of one worker's packed payload: chunks * 2^chunk_log2 * bits / 8 (the
+ * padded tail of the last chunk is part of the payload).  0 on bad arguments. */
+uint64_t thc_payload_bytes(uint64_t n, uint32_t chunk_log2, uint32_t bits);
+
+/* Bytes per aggregated coordinate: 1 if W * (2^bits - 1) <= 255, 2 if <= 65535,
+ * else 0.  This is the widened aggregate of the paper's "simple adaptation"
+ * (b >= q bits so that sums of q-bit values cannot overflow). */
+uint32_t thc_sum_bytes(uint32_t W, uint32_t bits);
+
+/* Partial rotation, forward: y = (1/sqrt(c)) H_c D x for every chunk, H_c the
+ * Sylvester-ordered Hadamard matrix, D the seeded +-1 diagonal above.
+ *   x   n values of dtype dt (fp32, or bf16 widened exactly)
+ *   y   chunks * c fp32 values (the zero-padded tail is rotated too) */
+int rht_forward(const void* x, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                float* y, void* stream);
+
+/* Partial rotation, inverse: x = D (1/sqrt(c)) H_c y; undoes rht_forward.
+ *   y   chunks * c fp32 values;   x   n fp32 values */
+int rht_inverse(const float* y, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                float* x, void* stream);
+
+/* Per-chunk range of one worker after the partial rotation ("we compute the
+ * value range of each chunk"), in the symmetric form used here:
+ * absmax[p] = max_j |y_j| over chunk p of rht_forward(grad).
+ *   absmax   chunks fp32 values */
+int thc_chunk_absmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2,
+                     uint64_t seed, float* absmax, void* stream);
+
+/* Shared grid: scale[p] = max over workers of absmax_all[w][p].  Stands in for
+ * the small max-all-reduce that lets every worker quantize onto the same grid,
+ * so that integer payloads can be summed.
+ *   absmax_all   W * chunks fp32, worker-major;   scale   chunks fp32 */
+int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
+                     void* stream);
+
+/* Encode one worker: rotate, then stochastically round every rotated value onto
+ * the 2^bits-point grid of [-s_p, +s_p] (index 0 at -s_p, index L = 2^bits - 1 at
+ * +s_p), and bit-pack:
+ *     inv = L / (s_p + s_p)  (0 if s_p == 0),  v = (y + s_p) * inv,
+ *     idx = min(floor(v + u), L),  u = (r + 0.5) / 256
+ * every operation a separately rounded fp32 operation.
+ *   shared_scale  chunks fp32 (the output of thc_scale_reduce), or NULL to use
+ *                 this worker's own absmax
+ *   payload       thc_payload_bytes bytes; coordinate g occupies bits
+ *                 [(g*bits) mod 8, +bits) of byte (g*bits) div 8
+ *   scale_out     chunks fp32 receiving the scale that was used; may be NULL */
+int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+               uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+               float* scale_out, void* stream);
+
+/* Aggregate: sums[g] = sum over w < W of the index worker w stored for
+ * coordinate g; exact (the reduction an all-reduce of the payloads performs,
+ * with b >= q bits per coordinate so it cannot overflow).
+ *   payloads   HOST array of W device pointers, each thc_payload_bytes bytes
+ *   sums       chunks * c elements of thc_sum_bytes(W, bits) bytes each */
+int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                  uint32_t bits, void* sums, void* stream);
+
+/* Decode the aggregate into the estimate of the workers' MEAN gradient:
+ *     step = (s_p + s_p) / L,  yhat = float(sum) * (step / W) - s_p,
+ *     out  = D (1/sqrt(c)) H_c yhat   (first n coordinates)
+ *   sums    as written by thc_aggregate;   scale   chunks fp32;   out   n fp32 */
+int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uint32_t chunk_log2,
+               uint64_t seed, uint32_t bits, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THC_H_ */

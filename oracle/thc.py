@@ -63,8 +63,9 @@ def num_chunks(n, chunk_log2):
 
 
 def payload_bytes(n, chunk_log2, bits):
-    """Bytes of one worker's packed q-bit payload (padded chunks included)."""
-    return num_chunks(n, chunk_log2) * (1 << chunk_log2) * bits // 8
+    """Bytes of one worker's packed q-bit payload (padded chunks included; a last
+    partial byte, possible only for 2 coordinates of 2 bits, is counted whole)."""
+    return (num_chunks(n, chunk_log2) * (1 << chunk_log2) * bits + 7) // 8
 
 
 def sum_dtype(W, bits):
@@ -241,6 +242,8 @@ def pack(idx, bits):
     if bits == 8:
         return idx.astype(np.uint8)
     per = 8 // bits
+    if idx.size % per:
+        idx = np.concatenate([idx, np.zeros(per - idx.size % per, dtype=np.uint16)])
     g = idx.reshape(-1, per)
     out = np.zeros(g.shape[0], dtype=np.uint16)
     for j in range(per):
@@ -260,7 +263,7 @@ def unpack(payload, bits):
 
 
 # ----------------------------------------------------------------------- aggregate
-def aggregate(payloads, bits):
+def aggregate(payloads, bits, count=None):
     """S_g = sum over workers of idx_g^(w), exact, in the narrowest of u8/u16 that
     cannot overflow ("All-reduce incompatibility": b >= q bits for the sums)."""
     W = len(payloads)
@@ -268,6 +271,8 @@ def aggregate(payloads, bits):
     for p in payloads:
         total += unpack(p, bits)
     assert total.max(initial=0) <= W * ((1 << bits) - 1)
+    if count is not None:            # drop the unused bits of a last partial byte
+        total = total[:count]
     return total.astype(sum_dtype(W, bits))
 
 

@@ -1,0 +1,182 @@
+"""ctypes binding of libthc.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/thc.h and does no arithmetic of its own; PyTorch supplies device memory
+and the stream.  The library must have been built (python -m
+paper_2407_01378_amd.build): there is no fallback, a missing library raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libthc.so")
+
+THC_F32, THC_BF16 = 0, 1
+THC_OK = 0
+
+_lib = None
+
+_u8pp = ctypes.POINTER(ctypes.c_void_p)
+_SIGNATURES = {
+    "thc_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "thc_version": (ctypes.c_int, []),
+    "thc_rounding_bits": (ctypes.c_uint32, []),
+    "thc_num_chunks": (ctypes.c_uint64, [ctypes.c_uint64, ctypes.c_uint32]),
+    "thc_payload_bytes": (ctypes.c_uint64, [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32]),
+    "thc_sum_bytes": (ctypes.c_uint32, [ctypes.c_uint32, ctypes.c_uint32]),
+    "rht_forward": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                   ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "rht_inverse": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
+                                   ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_chunk_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64,
+                                        ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p,
+                                        ctypes.c_void_p]),
+    "thc_scale_reduce": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64,
+                                        ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_encode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                  ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
+                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.c_void_p]),
+    "thc_aggregate": (ctypes.c_int, [_u8pp, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32,
+                                     ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                  ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                  ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]),
+}
+
+
+class ThcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def lib():
+    """The loaded shared library (loads it on first use; raises if it is not built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2407_01378_amd.build`; "
+                "there is no fallback path")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def exported_names():
+    return sorted(_SIGNATURES)
+
+
+def status_string(status):
+    return lib().thc_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != THC_OK:
+        raise ThcError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return THC_F32
+    if t.dtype == torch.bfloat16:
+        return THC_BF16
+    raise TypeError(f"gradient dtype {t.dtype} is not fp32 or bf16")
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _flat(t, dtype=None):
+    if not t.is_contiguous() or t.dim() != 1:
+        raise ValueError("expected a contiguous 1-D tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t
+
+
+# ------------------------------------------------------------------ size helpers
+def thc_version():
+    return lib().thc_version()
+
+
+def thc_rounding_bits():
+    return lib().thc_rounding_bits()
+
+
+def thc_num_chunks(n, chunk_log2):
+    return lib().thc_num_chunks(n, chunk_log2)
+
+
+def thc_payload_bytes(n, chunk_log2, bits):
+    return lib().thc_payload_bytes(n, chunk_log2, bits)
+
+
+def thc_sum_bytes(W, bits):
+    return lib().thc_sum_bytes(W, bits)
+
+
+# ------------------------------------------------------------------- entry points
+def rht_forward(x, chunk_log2, seed, y, stream=None):
+    _flat(x), _flat(y, torch.float32)
+    _check(lib().rht_forward(_ptr(x), _dtype_code(x), x.numel(), chunk_log2, seed, _ptr(y),
+                             _stream(stream)), "rht_forward")
+    return y
+
+
+def rht_inverse(y, n, chunk_log2, seed, x, stream=None):
+    _flat(y, torch.float32), _flat(x, torch.float32)
+    _check(lib().rht_inverse(_ptr(y), n, chunk_log2, seed, _ptr(x), _stream(stream)),
+           "rht_inverse")
+    return x
+
+
+def thc_chunk_absmax(grad, chunk_log2, seed, absmax, stream=None):
+    _flat(grad), _flat(absmax, torch.float32)
+    _check(lib().thc_chunk_absmax(_ptr(grad), _dtype_code(grad), grad.numel(), chunk_log2, seed,
+                                  _ptr(absmax), _stream(stream)), "thc_chunk_absmax")
+    return absmax
+
+
+def thc_scale_reduce(absmax_all, W, chunks, scale, stream=None):
+    _check(lib().thc_scale_reduce(_ptr(absmax_all), W, chunks, _ptr(scale), _stream(stream)),
+           "thc_scale_reduce")
+    return scale
+
+
+def thc_encode(grad, chunk_log2, seed, worker, bits, shared_scale, payload, scale_out=None,
+               stream=None):
+    _flat(grad), _flat(payload, torch.uint8)
+    _check(lib().thc_encode(_ptr(grad), _dtype_code(grad), grad.numel(), chunk_log2, seed, worker,
+                            bits, _ptr(shared_scale), _ptr(payload), _ptr(scale_out),
+                            _stream(stream)), "thc_encode")
+    return payload
+
+
+def thc_aggregate(payloads, n, chunk_log2, bits, sums, stream=None):
+    W = len(payloads)
+    arr = (ctypes.c_void_p * max(W, 1))(*[p.data_ptr() for p in payloads])
+    _check(lib().thc_aggregate(ctypes.cast(arr, _u8pp), W, n, chunk_log2, bits, _ptr(sums),
+                               _stream(stream)), "thc_aggregate")
+    return sums
+
+
+def thc_decode(sums, scale, W, n, chunk_log2, seed, bits, out, stream=None):
+    _flat(out, torch.float32)
+    _check(lib().thc_decode(_ptr(sums), _ptr(scale), W, n, chunk_log2, seed, bits, _ptr(out),
+                            _stream(stream)), "thc_decode")
+    return out

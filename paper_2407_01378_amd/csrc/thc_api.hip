@@ -1,0 +1,211 @@
+// C ABI of the library: argument checking on the host (before any HIP call), then
+// dispatch to the kernel launchers.  See include/thc.h for the contract.
+#include <math.h>
+
+#include "thc_internal.h"
+
+namespace {
+
+using thc::ChunkArgs;
+using thc::Mode;
+
+constexpr uint64_t kMaxCoords = 1ull << 44;  // keeps every byte count far below 2^63
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_common(uint64_t n, uint32_t chunk_log2) {
+    if (chunk_log2 < 1 || chunk_log2 > 14) return THC_ERR_CHUNK;
+    if (n > kMaxCoords) return THC_ERR_SIZE;
+    return THC_OK;
+}
+
+int check_bits(uint32_t bits) { return (bits == 2 || bits == 4 || bits == 8) ? THC_OK : THC_ERR_BITS; }
+
+int check_dtype(int dt) { return (dt == THC_F32 || dt == THC_BF16) ? THC_OK : THC_ERR_DTYPE; }
+
+uint64_t padded_coords(uint64_t n, uint32_t chunk_log2) {
+    const uint64_t c = 1ull << chunk_log2;
+    return (n + c - 1) / c * c;
+}
+
+ChunkArgs base_args(uint64_t n, uint32_t chunk_log2, uint64_t seed) {
+    ChunkArgs a{};
+    a.n = n;
+    a.padded = padded_coords(n, chunk_log2);
+    a.chunk_log2 = chunk_log2;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.inv_sqrt_c = (float)(1.0 / sqrt((double)(1ull << chunk_log2)));
+    return a;
+}
+
+int finish(hipError_t e) { return e == hipSuccess ? THC_OK : THC_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* thc_status_string(int status) {
+    switch (status) {
+        case THC_OK: return "ok";
+        case THC_ERR_NULL: return "a required pointer is NULL";
+        case THC_ERR_BITS: return "bits must be 2, 4 or 8";
+        case THC_ERR_CHUNK: return "chunk_log2 must be in [1, 14]";
+        case THC_ERR_WORKERS: return "W must be >= 1 and W * (2^bits - 1) <= 65535";
+        case THC_ERR_DTYPE: return "dtype must be THC_F32 or THC_BF16";
+        case THC_ERR_SIZE: return "size out of range";
+        case THC_ERR_HIP: return "HIP call failed";
+        case THC_ERR_ALIGN: return "pointer not aligned as required";
+        default: return "unknown status";
+    }
+}
+
+int thc_version(void) { return 100; }
+
+uint32_t thc_rounding_bits(void) { return 8; }
+
+uint64_t thc_num_chunks(uint64_t n, uint32_t chunk_log2) {
+    if (check_common(n, chunk_log2) != THC_OK) return 0;
+    return padded_coords(n, chunk_log2) >> chunk_log2;
+}
+
+uint64_t thc_payload_bytes(uint64_t n, uint32_t chunk_log2, uint32_t bits) {
+    if (check_common(n, chunk_log2) != THC_OK || check_bits(bits) != THC_OK) return 0;
+    return (padded_coords(n, chunk_log2) * bits + 7) / 8;
+}
+
+uint32_t thc_sum_bytes(uint32_t W, uint32_t bits) {
+    if (W == 0 || check_bits(bits) != THC_OK) return 0;
+    const uint64_t top = (uint64_t)W * ((1u << bits) - 1u);
+    if (top <= 255) return 1;
+    if (top <= 65535) return 2;
+    return 0;
+}
+
+int rht_forward(const void* x, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                float* y, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!x || !y) return THC_ERR_NULL;
+    if (!aligned(x, dt == THC_F32 ? 4 : 2) || !aligned(y, 4)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = x;
+    a.out = y;
+    a.in_bf16 = dt == THC_BF16;
+    return finish(thc::launch_generic(Mode::Forward, a, static_cast<hipStream_t>(stream)));
+}
+
+int rht_inverse(const float* y, uint64_t n, uint32_t chunk_log2, uint64_t seed, float* x,
+                void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!x || !y) return THC_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y, 4)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = y;
+    a.out = x;
+    return finish(thc::launch_generic(Mode::Inverse, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_chunk_absmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2,
+                     uint64_t seed, float* absmax, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!grad || !absmax) return THC_ERR_NULL;
+    if (!aligned(grad, dt == THC_F32 ? 4 : 2) || !aligned(absmax, 4)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = grad;
+    a.out = absmax;
+    a.in_bf16 = dt == THC_BF16;
+    return finish(thc::launch_generic(Mode::Absmax, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
+                     void* stream) {
+    if (W == 0) return THC_ERR_WORKERS;
+    if (chunks > kMaxCoords || (uint64_t)W * chunks > kMaxCoords) return THC_ERR_SIZE;
+    if (chunks == 0) return THC_OK;
+    if (!absmax_all || !scale) return THC_ERR_NULL;
+    if (!aligned(absmax_all, 4) || !aligned(scale, 4)) return THC_ERR_ALIGN;
+    return finish(
+        thc::launch_scale_reduce(absmax_all, W, chunks, scale, static_cast<hipStream_t>(stream)));
+}
+
+int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+               uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+               float* scale_out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!grad || !payload) return THC_ERR_NULL;
+    if (!aligned(grad, dt == THC_F32 ? 4 : 2) || !aligned(payload, 16) ||
+        !aligned(shared_scale, 4) || !aligned(scale_out, 4))
+        return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = grad;
+    a.out = payload;
+    a.scale_in = shared_scale;
+    a.scale_out = scale_out;
+    a.in_bf16 = dt == THC_BF16;
+    a.worker = worker;
+    a.bits = bits;
+    a.payload_bytes = (a.padded * bits + 7) / 8;
+    return finish(thc::launch_generic(Mode::Encode, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                  uint32_t bits, void* sums, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    const uint32_t sum_bytes = thc_sum_bytes(W, bits);
+    if (sum_bytes == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!payloads || !sums) return THC_ERR_NULL;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!payloads[w]) return THC_ERR_NULL;
+        if (!aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+    }
+    if (!aligned(sums, 16)) return THC_ERR_ALIGN;
+    const uint64_t padded = padded_coords(n, chunk_log2);
+    const uint64_t payload_bytes = (padded * bits + 7) / 8;
+    for (uint32_t w0 = 0; w0 < W; w0 += thc::kMaxAggBatch) {
+        thc::PayloadBatch batch{};
+        const uint32_t count = (W - w0 < (uint32_t)thc::kMaxAggBatch) ? W - w0 : thc::kMaxAggBatch;
+        for (uint32_t i = 0; i < count; ++i) batch.p[i] = payloads[w0 + i];
+        const hipError_t e =
+            thc::launch_aggregate(batch, count, w0 != 0, bits, sum_bytes, payload_bytes, padded,
+                                  sums, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return THC_ERR_HIP;
+    }
+    return THC_OK;
+}
+
+int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uint32_t chunk_log2,
+               uint64_t seed, uint32_t bits, float* out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    const uint32_t sum_bytes = thc_sum_bytes(W, bits);
+    if (sum_bytes == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!sums || !scale || !out) return THC_ERR_NULL;
+    if (!aligned(sums, 16) || !aligned(scale, 4) || !aligned(out, 4)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = sums;
+    a.out = out;
+    a.scale_in = scale;
+    a.bits = bits;
+    a.W = W;
+    a.sum_bytes = sum_bytes;
+    return finish(thc::launch_generic(Mode::Decode, a, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

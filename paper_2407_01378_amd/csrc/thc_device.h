@@ -1,0 +1,70 @@
+// Device-side helpers shared by the gfx950 kernels: Philox4x32-10, the two random
+// streams (sign diagonal, rounding bytes) and small bit utilities.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+namespace thc {
+
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+constexpr uint32_t kTagSign = 0x5349474Eu;   // fourth counter word of the sign stream
+constexpr uint32_t kTagRound = 0x524F554Eu;  // fourth counter word of the rounding stream
+constexpr int kRoundingBits = 8;             // random bits per coordinate
+constexpr int kCoordsPerRoundBlock = 128 / kRoundingBits;  // 16
+
+struct u32x4 {
+    uint32_t w[4];
+};
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies and
+// a word permutation, key bumped by the Weyl constants between rounds.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    u32x4 o;
+    o.w[0] = c0;
+    o.w[1] = c1;
+    o.w[2] = c2;
+    o.w[3] = c3;
+    return o;
+}
+
+// 128 sign bits of coordinates [128*block, 128*block + 128): bit (g mod 32) of
+// word ((g div 32) mod 4); identical for every worker.
+__device__ __forceinline__ u32x4 sign_block(uint64_t block, uint32_t k0, uint32_t k1) {
+    return philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, kTagSign, k0, k1);
+}
+
+// 16 rounding bytes of coordinates [16*block, 16*block + 16) of one worker.
+__device__ __forceinline__ u32x4 round_block(uint64_t block, uint32_t worker, uint32_t k0,
+                                             uint32_t k1) {
+    return philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), worker, kTagRound, k0, k1);
+}
+
+__device__ __forceinline__ float flip_sign(float v, uint32_t bit) {
+    return __uint_as_float(__float_as_uint(v) ^ (bit << 31));
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) {
+    return __uint_as_float(h << 16);
+}
+
+}  // namespace thc

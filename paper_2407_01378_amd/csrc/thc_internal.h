@@ -1,0 +1,47 @@
+// Host-side declarations shared by the C ABI layer and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "thc.h"
+
+namespace thc {
+
+enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4 };
+
+// One description for every per-chunk kernel (rotation, range, encode, decode).
+struct ChunkArgs {
+    const void* in;         // gradient (fp32/bf16), y (fp32) or sums (u8/u16)
+    void* out;              // y, absmax, payload or x
+    const float* scale_in;  // shared scale (encode, may be null) / scale (decode)
+    float* scale_out;       // scale actually used by encode (may be null)
+    uint64_t n;             // coordinates of one worker
+    uint64_t padded;        // chunks * c
+    uint64_t payload_bytes; // ceil(padded * bits / 8)
+    uint32_t chunk_log2;
+    uint32_t key0, key1;    // seed, low and high word
+    uint32_t worker;
+    uint32_t bits;
+    uint32_t W;
+    uint32_t in_bf16;       // 1: gradient is bf16
+    uint32_t sum_bytes;     // decode: 1 or 2
+    float inv_sqrt_c;       // fp32 nearest of c^(-1/2)
+};
+
+// Generic path: any chunk_log2 in [1, 14], any alignment the ABI allows.
+hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream);
+
+constexpr int kMaxAggBatch = 16;
+struct PayloadBatch {
+    const uint8_t* p[kMaxAggBatch];
+};
+
+hipError_t launch_aggregate(const PayloadBatch& batch, uint32_t count, bool accumulate,
+                            uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes,
+                            uint64_t padded, void* sums, hipStream_t stream);
+
+hipError_t launch_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
+                               hipStream_t stream);
+
+}  // namespace thc

@@ -1,0 +1,83 @@
+"""Helpers for the GPU parity tests: run the path through the C ABI binding."""
+import numpy as np
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import thc as O
+from synth import to_numpy_bits
+
+DEV = "cuda:0"
+
+
+def run_path(xs, l, seed, bits, own_scale=False):
+    """absmax -> scale_reduce -> encode x W -> aggregate -> decode on the GPU.
+    xs: list of W device tensors (fp32 or bf16).  Returns device tensors."""
+    W = len(xs)
+    n = xs[0].numel()
+    dev = xs[0].device
+    P = thc.thc_num_chunks(n, l)
+    absmax = torch.full((W * P,), -1.0, dtype=torch.float32, device=dev)
+    scale = torch.full((P,), -1.0, dtype=torch.float32, device=dev)
+    nb = thc.thc_payload_bytes(n, l, bits)
+    payloads = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=dev) for _ in range(W)]
+    sb = thc.thc_sum_bytes(W, bits)
+    sums = torch.full((P << l,), 77, dtype=torch.uint8 if sb == 1 else torch.int16, device=dev)
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=dev)
+    for w in range(W):
+        thc.thc_chunk_absmax(xs[w], l, seed, absmax[w * P:(w + 1) * P])
+    thc.thc_scale_reduce(absmax, W, P, scale)
+    for w in range(W):
+        thc.thc_encode(xs[w], l, seed, w, bits, scale, payloads[w])
+    thc.thc_aggregate(payloads, n, l, bits, sums)
+    thc.thc_decode(sums, scale, W, n, l, seed, bits, out)
+    torch.cuda.synchronize()
+    return dict(absmax=absmax.view(W, P), scale=scale, payloads=payloads, sums=sums, out=out)
+
+
+def sums_to_numpy(sums):
+    a = sums.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
+def check_against_oracle(xs, got, l, seed, bits, chunks=None):
+    """Element-by-element comparison with the oracle.  chunks: list of chunk
+    indices to check (None = all); the oracle is run on those chunks only, with
+    their global offset."""
+    W = len(xs)
+    n = xs[0].numel()
+    c = 1 << l
+    P = O.num_chunks(n, l)
+    bf16 = xs[0].dtype == torch.bfloat16
+    if chunks is None:
+        groups = [(0, n)]
+    else:
+        groups = [(p * c, min(n, (p + 1) * c) - p * c) for p in sorted(set(chunks))]
+    scale = got["scale"].cpu().numpy()
+    absmax = got["absmax"].cpu().numpy()
+    sums = sums_to_numpy(got["sums"])
+    out = got["out"].cpu().numpy()
+    pay = [p.cpu().numpy() for p in got["payloads"]]
+    worst = 0.0
+    for g0, ln in groups:
+        hx = [to_numpy_bits(x[g0:g0 + ln]) for x in xs]
+        ref = O.pipeline(hx, l, seed, bits, dtype=np.float32, bf16=bf16, g0=g0)
+        p0, np_ = g0 // c, O.num_chunks(ln, l)
+        assert (absmax[:, p0:p0 + np_] == ref["absmax"]).all(), f"absmax differs, chunk {p0}"
+        assert (scale[p0:p0 + np_] == ref["scale"]).all(), f"scale differs, chunk {p0}"
+        b0, b1 = g0 * bits // 8, (g0 + np_ * c) * bits // 8
+        for w in range(W):
+            same = pay[w][b0:b1] == ref["payloads"][w]
+            assert same.all(), f"payload of worker {w} differs in chunk {p0}: {np.flatnonzero(~same)[:8]}"
+        assert (sums[g0:g0 + np_ * c] == ref["sums"]).all(), f"sums differ, chunk {p0}"
+        # decode, stage-wise: float64 definition fed the same sums and scales
+        d64 = O.decode(ref["sums"], ref["scale"].astype(np.float64), W, ln, l, seed, bits, g0=g0)
+        seg = out[g0:g0 + ln]
+        nrm = np.linalg.norm(d64)
+        if nrm == 0:
+            assert (seg == 0).all()
+        else:
+            err = np.linalg.norm(seg - d64) / nrm
+            assert err <= 1e-5, f"decode rel-L2 {err} in chunk {p0}"
+            worst = max(worst, err)
+        assert (seg == ref["out"]).all(), f"decode differs from the fp32 canonical order, chunk {p0}"
+    return worst

@@ -1,0 +1,136 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function the
+header declares, and rejects bad arguments on the host before any HIP call (so no
+GPU is needed: none of these calls may reach a launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_01378_amd as thc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "thc.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(thc.binding.LIB_PATH):
+        from paper_2407_01378_amd.build import build_library
+        build_library(verbose=False)
+    return thc.lib()
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", src)
+    return sorted({n for n in names if n.startswith(("thc_", "rht_"))})
+
+
+def test_every_declared_function_is_exported_and_bound(L):
+    declared = _declared()
+    assert {"rht_forward", "rht_inverse", "thc_chunk_absmax", "thc_scale_reduce", "thc_encode",
+            "thc_aggregate", "thc_decode", "thc_status_string", "thc_version", "thc_num_chunks",
+            "thc_payload_bytes", "thc_sum_bytes"} <= set(declared)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(thc.exported_names()) == declared
+
+
+def test_size_helpers(L):
+    assert thc.thc_version() >= 100
+    assert thc.thc_rounding_bits() == 8
+    assert thc.thc_num_chunks(0, 14) == 0
+    assert thc.thc_num_chunks(1, 14) == 1
+    assert thc.thc_num_chunks(1 << 14, 14) == 1
+    assert thc.thc_num_chunks((1 << 14) + 1, 14) == 2
+    assert thc.thc_num_chunks(25_557_032, 14) == 1560
+    assert thc.thc_num_chunks(1_300_000_000, 14) == 79346
+    assert thc.thc_num_chunks(10, 0) == 0 and thc.thc_num_chunks(10, 15) == 0
+    assert thc.thc_payload_bytes(25_557_032, 14, 4) == 1560 * 8192
+    assert thc.thc_payload_bytes(1 << 20, 10, 2) == (1 << 20) // 4
+    assert thc.thc_payload_bytes(3, 1, 2) == 1          # 4 coordinates of 2 bits
+    assert thc.thc_payload_bytes(1, 1, 2) == 1          # half a byte is counted whole
+    assert thc.thc_payload_bytes(10, 14, 3) == 0
+    assert thc.thc_sum_bytes(4, 4) == 1 and thc.thc_sum_bytes(8, 4) == 1
+    assert thc.thc_sum_bytes(17, 4) == 1 and thc.thc_sum_bytes(18, 4) == 2
+    assert thc.thc_sum_bytes(8, 8) == 2 and thc.thc_sum_bytes(257, 8) == 2
+    assert thc.thc_sum_bytes(258, 8) == 0 and thc.thc_sum_bytes(0, 4) == 0
+    assert thc.thc_sum_bytes(8, 5) == 0
+
+
+def test_status_strings(L):
+    seen = set()
+    for code in range(0, -9, -1):
+        s = thc.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert thc.status_string(-99) == "unknown status"
+
+
+def test_bad_arguments_are_rejected_on_the_host(L):
+    """Dummy non-null addresses are never dereferenced: every call below must fail
+    validation (or be a no-op) before anything is enqueued."""
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1001)
+    nul = ctypes.c_void_p(0)
+    F32, BF16 = thc.THC_F32, thc.THC_BF16
+    # chunk_log2
+    assert L.rht_forward(p, F32, 100, 0, 0, p, nul) == -3
+    assert L.rht_forward(p, F32, 100, 15, 0, p, nul) == -3
+    assert L.rht_inverse(p, 100, 15, 0, p, nul) == -3
+    assert L.thc_chunk_absmax(p, F32, 100, 20, 0, p, nul) == -3
+    # dtype
+    assert L.rht_forward(p, 7, 100, 10, 0, p, nul) == -5
+    assert L.thc_encode(p, 2, 100, 10, 0, 0, 4, nul, p, nul, nul) == -5
+    # bits
+    for bad in (0, 1, 3, 5, 16):
+        assert L.thc_encode(p, F32, 100, 10, 0, 0, bad, nul, p, nul, nul) == -2
+        assert L.thc_decode(p, p, 4, 100, 10, 0, bad, p, nul) == -2
+    # workers
+    arr = (ctypes.c_void_p * 1)(0x1000)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    assert L.thc_aggregate(pp, 0, 100, 10, 4, p, nul) == -4
+    assert L.thc_aggregate(pp, 4370, 100, 10, 4, p, nul) == -4      # 4370 * 15 = 65550
+    assert L.thc_decode(p, p, 0, 100, 10, 0, 4, p, nul) == -4
+    assert L.thc_decode(p, p, 258, 100, 10, 0, 8, p, nul) == -4
+    assert L.thc_scale_reduce(p, 0, 10, p, nul) == -4
+    # size
+    assert L.rht_forward(p, F32, 1 << 50, 10, 0, p, nul) == -6
+    # n == 0: success, nothing touched, even with null buffers
+    assert L.rht_forward(nul, F32, 0, 10, 0, nul, nul) == 0
+    assert L.rht_inverse(nul, 0, 10, 0, nul, nul) == 0
+    assert L.thc_chunk_absmax(nul, BF16, 0, 14, 0, nul, nul) == 0
+    assert L.thc_encode(nul, F32, 0, 10, 0, 0, 4, nul, nul, nul, nul) == 0
+    assert L.thc_aggregate(pp, 1, 0, 10, 4, nul, nul) == 0
+    assert L.thc_decode(nul, nul, 4, 0, 10, 0, 4, nul, nul) == 0
+    assert L.thc_scale_reduce(nul, 4, 0, nul, nul) == 0
+    # null pointers
+    assert L.rht_forward(nul, F32, 100, 10, 0, p, nul) == -1
+    assert L.rht_forward(p, F32, 100, 10, 0, nul, nul) == -1
+    assert L.rht_inverse(p, 100, 10, 0, nul, nul) == -1
+    assert L.thc_chunk_absmax(p, F32, 100, 10, 0, nul, nul) == -1
+    assert L.thc_scale_reduce(nul, 4, 10, p, nul) == -1
+    assert L.thc_encode(p, F32, 100, 10, 0, 0, 4, nul, nul, nul, nul) == -1
+    assert L.thc_aggregate(ctypes.cast(nul, ctypes.POINTER(ctypes.c_void_p)), 1, 100, 10, 4, p, nul) == -1
+    arr0 = (ctypes.c_void_p * 2)(0x1000, 0)
+    assert L.thc_aggregate(ctypes.cast(arr0, ctypes.POINTER(ctypes.c_void_p)), 2, 100, 10, 4, p, nul) == -1
+    assert L.thc_decode(p, nul, 4, 100, 10, 0, 4, p, nul) == -1
+    # alignment
+    assert L.rht_forward(odd, F32, 100, 10, 0, p, nul) == -8
+    assert L.rht_forward(ctypes.c_void_p(0x1002), F32, 100, 10, 0, p, nul) == -8
+    assert L.rht_forward(odd, BF16, 100, 10, 0, p, nul) == -8
+    assert L.thc_encode(p, F32, 100, 10, 0, 0, 4, nul, ctypes.c_void_p(0x1008), nul, nul) == -8
+    assert L.thc_decode(ctypes.c_void_p(0x1004), p, 4, 100, 10, 0, 4, p, nul) == -8
+    arr1 = (ctypes.c_void_p * 1)(0x1004)
+    assert L.thc_aggregate(ctypes.cast(arr1, ctypes.POINTER(ctypes.c_void_p)), 1, 100, 10, 4, p, nul) == -8
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    import paper_2407_01378_amd.binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()
