@@ -94,7 +94,7 @@ int rht_forward(const void* x, thc_dtype dt, uint64_t n, uint32_t chunk_log2, ui
     a.in = x;
     a.out = y;
     a.in_bf16 = dt == THC_BF16;
-    return finish(thc::launch_generic(Mode::Forward, a, static_cast<hipStream_t>(stream)));
+    return finish(thc::launch_chunks(Mode::Forward, a, static_cast<hipStream_t>(stream)));
 }
 
 int rht_inverse(const float* y, uint64_t n, uint32_t chunk_log2, uint64_t seed, float* x,
@@ -107,7 +107,7 @@ int rht_inverse(const float* y, uint64_t n, uint32_t chunk_log2, uint64_t seed, 
     ChunkArgs a = base_args(n, chunk_log2, seed);
     a.in = y;
     a.out = x;
-    return finish(thc::launch_generic(Mode::Inverse, a, static_cast<hipStream_t>(stream)));
+    return finish(thc::launch_chunks(Mode::Inverse, a, static_cast<hipStream_t>(stream)));
 }
 
 int thc_chunk_absmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2,
@@ -122,7 +122,7 @@ int thc_chunk_absmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_
     a.in = grad;
     a.out = absmax;
     a.in_bf16 = dt == THC_BF16;
-    return finish(thc::launch_generic(Mode::Absmax, a, static_cast<hipStream_t>(stream)));
+    return finish(thc::launch_chunks(Mode::Absmax, a, static_cast<hipStream_t>(stream)));
 }
 
 int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
@@ -157,7 +157,7 @@ int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, 
     a.worker = worker;
     a.bits = bits;
     a.payload_bytes = (a.padded * bits + 7) / 8;
-    return finish(thc::launch_generic(Mode::Encode, a, static_cast<hipStream_t>(stream)));
+    return finish(thc::launch_chunks(Mode::Encode, a, static_cast<hipStream_t>(stream)));
 }
 
 int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
@@ -205,7 +205,7 @@ int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uin
     a.bits = bits;
     a.W = W;
     a.sum_bytes = sum_bytes;
-    return finish(thc::launch_generic(Mode::Decode, a, static_cast<hipStream_t>(stream)));
+    return finish(thc::launch_chunks(Mode::Decode, a, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -1,0 +1,168 @@
+// Tuned kernels for chunk_log2 = 14 (the chunk size of every large workload): one
+// workgroup of 256 threads per chunk, the chunk lives in registers (64 coordinates per
+// thread) and crosses LDS three times (input staging + two re-shuffles), see
+// thc_core14.h.  Used when every pointer is 16-byte aligned; the generic kernels cover
+// everything else with identical results.
+#include "thc_core14.h"
+#include "thc_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace thc {
+namespace k14 {
+namespace {
+
+// One chunk per workgroup, gradient of ONE worker: rotation / range / encode.
+//   BF16   input type;  MODE  Forward | Absmax | Encode;  BITS payload width (Encode)
+template <bool BF16, Mode MODE, int BITS>
+__global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a) {
+    __shared__ Shared sh;
+    constexpr int kUnits = BF16 ? 8 : 16;
+    constexpr int kElem = BF16 ? 2 : 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint64_t p = blockIdx.x;
+    const uint64_t g0 = p << kChunkLog2;
+    const uint64_t left = a.n - g0;
+    const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+
+    Raw<kUnits> raw;
+    load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(a.in) + g0 * kElem, valid, t);
+    fill_sign_table(sh, g0, a.key0, a.key1, t);
+    raw_to_lds<kUnits>(sh, raw, t);
+    __syncthreads();
+    float v[kRegs];
+    lds_to_l1<kUnits, true>(sh, v, t);
+    rotate_l1_to_l3(sh, v, lane, wave);
+
+    if constexpr (MODE == Mode::Forward) {
+        float* y = static_cast<float*>(a.out) + g0;
+#pragma unroll
+        for (int run = 0; run < 4; ++run)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int b = 16 * run + 4 * k;
+                *reinterpret_cast<float4*>(y + run * 4096 + t * 16 + 4 * k) =
+                    make_float4(v[b] * kInvSqrtC, v[b + 1] * kInvSqrtC, v[b + 2] * kInvSqrtC,
+                                v[b + 3] * kInvSqrtC);
+            }
+    } else if constexpr (MODE == Mode::Absmax) {
+        const float m = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
+        if (t == 0) static_cast<float*>(a.out)[p] = m;
+    } else {
+        float s;
+        if (a.scale_in) {
+            s = a.scale_in[p];
+        } else {
+            s = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
+        }
+        if (a.scale_out && t == 0) a.scale_out[p] = s;
+        quantize_store<BITS>(v, s, g0, a.worker, a.key0, a.key1, static_cast<uint8_t*>(a.out), t);
+    }
+}
+
+// Inverse direction, one chunk per workgroup.
+//   SRC 0: rotated fp32 values (rht_inverse);  1: u8 sums;  2: u16 sums (thc_decode)
+template <int SRC>
+__global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
+    __shared__ Shared sh;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint64_t p = blockIdx.x;
+    const uint64_t g0 = p << kChunkLog2;
+    const uint64_t left = a.n - g0;
+    const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    float v[kRegs];
+    fill_sign_table(sh, g0, a.key0, a.key1, t);
+    if constexpr (SRC == 0) {
+        Raw<16> raw;   // y is complete (padded), so every unit exists
+        load_raw<16, 4>(raw, static_cast<const float*>(a.in) + g0, (uint32_t)kChunk, t);
+        raw_to_lds<16>(sh, raw, t);
+        __syncthreads();
+        lds_to_l1<16, false>(sh, v, t);
+    } else {
+        const float s = a.scale_in[p];
+        const float step = (s + s) / (float)((1u << a.bits) - 1u);
+        const float q = step / (float)a.W;
+        if constexpr (SRC == 1) {
+            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint8_t*>(a.in) + g0) + 4 * t;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint4 w = src[k];
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        v[16 * k + 4 * d + b] = (float)((ww[d] >> (8 * b)) & 0xFFu) * q - s;
+            }
+        } else {
+            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.in) + g0) + 8 * t;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint4 w = src[k];
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        v[8 * k + 2 * d + b] = (float)((ww[d] >> (16 * b)) & 0xFFFFu) * q - s;
+            }
+        }
+    }
+    rotate_l1_to_l3(sh, v, lane, wave);
+    store_signed_l3(sh, v, static_cast<float*>(a.out) + g0, valid, t);
+}
+
+template <bool BF16, Mode MODE>
+hipError_t launch_bits(const ChunkArgs& a, dim3 grid, hipStream_t stream) {
+    if constexpr (MODE == Mode::Encode) {
+        if (a.bits == 2)
+            hipLaunchKernelGGL((per_worker_kernel<BF16, MODE, 2>), grid, dim3(kThreads), 0, stream, a);
+        else if (a.bits == 4)
+            hipLaunchKernelGGL((per_worker_kernel<BF16, MODE, 4>), grid, dim3(kThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL((per_worker_kernel<BF16, MODE, 8>), grid, dim3(kThreads), 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((per_worker_kernel<BF16, MODE, 4>), grid, dim3(kThreads), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+}  // namespace k14
+
+bool fast14_applicable(Mode mode, const ChunkArgs& a) {
+    if (a.chunk_log2 != 14) return false;
+    if ((a.padded >> 14) > 0x7FFFFFFFull) return false;
+    return k14::aligned16(a.in) && k14::aligned16(a.out);
+}
+
+hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
+    using namespace k14;
+    const dim3 grid((uint32_t)(a.padded >> 14));
+    if (grid.x == 0) return hipSuccess;
+    switch (mode) {
+        case Mode::Forward:
+            return a.in_bf16 ? launch_bits<true, Mode::Forward>(a, grid, stream)
+                             : launch_bits<false, Mode::Forward>(a, grid, stream);
+        case Mode::Absmax:
+            return a.in_bf16 ? launch_bits<true, Mode::Absmax>(a, grid, stream)
+                             : launch_bits<false, Mode::Absmax>(a, grid, stream);
+        case Mode::Encode:
+            return a.in_bf16 ? launch_bits<true, Mode::Encode>(a, grid, stream)
+                             : launch_bits<false, Mode::Encode>(a, grid, stream);
+        case Mode::Inverse:
+            hipLaunchKernelGGL(inverse_kernel<0>, grid, dim3(kThreads), 0, stream, a);
+            return hipGetLastError();
+        case Mode::Decode:
+            if (a.sum_bytes == 1)
+                hipLaunchKernelGGL(inverse_kernel<1>, grid, dim3(kThreads), 0, stream, a);
+            else
+                hipLaunchKernelGGL(inverse_kernel<2>, grid, dim3(kThreads), 0, stream, a);
+            return hipGetLastError();
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace thc

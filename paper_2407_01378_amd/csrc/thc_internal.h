@@ -32,6 +32,16 @@ struct ChunkArgs {
 // Generic path: any chunk_log2 in [1, 14], any alignment the ABI allows.
 hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream);
 
+// Tuned path for chunk_log2 == 14 and 16-byte aligned buffers; same results.
+bool fast14_applicable(Mode mode, const ChunkArgs& a);
+hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream);
+
+// Picks the tuned kernels when they apply, the generic ones otherwise.
+inline hipError_t launch_chunks(Mode mode, const ChunkArgs& a, hipStream_t stream) {
+    return fast14_applicable(mode, a) ? launch_fast14(mode, a, stream)
+                                      : launch_generic(mode, a, stream);
+}
+
 constexpr int kMaxAggBatch = 16;
 struct PayloadBatch {
     const uint8_t* p[kMaxAggBatch];
