@@ -2,12 +2,18 @@
 """Benchmark of the whole hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt_1p3b] [--bits B]
+                    [--unfused]
 
-One step = absmax, shared scale, encode (all W workers), aggregate and decode of
-every bucket of the workload, inputs resident in HBM.  Prints ONE JSON line with
-the gradient throughput (bytes of worker gradients consumed per second), the
-roofline of the dominant kernel (algorithmic bytes / measured launch duration
-against 8 TB/s) and the CPU oracle timed on a bounded slice of the same inputs.
+One step = every bucket of the workload through the whole path, inputs resident in
+HBM: rotation, shared per-chunk scale, stochastic rounding + packing of all W
+workers (thc_encode_all), then integer aggregation, dequantization and inverse
+rotation (thc_aggregate_decode).  --unfused times the one-call-per-step form
+(thc_chunk_absmax, thc_scale_reduce, thc_encode, thc_aggregate, thc_decode) instead.
+
+Prints ONE JSON line: gradient throughput (bytes of worker gradients consumed per
+second), the roofline of the dominant kernel (algorithmic bytes per launch / measured
+launch duration against 8 TB/s) and the CPU oracle timed on a bounded slice of the
+same inputs.
 """
 import argparse
 import json
@@ -29,6 +35,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt_1p3b")
     ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=23,
                     help="coordinates per worker of the slice the CPU oracle is timed on (log2)")
@@ -38,28 +45,48 @@ def parse():
 class Path:
     """Buffers and launch sequence of the path for one workload."""
 
-    def __init__(self, thc, torch, wl, bits, xs, seed=0):
-        self.thc, self.torch, self.wl, self.bits, self.xs, self.seed = thc, torch, wl, bits, xs, seed
+    def __init__(self, thc, torch, wl, bits, xs, seed=0, fused=True):
+        self.thc, self.wl, self.bits, self.fused = thc, wl, bits, fused
         dev = xs[0].device
         self.W, self.l = wl.W, wl.chunk_log2
-        self.buckets = wl.buckets()
         W, l = self.W, self.l
         self.items = []
-        sb = thc.thc_sum_bytes(W, bits)
-        self.sum_bytes = sb
-        sum_dt = torch.uint8 if sb == 1 else torch.int16
-        for k, (st, ln) in enumerate(self.buckets):
+        self.sum_bytes = thc.thc_sum_bytes(W, bits)
+        sum_dt = torch.uint8 if self.sum_bytes == 1 else torch.int16
+        self.no_sums = fused and thc.thc_aggregate_decode_is_fused(W, l, bits)
+        for k, (st, ln) in enumerate(wl.buckets()):
             P = thc.thc_num_chunks(ln, l)
             nb = thc.thc_payload_bytes(ln, l, bits)
-            self.items.append(dict(
-                st=st, ln=ln, P=P, seed=seed + k,
-                grads=[x[st:st + ln] for x in xs],
-                absmax=torch.empty(W * P, dtype=torch.float32, device=dev),
-                scale=torch.empty(P, dtype=torch.float32, device=dev),
-                payloads=[torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(W)],
-                sums=torch.empty(P << l, dtype=sum_dt, device=dev),
-                out=torch.empty(ln, dtype=torch.float32, device=dev)))
+            it = dict(st=st, ln=ln, P=P, seed=seed + k,
+                      grads=[x[st:st + ln] for x in xs],
+                      scale=torch.empty(P, dtype=torch.float32, device=dev),
+                      payloads=[torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(W)],
+                      out=torch.empty(ln, dtype=torch.float32, device=dev))
+            if fused:
+                it["ws"] = torch.empty(thc.thc_encode_all_workspace_bytes(W, ln, l),
+                                       dtype=torch.uint8, device=dev)
+            else:
+                it["absmax"] = torch.empty(W * P, dtype=torch.float32, device=dev)
+            it["sums"] = None if self.no_sums else torch.empty(P << l, dtype=sum_dt, device=dev)
+            self.items.append(it)
+        if fused:
+            self.phases = {"encode_all": (self.encode_all, 1), "aggregate_decode": (self.aggregate_decode, 1)}
+            self.dominant = "encode_all"
+        else:
+            self.phases = {"absmax": (self.absmax, W), "encode": (self.encode, W),
+                           "aggregate": (self.aggregate, 1), "decode": (self.decode, 1)}
+            self.dominant = "encode"
 
+    # fused form
+    def encode_all(self, it):
+        self.thc.thc_encode_all(it["grads"], self.l, it["seed"], self.bits, it["payloads"],
+                                it["scale"], it["ws"])
+
+    def aggregate_decode(self, it):
+        self.thc.thc_aggregate_decode(it["payloads"], it["scale"], it["ln"], self.l, it["seed"],
+                                      self.bits, it["sums"], it["out"])
+
+    # one call per step of the method
     def absmax(self, it):
         for w in range(self.W):
             self.thc.thc_chunk_absmax(it["grads"][w], self.l, it["seed"],
@@ -80,14 +107,16 @@ class Path:
 
     def step(self):
         for it in self.items:
-            self.absmax(it)
-            self.encode(it)
-            self.aggregate(it)
-            self.decode(it)
+            for fn, _ in self.phases.values():
+                fn(it)
+
+    def timed_out(self):
+        return self.fused and any(self.thc.thc_encode_all_timed_out(it["ws"]) for it in self.items)
 
 
 def time_region(torch, fn, reps):
-    """Milliseconds per repetition of fn(), HIP events on the current stream."""
+    """Milliseconds per repetition of fn(): HIP events recorded on the stream the
+    kernels are launched on (torch's current stream)."""
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -112,21 +141,22 @@ def cpu_baseline(wl, bits, xs, log2_sample):
     O.pipeline(hx, wl.chunk_log2, 0, bits, dtype=np.float32, bf16=(wl.dtype == "bf16"))
     dt = time.perf_counter() - t0
     s_in = 2 if wl.dtype == "bf16" else 4
-    return dict(value=wl.W * m * s_in / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
+    return dict(value=round(wl.W * m * s_in / dt / 1e9, 5), unit="GB/s", cores=1, kind="oracle",
                 sample=f"first 2^{log2_sample} coordinates of each of the {wl.W} workers "
                        f"({dt:.1f} s of NumPy, one thread)")
 
 
-def read_traffic(workload_name, bits):
-    """HBM bytes per launch of the dominant kernel, measured offline with rocprofv3
-    --pmc (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
+def read_traffic(workload_name, bits, kernel):
+    """HBM bytes per launch of a kernel, measured offline with rocprofv3 --pmc
+    (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
     `<workload> <bits> <kernel> <bytes_per_launch>`."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
         f = line.split()
-        if len(f) >= 4 and not line.startswith("#") and f[0] == workload_name and f[1] == str(bits):
+        if (len(f) >= 4 and not line.startswith("#") and f[0] == workload_name
+                and f[1] == str(bits) and f[2] == kernel):
             return float(f[3])
     return None
 
@@ -148,51 +178,54 @@ def main():
     wl = workload(a.workload)
     bits = a.bits if a.bits is not None else wl.bits[0]
     s_in = 2 if wl.dtype == "bf16" else 4
+    W = wl.W
 
-    xs = [generate(wl, w, dev) for w in range(wl.W)]
-    path = Path(thc, torch, wl, bits, xs)
+    xs = [generate(wl, w, dev) for w in range(W)]
+    path = Path(thc, torch, wl, bits, xs, fused=not a.unfused)
     torch.cuda.synchronize()
 
     for _ in range(a.warmup):
         path.step()
     ms = time_region(torch, path.step, a.steps)
+    assert not path.timed_out(), "a bounded wait inside thc_encode_all expired"
 
     # per-kernel launch durations, live, on the same stream
-    def all_items(fn):
-        def run():
+    kernels = {}
+    nb = len(path.items)
+    for name, (fn, per_bucket) in path.phases.items():
+        def run(fn=fn):
             for it in path.items:
                 fn(it)
-        return run
-    kernels = {}
-    launches = {"absmax": wl.W * len(path.items), "encode": wl.W * len(path.items),
-                "aggregate": len(path.items), "decode": len(path.items)}
-    for name, fn in (("absmax", path.absmax), ("encode", path.encode),
-                     ("aggregate", path.aggregate), ("decode", path.decode)):
-        t = time_region(torch, all_items(fn), max(2, a.steps // 2))
-        kernels[name] = dict(ms_per_step=round(t, 4), us_per_launch=round(1e3 * t / launches[name], 3))
+        t = time_region(torch, run, max(2, a.steps // 2))
+        kernels[name] = dict(ms_per_step=round(t, 4), launches_per_step=nb * per_bucket,
+                             us_per_launch=round(1e3 * t / (nb * per_bucket), 3))
 
-    # dominant kernel: thc_encode (W launches per bucket).  Algorithmic bytes per
-    # worker-coordinate: the gradient read once + its payload written once.
-    n_total = wl.n
-    enc_bytes_per_launch = (n_total / len(path.items)) * (s_in + bits / 8.0)
-    enc_s = kernels["encode"]["us_per_launch"] * 1e-6
-    achieved = enc_bytes_per_launch / enc_s / 1e9
-    traffic = read_traffic(wl.name, bits)
+    # Dominant kernel and its algorithmic bytes per launch.  Per worker-coordinate the
+    # encode step must read the gradient once and write its payload once.
+    coords_per_launch = wl.n / nb
+    if path.fused:
+        dom_bytes = coords_per_launch * W * (s_in + bits / 8.0)
+        dom_name = "thc_encode_all"
+    else:
+        dom_bytes = coords_per_launch * (s_in + bits / 8.0)
+        dom_name = "thc_encode"
+    dom_s = kernels[path.dominant]["us_per_launch"] * 1e-6
+    achieved = dom_bytes / dom_s / 1e9
 
     sb = path.sum_bytes
-    alg_bytes_per_coord = wl.W * (s_in + bits / 8.0) + wl.W * bits / 8.0 + 2 * sb + 4
-    value = wl.W * wl.n * s_in / (ms * 1e-3) / 1e9
+    alg_bytes_per_coord = W * (s_in + bits / 8.0) + W * bits / 8.0 + 2 * sb + 4
+    value = W * wl.n * s_in / (ms * 1e-3) / 1e9
     res = {
         "metric": "gradient GB/s for encode+aggregate+decode (W workers), 1 GPU",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "W": wl.W, "n": wl.n, "input": wl.dtype, "bits": bits,
-                   "chunk_log2": wl.chunk_log2, "buckets": len(path.items),
-                   "bucket_elems": wl.bucket or wl.n},
-        "roofline": {"bound": "hbm", "kernel": "thc_encode", "achieved": round(achieved, 1),
+        "config": {"workload": wl.name, "W": W, "n": wl.n, "input": wl.dtype, "bits": bits,
+                   "chunk_log2": wl.chunk_log2, "buckets": nb, "bucket_elems": wl.bucket or wl.n,
+                   "form": "fused" if path.fused else "unfused"},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic},
+                     "traffic": read_traffic(wl.name, bits, dom_name)},
         "pipeline_hbm": {"algorithmic_bytes_per_coord": alg_bytes_per_coord,
                          "achieved_GBps": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},

@@ -138,6 +138,46 @@ int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32
 int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uint32_t chunk_log2,
                uint64_t seed, uint32_t bits, float* out, void* stream);
 
+/* ---- batched / fused entry points -------------------------------------------------
+ * Same mathematics as the calls above and byte-identical payloads, scales, sums and
+ * outputs; they exist because the path is bandwidth-bound and these forms read each
+ * gradient once and never store the integer sums. */
+
+/* Bytes of zero-initialisation-free scratch thc_encode_all needs for W workers of n
+ * coordinates (the call clears what it uses).  0 on bad arguments. */
+uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2);
+
+/* Encode all W workers in one pass: per chunk, rotate every worker's gradient, agree
+ * on the shared scale (max over workers of the per-chunk range: the steps
+ * thc_chunk_absmax + thc_scale_reduce), quantize onto it and pack (thc_encode).
+ *   grads      HOST array of W device pointers, n values of dtype dt each
+ *   payloads   HOST array of W device pointers, thc_payload_bytes each
+ *   scale      chunks fp32, receives the shared scale
+ *   workspace  device scratch of at least thc_encode_all_workspace_bytes bytes, 16-byte
+ *              aligned.  Its first 32-bit word is 0 after a good run and 1 if a bounded
+ *              wait between workgroups expired (the payloads are then invalid); check it
+ *              after synchronising the stream.
+ * Calls that share a workspace must not overlap in time. */
+int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                   float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Upper bound on the polls of one inter-workgroup wait inside thc_encode_all (default
+ * 2^22, about seconds).  A tuning and test knob: with a tiny limit the waits expire, the
+ * error word is set and every wave still exits. */
+void thc_set_spin_limit(uint32_t polls);
+
+/* 1 if thc_aggregate_decode can run fused for this shape, in which case `sums` may be
+ * NULL; 0 if it will fall back to thc_aggregate + thc_decode and needs `sums`. */
+int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits);
+
+/* thc_aggregate followed by thc_decode.
+ *   sums   as for thc_aggregate; when the fused form applies it may be NULL and the
+ *          integer sums are then never stored */
+int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float* scale,
+                         uint64_t n, uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                         void* sums, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

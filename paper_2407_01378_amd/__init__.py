@@ -15,6 +15,12 @@ from .binding import (  # noqa: F401
     rht_inverse,
     status_string,
     thc_aggregate,
+    thc_aggregate_decode,
+    thc_aggregate_decode_is_fused,
+    thc_encode_all,
+    thc_encode_all_timed_out,
+    thc_encode_all_workspace_bytes,
+    thc_set_spin_limit,
     thc_chunk_absmax,
     thc_decode,
     thc_encode,

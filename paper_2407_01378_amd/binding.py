@@ -44,6 +44,19 @@ _SIGNATURES = {
     "thc_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
                                   ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                   ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_encode_all_workspace_bytes": (ctypes.c_uint64, [ctypes.c_uint32, ctypes.c_uint64,
+                                                         ctypes.c_uint32]),
+    "thc_encode_all": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_void_p]),
+    "thc_set_spin_limit": (None, [ctypes.c_uint32]),
+    "thc_aggregate_decode_is_fused": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint32,
+                                                     ctypes.c_uint32]),
+    "thc_aggregate_decode": (ctypes.c_int, [_u8pp, ctypes.c_uint32, ctypes.c_void_p,
+                                            ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                            ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p]),
 }
 
 
@@ -179,4 +192,52 @@ def thc_decode(sums, scale, W, n, chunk_log2, seed, bits, out, stream=None):
     _flat(out, torch.float32)
     _check(lib().thc_decode(_ptr(sums), _ptr(scale), W, n, chunk_log2, seed, bits, _ptr(out),
                             _stream(stream)), "thc_decode")
+    return out
+
+
+# ------------------------------------------------------------- batched / fused forms
+def _ptr_array(tensors):
+    arr = (ctypes.c_void_p * max(len(tensors), 1))(*[t.data_ptr() for t in tensors])
+    return arr, ctypes.cast(arr, _u8pp)
+
+
+def thc_encode_all_workspace_bytes(W, n, chunk_log2):
+    return lib().thc_encode_all_workspace_bytes(W, n, chunk_log2)
+
+
+def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+    W = len(grads)
+    n = grads[0].numel()
+    for g in grads:
+        _flat(g)
+        if g.numel() != n or g.dtype != grads[0].dtype:
+            raise ValueError("all workers must have gradients of one size and dtype")
+    keep_g, pg = _ptr_array(grads)
+    keep_p, pp = _ptr_array(payloads)
+    _check(lib().thc_encode_all(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
+                                _ptr(scale), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)),
+           "thc_encode_all")
+    return payloads
+
+
+def thc_encode_all_timed_out(workspace):
+    """Reads the workspace's error word (synchronises): True if a bounded wait expired."""
+    return bool(workspace.view(torch.uint8)[:4].cpu().numpy().view("<u4")[0])
+
+
+def thc_set_spin_limit(polls):
+    lib().thc_set_spin_limit(polls)
+
+
+def thc_aggregate_decode_is_fused(W, chunk_log2, bits):
+    return bool(lib().thc_aggregate_decode_is_fused(W, chunk_log2, bits))
+
+
+def thc_aggregate_decode(payloads, scale, n, chunk_log2, seed, bits, sums, out, stream=None):
+    W = len(payloads)
+    keep_p, pp = _ptr_array(payloads)
+    _flat(out, torch.float32)
+    _check(lib().thc_aggregate_decode(pp, W, _ptr(scale), n, chunk_log2, seed, bits, _ptr(sums),
+                                      _ptr(out), _stream(stream)), "thc_aggregate_decode")
     return out

@@ -176,6 +176,12 @@ int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32
     if (!aligned(sums, 16)) return THC_ERR_ALIGN;
     const uint64_t padded = padded_coords(n, chunk_log2);
     const uint64_t payload_bytes = (padded * bits + 7) / 8;
+    if (thc::aggregate_fast_applicable(W, bits, sum_bytes, payload_bytes)) {
+        thc::FusedPayloadPtrs ptrs{};
+        for (uint32_t w = 0; w < W; ++w) ptrs.p[w] = payloads[w];
+        return finish(thc::launch_aggregate_fast(ptrs, W, bits, payload_bytes, sums,
+                                                 static_cast<hipStream_t>(stream)));
+    }
     for (uint32_t w0 = 0; w0 < W; w0 += thc::kMaxAggBatch) {
         thc::PayloadBatch batch{};
         const uint32_t count = (W - w0 < (uint32_t)thc::kMaxAggBatch) ? W - w0 : thc::kMaxAggBatch;
@@ -206,6 +212,112 @@ int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uin
     a.W = W;
     a.sum_bytes = sum_bytes;
     return finish(thc::launch_chunks(Mode::Decode, a, static_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------- batched / fused forms
+static uint32_t g_spin_limit = 1u << 22;
+
+void thc_set_spin_limit(uint32_t polls) { g_spin_limit = polls; }
+
+uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2) {
+    if (W == 0 || check_common(n, chunk_log2) != THC_OK) return 0;
+    const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+    // error word (padded to 16 bytes) + 4 W words per chunk (one per wave of every
+    // worker's workgroup; the unfused fallback keeps its per-worker ranges there too)
+    return 16 + 16 * (uint64_t)W * chunks;
+}
+
+int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                   float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!grads || !payloads || !scale || !workspace) return THC_ERR_NULL;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!grads[w] || !payloads[w]) return THC_ERR_NULL;
+        if (!aligned(grads[w], dt == THC_F32 ? 4 : 2) || !aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+    }
+    if (!aligned(scale, 4) || !aligned(workspace, 16)) return THC_ERR_ALIGN;
+    if (workspace_bytes < thc_encode_all_workspace_bytes(W, n, chunk_log2)) return THC_ERR_SIZE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+    uint32_t* words = static_cast<uint32_t*>(workspace);
+
+    thc::EncodeAllArgs a{};
+    a.n = n;
+    a.chunks = chunks;
+    a.W = W;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.max_spins = g_spin_limit;
+    a.scale = scale;
+    a.error = words;
+    a.slots = words + 4;
+    if (W <= (uint32_t)thc::kMaxFusedWorkers) {
+        thc::FusedWorkerPtrs ptrs{};
+        for (uint32_t w = 0; w < W; ++w) {
+            ptrs.grad[w] = grads[w];
+            ptrs.payload[w] = payloads[w];
+        }
+        if (thc::encode_all_fused_applicable(a, ptrs, chunk_log2)) {
+            if (thc::launch_zero_words(words, 4 + 4 * (uint64_t)W * chunks, st) != hipSuccess) return THC_ERR_HIP;
+            return finish(thc::launch_encode_all_fused(a, ptrs, dt == THC_BF16, bits, st));
+        }
+    }
+    // Fallback: the unfused sequence, per-worker ranges kept in the workspace.
+    if (thc::launch_zero_words(words, 4, st) != hipSuccess) return THC_ERR_HIP;
+    float* absmax_all = reinterpret_cast<float*>(words + 4);
+    for (uint32_t w = 0; w < W; ++w) {
+        rc = thc_chunk_absmax(grads[w], dt, n, chunk_log2, seed, absmax_all + (uint64_t)w * chunks, stream);
+        if (rc != THC_OK) return rc;
+    }
+    rc = thc_scale_reduce(absmax_all, W, chunks, scale, stream);
+    for (uint32_t w = 0; rc == THC_OK && w < W; ++w)
+        rc = thc_encode(grads[w], dt, n, chunk_log2, seed, w, bits, scale, payloads[w], nullptr, stream);
+    return rc;
+}
+
+int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
+    if (check_bits(bits) != THC_OK || thc_sum_bytes(W, bits) == 0) return 0;
+    return thc::aggregate_decode_fused_applicable(W, chunk_log2, bits) ? 1 : 0;
+}
+
+int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float* scale,
+                         uint64_t n, uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                         void* sums, float* out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!payloads || !scale || !out) return THC_ERR_NULL;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!payloads[w]) return THC_ERR_NULL;
+        if (!aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+    }
+    if (!aligned(scale, 4) || !aligned(out, 4) || !aligned(sums, 16)) return THC_ERR_ALIGN;
+    if (thc::aggregate_decode_fused_applicable(W, chunk_log2, bits) && aligned(out, 16)) {
+        thc::FusedPayloadPtrs ptrs{};
+        for (uint32_t w = 0; w < W; ++w) ptrs.p[w] = payloads[w];
+        thc::AggDecodeArgs a{};
+        a.n = n;
+        a.chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+        a.W = W;
+        a.key0 = (uint32_t)seed;
+        a.key1 = (uint32_t)(seed >> 32);
+        a.scale = scale;
+        a.sums = sums;
+        a.out = out;
+        return finish(thc::launch_aggregate_decode_fused(a, ptrs, bits, static_cast<hipStream_t>(stream)));
+    }
+    if (!sums) return THC_ERR_NULL;
+    rc = thc_aggregate(payloads, W, n, chunk_log2, bits, sums, stream);
+    if (rc != THC_OK) return rc;
+    return thc_decode(sums, scale, W, n, chunk_log2, seed, bits, out, stream);
 }
 
 }  // extern "C"

@@ -1,0 +1,414 @@
+// Fused kernels for chunk_log2 = 14.
+//
+// encode_all: ONE pass over every worker's gradient.  A work item is (chunk p, worker
+// w); the workgroup that owns it rotates the chunk, publishes the chunk's largest
+// magnitude to a per-chunk slot in global memory, waits until all W workers of chunk p
+// have published, and only then quantizes - the rotated chunk never leaves registers,
+// so each gradient is read from HBM once.  The grid is persistent and no larger than
+// what is resident at once (occupancy x CUs), items are dealt round-robin
+// (item = workgroup + k * grid), so the W owners of a chunk run side by side and every
+// wait is for a workgroup that is already running.  Waits are bounded: on time-out an
+// error word is set and the wave carries on, so every wave always exits.
+//
+// aggregate_decode: sums the W payloads of a chunk in packed sub-word lanes straight
+// into the inverse rotation; the integer sums never touch HBM unless asked for.
+#include "thc_core14.h"
+#include "thc_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace thc {
+namespace k14 {
+namespace {
+
+// ------------------------------------------------------------------ encode_all
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(kThreads, 2) void encode_all_kernel(const EncodeAllArgs a,
+                                                              const FusedWorkerPtrs ptrs) {
+    __shared__ Shared sh;
+    constexpr int kUnits = BF16 ? 8 : 16;
+    constexpr int kElem = BF16 ? 2 : 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t total = (uint32_t)a.chunks * a.W;
+    const uint32_t G = gridDim.x;
+    uint32_t item = blockIdx.x;
+    if (item >= total) return;
+
+    auto chunk_valid = [&](uint32_t p) -> uint32_t {
+        const uint64_t left = a.n - ((uint64_t)p << kChunkLog2);
+        return left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    };
+    uint32_t p = item / a.W, w = item - p * a.W;
+    Raw<kUnits> raw;
+    load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + ((uint64_t)p << kChunkLog2) * kElem,
+                            chunk_valid(p), t);
+    for (;;) {
+        const uint64_t g0 = (uint64_t)p << kChunkLog2;
+        fill_sign_table(sh, g0, a.key0, a.key1, t);
+        raw_to_lds<kUnits>(sh, raw, t);
+        __syncthreads();
+        float v[kRegs];
+        lds_to_l1<kUnits, true>(sh, v, t);
+
+        // prefetch the next item of this workgroup while this one is rotated
+        const uint32_t next = item + G;
+        const bool has_next = next < total;
+        uint32_t p2 = 0, w2 = 0;
+        if (has_next) {
+            p2 = next / a.W;
+            w2 = next - p2 * a.W;
+            load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w2]) + ((uint64_t)p2 << kChunkLog2) * kElem,
+                                    chunk_valid(p2), t);
+        }
+        rotate_l1_to_l3(sh, v, lane, wave);
+
+        // this wave's share of the chunk's range
+        float m = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kRegs; i += 2) m = fmaxf(m, fmaxf(fabsf(v[i]), fabsf(v[i + 1])));
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        m = m * kInvSqrtC;
+
+        // Publish: one word per wave, value | valid bit (non-negative floats order like
+        // their bit patterns and leave bit 31 free).  The words travel between workgroups
+        // only through device-scope stores and loads, which are served at the memory
+        // side, so no cache write-back or invalidate is needed.  The slots start zeroed.
+        const uint32_t nwords = 4u * a.W;   // four waves per workgroup, W workgroups per chunk
+        uint32_t* slot = a.slots + (uint64_t)p * nwords;
+        if (lane == 0)
+            __hip_atomic_store(&slot[4u * w + wave], __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        // Wait until every wave of every worker of this chunk has published, then take
+        // the largest value.  Bounded: on time-out flag the error word and carry on.
+        uint32_t sbits = 0u;
+        for (uint32_t spins = 0;; ++spins) {
+            uint32_t all_valid = 0x80000000u, mx = 0u;
+            for (uint32_t base = 0; base < nwords; base += 64u) {
+                const uint32_t i = base + lane;
+                const uint32_t val = i < nwords ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                                : 0x80000000u;
+                all_valid &= val;
+                const uint32_t mag = val & 0x7FFFFFFFu;
+                mx = mag > mx ? mag : mx;
+            }
+            const bool done = __all(all_valid != 0u);
+            if (done || spins >= a.max_spins) {
+                if (!done && lane == 0)
+                    __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) {
+                    const uint32_t other = __shfl_xor(mx, o, 64);
+                    mx = other > mx ? other : mx;
+                }
+                sbits = mx;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        const float s = __uint_as_float(sbits);
+        if (w == 0 && t == 0) a.scale[p] = s;
+        quantize_store<BITS>(v, s, g0, w, a.key0, a.key1, ptrs.payload[w], t);
+
+        if (!has_next) break;
+        item = next;
+        p = p2;
+        w = w2;
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* dst, uint64_t words) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) dst[i] = 0u;
+}
+
+// ------------------------------------------------------------- aggregate_decode
+// One chunk per work item, persistent grid.  Thread t owns coordinates 64 t .. 64 t + 63
+// (layout L1): 8 * BITS payload bytes per worker.
+template <int BITS>
+__global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const AggDecodeArgs a,
+                                                                    const FusedPayloadPtrs ptrs) {
+    __shared__ Shared sh;
+    constexpr int kVec = BITS / 2;            // uint4 loads per worker per thread
+    constexpr int kWords = 4 * kVec;          // payload dwords per worker per thread
+    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;   // sub-word accumulators per dword
+    constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const float Lf = (float)((1u << BITS) - 1u);
+    const float Wf = (float)a.W;
+
+    for (uint64_t p = blockIdx.x; p < a.chunks; p += gridDim.x) {
+        const uint64_t g0 = p << kChunkLog2;
+        const uint64_t left = a.n - g0;
+        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        fill_sign_table(sh, g0, a.key0, a.key1, t);
+
+        uint32_t acc[kWords][kLanes];
+#pragma unroll
+        for (int d = 0; d < kWords; ++d)
+#pragma unroll
+            for (int k = 0; k < kLanes; ++k) acc[d][k] = 0u;
+        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (8u * BITS);
+        for (uint32_t w0 = 0; w0 < a.W; w0 += 4) {
+            uint4 x[4][kVec];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j < a.W) {
+                    const uint4* src = reinterpret_cast<const uint4*>(ptrs.p[w0 + j] + byte0);
+#pragma unroll
+                    for (int k = 0; k < kVec; ++k) x[j][k] = src[k];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j < a.W) {
+#pragma unroll
+                    for (int k = 0; k < kVec; ++k) {
+                        const uint32_t ww[4] = {x[j][k].x, x[j][k].y, x[j][k].z, x[j][k].w};
+#pragma unroll
+                        for (int d = 0; d < 4; ++d)
+#pragma unroll
+                            for (int q = 0; q < kLanes; ++q)
+                                acc[4 * k + d][q] += (ww[d] >> (BITS * q)) & kMask;
+                    }
+                }
+            }
+        }
+
+        // sums -> rotated-domain estimate of the mean, layout L1
+        const float s = a.scale[p];
+        const float step = (s + s) / Lf;
+        const float qf = step / Wf;
+        float v[kRegs];
+        uint32_t S[kRegs];
+#pragma unroll
+        for (int d = 0; d < kWords; ++d) {
+            if (BITS == 8) {         // dword d: coordinates 4d..4d+3; lane 0 = even, lane 1 = odd
+                S[4 * d + 0] = acc[d][0] & 0xFFFFu;
+                S[4 * d + 1] = acc[d][1] & 0xFFFFu;
+                S[4 * d + 2] = acc[d][0] >> 16;
+                S[4 * d + 3] = acc[d][1] >> 16;
+            } else {                 // dword d: 32/BITS coordinates; lane q byte b = coordinate (8/BITS) b + q
+                constexpr int per = 32 / BITS;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int q = 0; q < kLanes; ++q)
+                        S[per * d + kLanes * b + q] = (acc[d][q] >> (8 * b)) & 0xFFu;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRegs; ++r) v[r] = (float)S[r] * qf - s;
+
+        if (a.sums) {   // the caller also wants the integer aggregate
+            if (BITS == 8) {
+                uint16_t* dst = static_cast<uint16_t*>(a.sums) + g0 + 64u * t;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    *reinterpret_cast<uint4*>(dst + 8 * k) =
+                        make_uint4(S[8 * k] | (S[8 * k + 1] << 16), S[8 * k + 2] | (S[8 * k + 3] << 16),
+                                   S[8 * k + 4] | (S[8 * k + 5] << 16), S[8 * k + 6] | (S[8 * k + 7] << 16));
+            } else {
+                uint8_t* dst = static_cast<uint8_t*>(a.sums) + g0 + 64u * t;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t o[4];
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const int r = 16 * k + 4 * d;
+                        o[d] = S[r] | (S[r + 1] << 8) | (S[r + 2] << 16) | (S[r + 3] << 24);
+                    }
+                    *reinterpret_cast<uint4*>(dst + 16 * k) = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            }
+        }
+        rotate_l1_to_l3(sh, v, lane, wave);
+        store_signed_l3(sh, v, a.out + g0, valid, t);
+        __syncthreads();   // the sign table is rewritten by the next item
+    }
+}
+
+// ------------------------------------------------------------------ aggregate only
+// Streaming sum of W payloads: each thread owns 16 payload bytes per worker.
+template <int BITS, typename SumT>
+__global__ __launch_bounds__(256) void aggregate_fast_kernel(const FusedPayloadPtrs ptrs, uint32_t W,
+                                                             uint64_t vecs, SumT* sums) {
+    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;
+    constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    constexpr int kCoords = 128 / BITS;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs;
+         i += (uint64_t)gridDim.x * blockDim.x) {
+        uint32_t acc[4][kLanes];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int q = 0; q < kLanes; ++q) acc[d][q] = 0u;
+        for (uint32_t w0 = 0; w0 < W; w0 += 8) {
+            uint4 x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (w0 + j < W) x[j] = reinterpret_cast<const uint4*>(ptrs.p[w0 + j])[i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (w0 + j < W) {
+                    const uint32_t ww[4] = {x[j].x, x[j].y, x[j].z, x[j].w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+#pragma unroll
+                        for (int q = 0; q < kLanes; ++q) acc[d][q] += (ww[d] >> (BITS * q)) & kMask;
+                }
+        }
+        SumT* dst = sums + i * kCoords;
+        if (BITS == 8) {   // u16 sums: (even, odd) pairs
+            uint32_t o[8];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                o[2 * d] = __builtin_amdgcn_perm(acc[d][1], acc[d][0], 0x05040100u);
+                o[2 * d + 1] = __builtin_amdgcn_perm(acc[d][1], acc[d][0], 0x07060302u);
+            }
+            reinterpret_cast<uint4*>(dst)[0] = make_uint4(o[0], o[1], o[2], o[3]);
+            reinterpret_cast<uint4*>(dst)[1] = make_uint4(o[4], o[5], o[6], o[7]);
+        } else if (BITS == 4) {   // u8 sums: lane 0 = even coordinates, lane 1 = odd
+            uint32_t o[8];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                o[2 * d] = __builtin_amdgcn_perm(acc[d][1], acc[d][0], 0x05010400u);
+                o[2 * d + 1] = __builtin_amdgcn_perm(acc[d][1], acc[d][0], 0x07030602u);
+            }
+            reinterpret_cast<uint4*>(dst)[0] = make_uint4(o[0], o[1], o[2], o[3]);
+            reinterpret_cast<uint4*>(dst)[1] = make_uint4(o[4], o[5], o[6], o[7]);
+        } else {                  // 2 bits: lane q byte b = coordinate 4 b + q of the dword's 16
+            uint32_t o[16];
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    uint32_t v = 0u;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v |= ((acc[d][q] >> (8 * b)) & 0xFFu) << (8 * q);
+                    o[4 * d + b] = v;
+                }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                reinterpret_cast<uint4*>(dst)[k] = make_uint4(o[4 * k], o[4 * k + 1], o[4 * k + 2], o[4 * k + 3]);
+        }
+    }
+}
+
+int g_cus = 0;
+int device_cus() {
+    if (g_cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            g_cus = prop.multiProcessorCount;
+    }
+    return g_cus;
+}
+
+template <typename K>
+uint32_t resident_grid(K kernel) {
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, kThreads, 0) != hipSuccess || occ < 1)
+        return 0;
+    const int cus = device_cus();
+    return cus > 0 ? (uint32_t)(occ * cus) : 0;
+}
+
+template <bool BF16, int BITS>
+hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
+    uint32_t G = resident_grid(encode_all_kernel<BF16, BITS>);
+    if (G == 0) return hipErrorInvalidValue;
+    const uint64_t total = a.chunks * a.W;
+    if (G > total) G = (uint32_t)total;
+    if (G > a.W) G -= G % a.W;   // whole chunks per round of the grid
+    hipLaunchKernelGGL((encode_all_kernel<BF16, BITS>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace k14
+
+bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2) {
+    if (chunk_log2 != 14 || a.W > (uint32_t)kMaxFusedWorkers) return false;
+    if (a.chunks * a.W >= 0x7FFFFFFFull) return false;
+    for (uint32_t w = 0; w < a.W; ++w)
+        if ((reinterpret_cast<uintptr_t>(ptrs.grad[w]) & 15u) || (reinterpret_cast<uintptr_t>(ptrs.payload[w]) & 15u))
+            return false;
+    return true;
+}
+
+hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream) {
+    if (words == 0) return hipSuccess;
+    hipLaunchKernelGGL(k14::zero_words_kernel, dim3((uint32_t)((words + 255) / 256)), dim3(256), 0, stream,
+                       dst, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
+                                   uint32_t bits, hipStream_t stream) {
+    using namespace k14;
+    if (bf16) {
+        if (bits == 2) return launch_encode_all_t<true, 2>(a, ptrs, stream);
+        if (bits == 4) return launch_encode_all_t<true, 4>(a, ptrs, stream);
+        return launch_encode_all_t<true, 8>(a, ptrs, stream);
+    }
+    if (bits == 2) return launch_encode_all_t<false, 2>(a, ptrs, stream);
+    if (bits == 4) return launch_encode_all_t<false, 4>(a, ptrs, stream);
+    return launch_encode_all_t<false, 8>(a, ptrs, stream);
+}
+
+bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
+    if (chunk_log2 != 14 || W > (uint32_t)kMaxFusedPayloads) return false;
+    // packed accumulators: 8-bit lanes for 2- and 4-bit payloads, 16-bit lanes for 8-bit
+    const uint32_t top = W * ((1u << bits) - 1u);
+    return bits == 8 ? top <= 65535u : top <= 255u;
+}
+
+hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                         uint32_t bits, hipStream_t stream) {
+    using namespace k14;
+    if (a.chunks == 0) return hipSuccess;
+    uint32_t G = 0;
+    if (bits == 2) G = resident_grid(aggregate_decode_kernel<2>);
+    else if (bits == 4) G = resident_grid(aggregate_decode_kernel<4>);
+    else G = resident_grid(aggregate_decode_kernel<8>);
+    if (G == 0) return hipErrorInvalidValue;
+    if (G > a.chunks) G = (uint32_t)a.chunks;
+    if (bits == 2)
+        hipLaunchKernelGGL(aggregate_decode_kernel<2>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    else if (bits == 4)
+        hipLaunchKernelGGL(aggregate_decode_kernel<4>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    else
+        hipLaunchKernelGGL(aggregate_decode_kernel<8>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    return hipGetLastError();
+}
+
+bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes) {
+    if (W > (uint32_t)kMaxFusedPayloads || (payload_bytes & 15u)) return false;
+    return (bits == 8 && sum_bytes == 2) || (bits != 8 && sum_bytes == 1);
+}
+
+hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
+                                 uint64_t payload_bytes, void* sums, hipStream_t stream) {
+    using namespace k14;
+    const uint64_t vecs = payload_bytes / 16u;
+    if (vecs == 0) return hipSuccess;
+    const int cus = device_cus();
+    uint64_t blocks = (vecs + 255u) / 256u;
+    const uint64_t cap = (uint64_t)(cus > 0 ? cus : 256) * 16u;
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((uint32_t)blocks), block(256);
+    if (bits == 2)
+        hipLaunchKernelGGL((aggregate_fast_kernel<2, uint8_t>), grid, block, 0, stream, ptrs, W, vecs,
+                           static_cast<uint8_t*>(sums));
+    else if (bits == 4)
+        hipLaunchKernelGGL((aggregate_fast_kernel<4, uint8_t>), grid, block, 0, stream, ptrs, W, vecs,
+                           static_cast<uint8_t*>(sums));
+    else
+        hipLaunchKernelGGL((aggregate_fast_kernel<8, uint16_t>), grid, block, 0, stream, ptrs, W, vecs,
+                           static_cast<uint16_t*>(sums));
+    return hipGetLastError();
+}
+
+}  // namespace thc

@@ -42,6 +42,48 @@ inline hipError_t launch_chunks(Mode mode, const ChunkArgs& a, hipStream_t strea
                                       : launch_generic(mode, a, stream);
 }
 
+// ---- fused paths (chunk_log2 == 14) ------------------------------------------------
+constexpr int kMaxFusedWorkers = 64;
+struct FusedWorkerPtrs {
+    const void* grad[kMaxFusedWorkers];
+    uint8_t* payload[kMaxFusedWorkers];
+};
+struct EncodeAllArgs {
+    uint64_t n;
+    uint64_t chunks;
+    uint32_t W;
+    uint32_t key0, key1;
+    uint32_t max_spins;  // bound on the polls of one wait
+    float* scale;        // out: chunks shared scales
+    uint32_t* slots;     // zeroed: chunks x 4W words, one per wave of every worker
+    uint32_t* error;     // zeroed: set to 1 if a wait timed out
+};
+bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs,
+                                 uint32_t chunk_log2);
+hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
+                                   uint32_t bits, hipStream_t stream);
+hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream);
+
+constexpr int kMaxFusedPayloads = 32;
+struct FusedPayloadPtrs {
+    const uint8_t* p[kMaxFusedPayloads];
+};
+struct AggDecodeArgs {
+    uint64_t n;
+    uint64_t chunks;
+    uint32_t W;
+    uint32_t key0, key1;
+    const float* scale;
+    void* sums;  // may be null
+    float* out;
+};
+bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits);
+hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                         uint32_t bits, hipStream_t stream);
+bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes);
+hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
+                                 uint64_t payload_bytes, void* sums, hipStream_t stream);
+
 constexpr int kMaxAggBatch = 16;
 struct PayloadBatch {
     const uint8_t* p[kMaxAggBatch];

@@ -1,0 +1,125 @@
+"""The batched / fused entry points (one-pass thc_encode_all, thc_aggregate_decode)
+against the oracle and against the unfused calls: byte-identical payloads, scales,
+sums and outputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import thc as O
+from synth import generate, workload
+
+from gpu_util import DEV, check_against_oracle, run_path, run_path_fused, sums_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(n, dtype, seed, scale=1e-3):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    x = torch.randn(n, generator=g, device=DEV)
+    x = x / torch.sqrt((torch.randn(3, n, generator=g, device=DEV) ** 2).mean(dim=0))
+    return (x * scale).to(dtype)
+
+
+@pytest.mark.parametrize("l,bits,W,dtype,chunks", [
+    (14, 4, 8, torch.bfloat16, 70), (14, 2, 8, torch.bfloat16, 5), (14, 8, 8, torch.bfloat16, 5),
+    (14, 4, 8, torch.float32, 9), (14, 8, 3, torch.float32, 4), (14, 2, 1, torch.float32, 3),
+    (14, 4, 17, torch.bfloat16, 6), (14, 4, 18, torch.bfloat16, 3), (14, 4, 64, torch.bfloat16, 2),
+    (14, 2, 40, torch.float32, 2), (14, 8, 33, torch.bfloat16, 2),
+    (10, 4, 4, torch.float32, 40), (12, 8, 5, torch.bfloat16, 9), (3, 2, 3, torch.float32, 1000),
+])
+def test_fused_path_matches_oracle_and_unfused(l, bits, W, dtype, chunks):
+    c = 1 << l
+    n = chunks * c + (c // 2 + 1 if c > 2 else 1)
+    print(f"fused l={l} bits={bits} W={W} dtype={dtype} n={n}", flush=True)
+    xs = [_rand(n, dtype, 77 * l + w, scale=10.0 ** (-1 - (w % 4))) for w in range(W)]
+    fused = run_path_fused(xs, l, 13, bits)
+    check_against_oracle(xs, fused, l, 13, bits)
+    plain = run_path(xs, l, 13, bits)
+    assert torch.equal(fused["scale"], plain["scale"])
+    for a, b in zip(fused["payloads"], plain["payloads"]):
+        assert torch.equal(a, b)
+    assert torch.equal(fused["sums"], plain["sums"])
+    assert torch.equal(fused["out"], plain["out"])
+    # sums == NULL is allowed exactly when the fused form applies
+    if thc.thc_aggregate_decode_is_fused(W, l, bits):
+        nosum = run_path_fused(xs, l, 13, bits, keep_sums=False)
+        assert torch.equal(nosum["out"], plain["out"])
+    else:
+        with pytest.raises(thc.ThcError):
+            thc.thc_aggregate_decode(fused["payloads"], fused["scale"], n, l, 13, bits, None,
+                                     torch.empty(n, device=DEV))
+
+
+def test_is_fused_predicate():
+    assert thc.thc_aggregate_decode_is_fused(8, 14, 4)
+    assert thc.thc_aggregate_decode_is_fused(17, 14, 4)
+    assert not thc.thc_aggregate_decode_is_fused(18, 14, 4)
+    assert thc.thc_aggregate_decode_is_fused(8, 14, 8)
+    assert not thc.thc_aggregate_decode_is_fused(8, 10, 4)
+    assert not thc.thc_aggregate_decode_is_fused(33, 14, 2)
+
+
+def test_workspace_is_reusable_and_small_inputs_work():
+    l, bits, W = 14, 4, 8
+    for n in (1, 5000, 1 << 14, (1 << 14) + 1):
+        xs = [_rand(n, torch.bfloat16, 3 + w) for w in range(W)]
+        a = run_path_fused(xs, l, 5, bits)
+        b = run_path(xs, l, 5, bits)
+        assert torch.equal(a["out"], b["out"]) and torch.equal(a["sums"], b["sums"])
+    # same workspace twice in a row, second call smaller
+    n1, n2 = 40 * (1 << 14) + 3, 7 * (1 << 14)
+    ws = torch.empty(thc.thc_encode_all_workspace_bytes(W, n1, l), dtype=torch.uint8, device=DEV)
+    for n in (n1, n2):
+        xs = [_rand(n, torch.bfloat16, 30 + w) for w in range(W)]
+        P = thc.thc_num_chunks(n, l)
+        pay = [torch.empty(thc.thc_payload_bytes(n, l, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
+        sc = torch.empty(P, device=DEV)
+        thc.thc_encode_all(xs, l, 6, bits, pay, sc, ws)
+        torch.cuda.synchronize()
+        assert not thc.thc_encode_all_timed_out(ws)
+        ref = run_path(xs, l, 6, bits)
+        assert torch.equal(sc, ref["scale"])
+        for x, y in zip(pay, ref["payloads"]):
+            assert torch.equal(x, y)
+
+
+def test_expired_wait_sets_the_error_word_and_every_wave_exits():
+    """Failure handling forced from the host: with a poll limit of zero the waits
+    between workgroups give up at once; the kernel must still finish, and the error
+    word reports it.  With the limit restored the same call is correct again."""
+    l, bits, W = 14, 4, 8
+    n = 600 * (1 << 14)
+    xs = [_rand(n, torch.bfloat16, 90 + w) for w in range(W)]
+    P = thc.thc_num_chunks(n, l)
+    pay = [torch.empty(thc.thc_payload_bytes(n, l, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
+    sc = torch.empty(P, device=DEV)
+    ws = torch.empty(thc.thc_encode_all_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
+    try:
+        thc.thc_set_spin_limit(0)
+        thc.thc_encode_all(xs, l, 2, bits, pay, sc, ws)
+        torch.cuda.synchronize()            # returns: nothing hangs
+        expired = thc.thc_encode_all_timed_out(ws)
+    finally:
+        thc.thc_set_spin_limit(1 << 22)
+    assert expired                           # 4800 items: some wave had to wait at least once
+    thc.thc_encode_all(xs, l, 2, bits, pay, sc, ws)
+    torch.cuda.synchronize()
+    assert not thc.thc_encode_all_timed_out(ws)
+    ref = run_path(xs, l, 2, bits)
+    assert torch.equal(sc, ref["scale"])
+    for x, y in zip(pay, ref["payloads"]):
+        assert torch.equal(x, y)
+
+
+def test_fused_on_full_1p3b_bucket_sampled_chunks():
+    wl = workload("gpt_1p3b")
+    for k, n in enumerate((wl.buckets()[0][1], wl.buckets()[-1][1])):
+        xs = [generate(wl, w, DEV, max_elems=n) for w in range(wl.W)]
+        got = run_path_fused(xs, 14, 21 + k, 4, keep_sums=(k == 0))
+        P = O.num_chunks(n, 14)
+        rng = np.random.default_rng(k)
+        chunks = sorted({0, P - 1, P // 2} | set(rng.integers(0, P, size=20).tolist()))
+        check_against_oracle(xs, got, 14, 21 + k, 4, chunks=chunks)
+        del xs, got
