@@ -222,9 +222,9 @@ void thc_set_spin_limit(uint32_t polls) { g_spin_limit = polls; }
 uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2) {
     if (W == 0 || check_common(n, chunk_log2) != THC_OK) return 0;
     const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
-    // error word (padded to 16 bytes) + 4 W words per chunk (one per wave of every
-    // worker's workgroup; the unfused fallback keeps its per-worker ranges there too)
-    return 16 + 16 * (uint64_t)W * chunks;
+    // error word (padded to 16 bytes) + one word per chunk for every wave of every
+    // worker's workgroup (the unfused fallback keeps its per-worker ranges there too)
+    return 16 + 4 * (uint64_t)thc::encode_all_slot_words(W) * chunks;
 }
 
 int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
@@ -264,7 +264,8 @@ int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t 
             ptrs.payload[w] = payloads[w];
         }
         if (thc::encode_all_fused_applicable(a, ptrs, chunk_log2)) {
-            if (thc::launch_zero_words(words, 4 + 4 * (uint64_t)W * chunks, st) != hipSuccess) return THC_ERR_HIP;
+            const uint64_t slot_words = (uint64_t)thc::encode_all_slot_words(W) * chunks;
+            if (thc::launch_zero_words(words, 4 + slot_words, st) != hipSuccess) return THC_ERR_HIP;
             return finish(thc::launch_encode_all_fused(a, ptrs, dt == THC_BF16, bits, st));
         }
     }

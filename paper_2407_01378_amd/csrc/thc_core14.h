@@ -1,9 +1,11 @@
-// Device building blocks of the chunk-2^14 kernels: one workgroup of 256 threads (4
-// waves) rotates one chunk held 64 coordinates per thread.  Butterfly stages run in
+// Device building blocks of the chunk-2^14 kernels: one workgroup of 512 threads (8
+// waves) rotates one chunk held 32 coordinates per thread.  Butterfly stages run in
 // stride order 1, 2, 4, ..., 8192, every stage one fp32 add and one fp32 subtract per
 // pair, so results are bit-identical to the stage-by-stage definition; between the
-// three register-resident groups of stages the chunk is re-shuffled through LDS with
-// the conflict-free maps of thc_layout14.h.
+// three register-resident groups of stages (5 + 5 + 4) the chunk is re-shuffled through
+// LDS with the conflict-free maps of thc_layout14.h, and once more into the layout the
+// consumer wants (32 consecutive coordinates per thread for the quantizer, 4 per lane
+// for coalesced fp32 stores).
 #pragma once
 
 #include "thc_device.h"
@@ -14,17 +16,18 @@
 namespace thc {
 namespace k14 {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kChunkLog2 = 14;
 constexpr int kChunk = 1 << kChunkLog2;
-constexpr int kRegs = 64;                 // coordinates per thread
+constexpr int kRegs = 32;                 // coordinates per thread
 constexpr float kInvSqrtC = 0.0078125f;   // 2^-7, exact
 
 struct alignas(16) Shared {
     float xb[kChunk];            // exchange buffer, 64 KB
-    uint32_t sgn[kChunk / 32];   // sign diagonal of the chunk, one bit per coordinate
-    float red[8];
-    uint32_t misc[4];
+    uint32_t sgn[kChunk / 32];   // sign diagonal of the chunk, bit (i mod 32) of word i / 32
+    uint32_t sgx[kChunk / 32];   // the same words with even bits gathered in the low half,
+                                 // odd bits in the high half (for bf16 pairs)
+    float red[8];                // one slot per wave for workgroup-wide reductions
 };
 
 // Butterflies on register-index bits [LO, HI): v[i], v[i+h] <- v[i] + v[i+h], v[i] - v[i+h].
@@ -44,19 +47,32 @@ __device__ __forceinline__ void butterflies(float (&v)[kRegs]) {
     }
 }
 
+// Even bits of x to the low half, odd bits to the high half (bit 2p -> p, 2p+1 -> 16+p).
+__device__ __forceinline__ uint32_t unshuffle_bits(uint32_t x) {
+    uint32_t t;
+    t = (x ^ (x >> 1)) & 0x22222222u; x ^= t ^ (t << 1);
+    t = (x ^ (x >> 2)) & 0x0C0C0C0Cu; x ^= t ^ (t << 2);
+    t = (x ^ (x >> 4)) & 0x00F000F0u; x ^= t ^ (t << 4);
+    t = (x ^ (x >> 8)) & 0x0000FF00u; x ^= t ^ (t << 8);
+    return x;
+}
+
 // 128 threads compute the 16384 sign bits of the chunk that starts at coordinate g0
-// (a multiple of 16384) into sh.sgn.  Needs a barrier before use.
+// (a multiple of 16384).  Needs a barrier before use.
 __device__ __forceinline__ void fill_sign_table(Shared& sh, uint64_t g0, uint32_t key0,
                                                 uint32_t key1, uint32_t t) {
     if (t < kChunk / 128) {
         const u32x4 s = sign_block((g0 >> 7) + t, key0, key1);
         *reinterpret_cast<uint4*>(&sh.sgn[4 * t]) = make_uint4(s.w[0], s.w[1], s.w[2], s.w[3]);
+        *reinterpret_cast<uint4*>(&sh.sgx[4 * t]) =
+            make_uint4(unshuffle_bits(s.w[0]), unshuffle_bits(s.w[1]), unshuffle_bits(s.w[2]),
+                       unshuffle_bits(s.w[3]));
     }
 }
 
 // ---------------------------------------------------------------- input -> layout L1
-// Raw 16-byte units in load order (thread t, round j holds unit 256 j + t).
-template <int UNITS>  // 8 for bf16, 16 for fp32
+// Raw 16-byte units in load order (thread t, round j holds unit 512 j + t).
+template <int UNITS>  // 4 for bf16, 8 for fp32
 struct Raw {
     uint4 u[UNITS];
 };
@@ -70,11 +86,11 @@ __device__ __forceinline__ void load_raw(Raw<UNITS>& raw, const void* chunk_ptr,
     const uint4* src = static_cast<const uint4*>(chunk_ptr);
     if (valid == (uint32_t)kChunk) {
 #pragma unroll
-        for (int j = 0; j < UNITS; ++j) raw.u[j] = src[j * 256 + t];
+        for (int j = 0; j < UNITS; ++j) raw.u[j] = src[j * kThreads + t];
     } else {
 #pragma unroll
         for (int j = 0; j < UNITS; ++j) {
-            const uint32_t unit = j * 256 + t;
+            const uint32_t unit = j * kThreads + t;
             const uint32_t first = unit * kPerUnit;
             uint4 q = make_uint4(0u, 0u, 0u, 0u);
             if (first + kPerUnit <= valid) {
@@ -97,47 +113,43 @@ __device__ __forceinline__ void load_raw(Raw<UNITS>& raw, const void* chunk_ptr,
 
 template <int UNITS>
 __device__ __forceinline__ void raw_to_lds(Shared& sh, const Raw<UNITS>& raw, uint32_t t) {
-    constexpr uint32_t kShift = UNITS == 8 ? 3 : 4;
-    uint4* dst = reinterpret_cast<uint4*>(sh.xb) + lay14::e0_store_unit(t, 0, kShift);
+    uint4* dst = reinterpret_cast<uint4*>(sh.xb) + lay14::e0_store_unit(t, 0, UNITS);
 #pragma unroll
-    for (int j = 0; j < UNITS; ++j) dst[j * 256] = raw.u[j];
+    for (int j = 0; j < UNITS; ++j) dst[j * kThreads] = raw.u[j];
 }
 
-// Reads this thread's 64 consecutive coordinates back (layout L1), widens bf16,
+// Reads this thread's 32 consecutive coordinates back (layout L1), widens bf16,
 // and applies the sign diagonal when SIGNED.
 template <int UNITS, bool SIGNED>
 __device__ __forceinline__ void lds_to_l1(const Shared& sh, float (&v)[kRegs], uint32_t t) {
     const uint4* src = reinterpret_cast<const uint4*>(sh.xb);
-    uint32_t sw[2] = {0u, 0u};
-    if (SIGNED) {
-        sw[0] = sh.sgn[2 * t];
-        sw[1] = sh.sgn[2 * t + 1];
-    }
+    if (UNITS == 4) {  // bf16: 8 coordinates per unit, two per dword
+        const uint32_t sx = SIGNED ? sh.sgx[t] : 0u;
 #pragma unroll
-    for (int k = 0; k < UNITS; ++k) {
-        const uint4 q = src[lay14::e0_load_unit(t, k, UNITS)];
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-        if (UNITS == 8) {  // bf16: 8 coordinates per unit, two per dword
+        for (int k = 0; k < UNITS; ++k) {
+            const uint4 q = src[lay14::e0_load_unit(t, k, UNITS)];
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                const int r = 8 * k + 2 * d;  // even coordinate of the pair
-                const int rr = r & 31;
+                const int pair = 4 * k + d;  // coordinates 2 pair, 2 pair + 1
                 uint32_t x = w[d];
-                if (SIGNED) {
-                    const uint32_t s = sw[r >> 5];
-                    const uint32_t m_lo = (rr <= 15 ? (s << (15 - rr)) : (s >> (rr - 15))) & 0x8000u;
-                    const uint32_t m_hi = (s << (30 - rr)) & 0x80000000u;
-                    x ^= m_lo | m_hi;
-                }
-                v[r] = __uint_as_float(x << 16);
-                v[r + 1] = __uint_as_float(x & 0xFFFF0000u);
+                // sign bits of the pair sit at bits `pair` and 16 + `pair` of sx
+                if (SIGNED) x ^= (pair == 15 ? sx : (sx << (15 - pair))) & 0x80008000u;
+                v[2 * pair] = __uint_as_float(x << 16);
+                v[2 * pair + 1] = __uint_as_float(x & 0xFFFF0000u);
             }
-        } else {  // fp32: 4 coordinates per unit
+        }
+    } else {  // fp32: 4 coordinates per unit
+        const uint32_t sw = SIGNED ? sh.sgn[t] : 0u;
+#pragma unroll
+        for (int k = 0; k < UNITS; ++k) {
+            const uint4 q = src[lay14::e0_load_unit(t, k, UNITS)];
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int r = 4 * k + d;
                 uint32_t x = w[d];
-                if (SIGNED) x ^= (sw[r >> 5] << (31 - (r & 31))) & 0x80000000u;
+                if (SIGNED) x ^= (sw << (31 - r)) & 0x80000000u;
                 v[r] = __uint_as_float(x);
             }
         }
@@ -145,73 +157,115 @@ __device__ __forceinline__ void lds_to_l1(const Shared& sh, float (&v)[kRegs], u
 }
 
 // ------------------------------------------------------------------ LDS exchanges
-// L1 -> L2 (inside each wave's quarter of the buffer).
-__device__ __forceinline__ void exchange_x1_store(Shared& sh, const float (&v)[kRegs], uint32_t lane,
-                                                  uint32_t wave) {
-    float* reg = sh.xb + wave * 4096;
+__device__ __forceinline__ void x1_store(Shared& sh, const float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    float* reg = sh.xb + wave * 2048;
 #pragma unroll
-    for (int q = 0; q < 16; ++q)
+    for (int q = 0; q < 8; ++q)
         *reinterpret_cast<float4*>(reg + lay14::x1_store(lane, q)) =
             make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
 }
-__device__ __forceinline__ void exchange_x1_load(const Shared& sh, float (&v)[kRegs], uint32_t lane,
-                                                 uint32_t wave) {
-    const float* reg = sh.xb + wave * 4096;
+__device__ __forceinline__ void x1_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    const float* reg = sh.xb + wave * 2048;
 #pragma unroll
     for (int r = 0; r < kRegs; ++r) v[r] = reg[lay14::x1_load(lane, r)];
 }
-// L2 -> L3 (whole buffer).
-__device__ __forceinline__ void exchange_x2_store(Shared& sh, const float (&v)[kRegs], uint32_t lane,
-                                                  uint32_t wave) {
+__device__ __forceinline__ void x2_store(Shared& sh, const float (&v)[kRegs], uint32_t lane, uint32_t wave) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q)
+    for (int q = 0; q < 8; ++q)
         *reinterpret_cast<float4*>(sh.xb + lay14::x2_store(wave, lane, q)) =
             make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
 }
-__device__ __forceinline__ void exchange_x2_load(const Shared& sh, float (&v)[kRegs], uint32_t lane,
-                                                 uint32_t wave) {
+__device__ __forceinline__ void x2_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+    for (int r = 0; r < kRegs; ++r) v[r] = sh.xb[lay14::x2_load(wave, lane, r)];
+}
+__device__ __forceinline__ void x3e_store(Shared& sh, const float (&v)[kRegs], uint32_t lane, uint32_t wave) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) v[e + 16 * s] = sh.xb[lay14::x2_load(wave, lane, e, s)];
+    for (int r = 0; r < kRegs; ++r) sh.xb[lay14::x3e_store(wave, lane, r)] = v[r];
+}
+__device__ __forceinline__ void x3e_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const float4 f = *reinterpret_cast<const float4*>(sh.xb + lay14::x3e_load(wave, lane, q));
+        v[4 * q] = f.x;
+        v[4 * q + 1] = f.y;
+        v[4 * q + 2] = f.z;
+        v[4 * q + 3] = f.w;
+    }
+}
+__device__ __forceinline__ void x3d_store(Shared& sh, const float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+#pragma unroll
+    for (int r = 0; r < kRegs; ++r) sh.xb[lay14::x3d_store(wave, lane, r)] = v[r];
+}
+__device__ __forceinline__ void x3d_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+        const float4 f = *reinterpret_cast<const float4*>(sh.xb + lay14::x3d_load(wave, lane, h));
+        v[4 * h] = f.x;
+        v[4 * h + 1] = f.y;
+        v[4 * h + 2] = f.z;
+        v[4 * h + 3] = f.w;
+    }
 }
 
 // Stages 0..13 on a chunk that sits in layout L1 in v; result (unnormalised H_c x) in
-// layout L3: v[e + 16 s] is coordinate 4096 s + 16 t + e of the chunk.  Uses the whole
-// exchange buffer; it is free again after the trailing barrier of this function.
+// layout L3.  Starts with a barrier (every thread is past its earlier reads of the
+// buffer); the buffer is still being read when it returns.
 __device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], uint32_t lane,
                                                 uint32_t wave) {
-    butterflies<0, 6>(v);          // strides 1..32
-    __syncthreads();               // every thread is past its reads of the buffer
-    exchange_x1_store(sh, v, lane, wave);
+    butterflies<0, 5>(v);          // strides 1..16
     __syncthreads();
-    exchange_x1_load(sh, v, lane, wave);
-    butterflies<0, 6>(v);          // strides 64..2048
+    x1_store(sh, v, lane, wave);
     __syncthreads();
-    exchange_x2_store(sh, v, lane, wave);
+    x1_load(sh, v, lane, wave);
+    butterflies<0, 5>(v);          // strides 32..512
     __syncthreads();
-    exchange_x2_load(sh, v, lane, wave);
-    butterflies<4, 6>(v);          // strides 4096, 8192
+    x2_store(sh, v, lane, wave);
     __syncthreads();
+    x2_load(sh, v, lane, wave);
+    butterflies<1, 5>(v);          // strides 1024..8192 (register bit 0 is i9, already done)
 }
 
-// max |v| over the whole chunk (all threads return it).  One barrier pair.
-__device__ __forceinline__ float chunk_absmax(Shared& sh, const float (&v)[kRegs], uint32_t lane,
-                                              uint32_t wave) {
+// max |v| over this thread's registers, then over the wave.
+__device__ __forceinline__ float wave_absmax(const float (&v)[kRegs]) {
     float m = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kRegs; i += 2) m = fmaxf(m, fmaxf(fabsf(v[i]), fabsf(v[i + 1])));
+    for (int i = 0; i < kRegs; i += 2)
+        asm("v_max3_f32 %0, %1, |%2|, |%3|" : "=v"(m) : "v"(m), "v"(v[i]), "v"(v[i + 1]));
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    return m;
+}
+
+// max |v| over the whole chunk (every thread returns it).  Two barriers.
+__device__ __forceinline__ float chunk_absmax(Shared& sh, const float (&v)[kRegs], uint32_t lane,
+                                              uint32_t wave) {
+    float m = wave_absmax(v);
     if (lane == 0) sh.red[wave] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3]));
+    m = fmaxf(fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3])),
+              fmaxf(fmaxf(sh.red[4], sh.red[5]), fmaxf(sh.red[6], sh.red[7])));
     __syncthreads();
     return m;
 }
 
+// L3 -> L4e through the buffer (two barriers); v then holds coordinates 32 t .. 32 t + 31.
+__device__ __forceinline__ void l3_to_l4e(Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    __syncthreads();
+    x3e_store(sh, v, lane, wave);
+    __syncthreads();
+    x3e_load(sh, v, lane, wave);
+}
+// L3 -> L4d: v[4 h + e] is coordinate 2048 h + 4 t + e.
+__device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    __syncthreads();
+    x3d_store(sh, v, lane, wave);
+    __syncthreads();
+    x3d_load(sh, v, lane, wave);
+}
+
 // --------------------------------------------------------------------- quantizer
-// Stochastic rounding of the L3-resident chunk onto the 2^BITS-point grid of [-s, s],
+// Stochastic rounding of the L4e-resident chunk onto the 2^BITS-point grid of [-s, s],
 // packed and stored.  v holds the UNNORMALISED rotation; y = v * 2^-7.
 //   g0       global index of the chunk's first coordinate
 //   payload  start of this worker's payload
@@ -222,55 +276,55 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
     constexpr uint32_t L = (1u << BITS) - 1u;
     const float two = s + s;
     const float inv = two != 0.0f ? (float)L / two : 0.0f;
+    const uint64_t g = g0 + (uint64_t)t * 32u;
+    uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
 #pragma unroll
-    for (int run = 0; run < 4; ++run) {
-        const uint64_t g = g0 + (uint64_t)run * 4096u + (uint64_t)t * 16u;
-        const u32x4 rb = round_block(g >> 4, worker, key0, key1);
-        uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    for (int i = 0; i < BITS; ++i) pk[i] = 0u;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const u32x4 rb = round_block((g >> 4) + half, worker, key0, key1);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const float y = v[e + 16 * run] * kInvSqrtC;
+            const int r = 16 * half + e;
+            const float y = v[r] * kInvSqrtC;
             const float pos = (y + s) * inv;
-            const uint32_t r = (rb.w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
-            const float u = __builtin_fmaf((float)r, 0x1p-8f, 0x1p-9f);   // (r + 0.5) / 256, exact
+            const uint32_t rnd = (rb.w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+            const float u = __builtin_fmaf((float)rnd, 0x1p-8f, 0x1p-9f);   // (r + 0.5) / 256, exact
             const float tt = pos + u;
-            uint32_t q = (uint32_t)tt;                                     // tt >= 0: truncation = floor
+            uint32_t q = (uint32_t)tt;                                       // tt >= 0: truncation = floor
             q = q < L ? q : L;
-            const int bit = e * BITS;
+            const int bit = r * BITS;
             pk[bit >> 5] |= q << (bit & 31);
         }
-        uint8_t* dst = payload + (g * BITS) / 8u;
-        if (BITS == 8) {
-            *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        } else if (BITS == 4) {
-            *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
-        } else {
-            *reinterpret_cast<uint32_t*>(dst) = pk[0];
-        }
+    }
+    uint8_t* dst = payload + (g * BITS) / 8u;
+    if (BITS == 8) {
+        reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        reinterpret_cast<uint4*>(dst)[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+    } else if (BITS == 4) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    } else {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
     }
 }
 
-// Output side of the inverse rotation: x = D (v * 2^-7), L3 layout, first `valid`
-// coordinates of the chunk are stored.
-__device__ __forceinline__ void store_signed_l3(const Shared& sh, const float (&v)[kRegs], float* out,
-                                                uint32_t valid, uint32_t t) {
+// Output side of the inverse rotation: x = D (v * 2^-7) from layout L4d; the first
+// `valid` coordinates of the chunk are stored.
+__device__ __forceinline__ void store_signed_l4d(const Shared& sh, const float (&v)[kRegs], float* out,
+                                                 uint32_t valid, uint32_t t) {
 #pragma unroll
-    for (int run = 0; run < 4; ++run) {
-        const uint32_t i0 = run * 4096u + t * 16u;
-        const uint32_t sb = (sh.sgn[i0 >> 5] >> (i0 & 31u)) & 0xFFFFu;
-        float x[16];
+    for (int h = 0; h < 8; ++h) {
+        const uint32_t i0 = h * 2048u + t * 4u;
+        const uint32_t sb = sh.sgn[i0 >> 5] >> (i0 & 31u);   // bits 0..3: signs of the 4 coordinates
+        float x[4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            x[e] = __uint_as_float(__float_as_uint(v[e + 16 * run] * kInvSqrtC) ^
-                                   ((sb << (31 - e)) & 0x80000000u));
-        if (i0 + 16u <= valid) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                *reinterpret_cast<float4*>(out + i0 + 4 * k) =
-                    make_float4(x[4 * k], x[4 * k + 1], x[4 * k + 2], x[4 * k + 3]);
+        for (int e = 0; e < 4; ++e)
+            x[e] = __uint_as_float(__float_as_uint(v[4 * h + e] * kInvSqrtC) ^ ((sb << (31 - e)) & 0x80000000u));
+        if (i0 + 4u <= valid) {
+            *reinterpret_cast<float4*>(out + i0) = make_float4(x[0], x[1], x[2], x[3]);
         } else {
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
+            for (int e = 0; e < 4; ++e)
                 if (i0 + e < valid) out[i0 + e] = x[e];
         }
     }

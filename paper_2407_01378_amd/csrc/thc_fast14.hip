@@ -1,6 +1,6 @@
 // Tuned kernels for chunk_log2 = 14 (the chunk size of every large workload): one
-// workgroup of 256 threads per chunk, the chunk lives in registers (64 coordinates per
-// thread) and crosses LDS three times (input staging + two re-shuffles), see
+// workgroup of 512 threads per chunk, the chunk lives in registers (32 coordinates per
+// thread) and is re-shuffled through LDS between groups of butterfly stages, see
 // thc_core14.h.  Used when every pointer is 16-byte aligned; the generic kernels cover
 // everything else with identical results.
 #include "thc_core14.h"
@@ -17,7 +17,7 @@ namespace {
 template <bool BF16, Mode MODE, int BITS>
 __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a) {
     __shared__ Shared sh;
-    constexpr int kUnits = BF16 ? 8 : 16;
+    constexpr int kUnits = BF16 ? 4 : 8;
     constexpr int kElem = BF16 ? 2 : 4;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint64_t p = blockIdx.x;
@@ -35,16 +35,13 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
     rotate_l1_to_l3(sh, v, lane, wave);
 
     if constexpr (MODE == Mode::Forward) {
+        l3_to_l4d(sh, v, lane, wave);
         float* y = static_cast<float*>(a.out) + g0;
 #pragma unroll
-        for (int run = 0; run < 4; ++run)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int b = 16 * run + 4 * k;
-                *reinterpret_cast<float4*>(y + run * 4096 + t * 16 + 4 * k) =
-                    make_float4(v[b] * kInvSqrtC, v[b + 1] * kInvSqrtC, v[b + 2] * kInvSqrtC,
-                                v[b + 3] * kInvSqrtC);
-            }
+        for (int h = 0; h < 8; ++h)
+            *reinterpret_cast<float4*>(y + h * 2048 + t * 4) =
+                make_float4(v[4 * h] * kInvSqrtC, v[4 * h + 1] * kInvSqrtC, v[4 * h + 2] * kInvSqrtC,
+                            v[4 * h + 3] * kInvSqrtC);
     } else if constexpr (MODE == Mode::Absmax) {
         const float m = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
         if (t == 0) static_cast<float*>(a.out)[p] = m;
@@ -56,6 +53,7 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
             s = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
         }
         if (a.scale_out && t == 0) a.scale_out[p] = s;
+        l3_to_l4e(sh, v, lane, wave);
         quantize_store<BITS>(v, s, g0, a.worker, a.key0, a.key1, static_cast<uint8_t*>(a.out), t);
     }
 }
@@ -73,19 +71,19 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     float v[kRegs];
     fill_sign_table(sh, g0, a.key0, a.key1, t);
     if constexpr (SRC == 0) {
-        Raw<16> raw;   // y is complete (padded), so every unit exists
-        load_raw<16, 4>(raw, static_cast<const float*>(a.in) + g0, (uint32_t)kChunk, t);
-        raw_to_lds<16>(sh, raw, t);
+        Raw<8> raw;   // y is complete (padded), so every unit exists
+        load_raw<8, 4>(raw, static_cast<const float*>(a.in) + g0, (uint32_t)kChunk, t);
+        raw_to_lds<8>(sh, raw, t);
         __syncthreads();
-        lds_to_l1<16, false>(sh, v, t);
+        lds_to_l1<8, false>(sh, v, t);
     } else {
         const float s = a.scale_in[p];
         const float step = (s + s) / (float)((1u << a.bits) - 1u);
         const float q = step / (float)a.W;
         if constexpr (SRC == 1) {
-            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint8_t*>(a.in) + g0) + 4 * t;
+            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint8_t*>(a.in) + g0) + 2 * t;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
+            for (int k = 0; k < 2; ++k) {
                 const uint4 w = src[k];
                 const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -95,9 +93,9 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
                         v[16 * k + 4 * d + b] = (float)((ww[d] >> (8 * b)) & 0xFFu) * q - s;
             }
         } else {
-            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.in) + g0) + 8 * t;
+            const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.in) + g0) + 4 * t;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 4; ++k) {
                 const uint4 w = src[k];
                 const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -109,7 +107,8 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
         }
     }
     rotate_l1_to_l3(sh, v, lane, wave);
-    store_signed_l3(sh, v, static_cast<float*>(a.out) + g0, valid, t);
+    l3_to_l4d(sh, v, lane, wave);
+    store_signed_l4d(sh, v, static_cast<float*>(a.out) + g0, valid, t);
 }
 
 template <bool BF16, Mode MODE>

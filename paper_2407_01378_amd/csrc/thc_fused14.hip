@@ -2,7 +2,7 @@
 //
 // encode_all: ONE pass over every worker's gradient.  A work item is (chunk p, worker
 // w); the workgroup that owns it rotates the chunk, publishes the chunk's largest
-// magnitude to a per-chunk slot in global memory, waits until all W workers of chunk p
+// magnitude to per-chunk slots in global memory, waits until all W workers of chunk p
 // have published, and only then quantizes - the rotated chunk never leaves registers,
 // so each gradient is read from HBM once.  The grid is persistent and no larger than
 // what is resident at once (occupancy x CUs), items are dealt round-robin
@@ -21,73 +21,77 @@ namespace thc {
 namespace k14 {
 namespace {
 
-// ------------------------------------------------------------------ encode_all
-template <bool BF16, int BITS>
-__global__ __launch_bounds__(kThreads, 2) void encode_all_kernel(const EncodeAllArgs a,
-                                                              const FusedWorkerPtrs ptrs) {
-    __shared__ Shared sh;
-    constexpr int kUnits = BF16 ? 8 : 16;
-    constexpr int kElem = BF16 ? 2 : 4;
-    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t total = (uint32_t)a.chunks * a.W;
-    const uint32_t G = gridDim.x;
-    uint32_t item = blockIdx.x;
-    if (item >= total) return;
+constexpr uint32_t kWaves = kThreads / 64;
+// Second argument of __launch_bounds__ (waves per SIMD the compiler must allow): two
+// workgroups of 8 waves per CU = 4 waves on each of the 4 SIMDs = at most 128 VGPRs.
+constexpr int kWavesPerSimd = 4;
+// encode_all can keep two items in flight per workgroup (front half of item k+1 between
+// the publish and the wait of item k).  With four waves per SIMD the other workgroup on
+// the CU already covers the wait, and one item in flight keeps the kernel out of scratch.
+constexpr bool kTwoInFlight = false;
 
-    auto chunk_valid = [&](uint32_t p) -> uint32_t {
-        const uint64_t left = a.n - ((uint64_t)p << kChunkLog2);
-        return left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-    };
-    uint32_t p = item / a.W, w = item - p * a.W;
-    Raw<kUnits> raw;
-    load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + ((uint64_t)p << kChunkLog2) * kElem,
-                            chunk_valid(p), t);
-    for (;;) {
+// ------------------------------------------------------------------ encode_all
+template <bool BF16>
+struct EncodeAllCtx {
+    static constexpr int kUnits = BF16 ? 4 : 8;
+    static constexpr int kElem = BF16 ? 2 : 4;
+    static constexpr bool kPrefetch = BF16;   // load the next item's input one item ahead
+    const EncodeAllArgs& a;
+    const FusedWorkerPtrs& ptrs;
+    Shared& sh;
+    Raw<kUnits> raw;        // input of the next item to enter the pipeline, in flight
+    uint32_t t, lane, wave, total, G, nwords;
+
+    __device__ __forceinline__ void prefetch(uint32_t item) {
+        const uint32_t p = item / a.W, w = item - p * a.W;
         const uint64_t g0 = (uint64_t)p << kChunkLog2;
-        fill_sign_table(sh, g0, a.key0, a.key1, t);
+        const uint64_t left = a.n - g0;
+        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem, valid, t);
+    }
+
+    // Front half of an item: stage the prefetched input, rotate, publish this wave's share
+    // of the chunk's range, and bring the chunk into the quantizer's layout.  Also starts
+    // the loads of the item after it.
+    __device__ __forceinline__ void front(float (&v)[kRegs], uint32_t item) {
+        const uint32_t p = item / a.W, w = item - p * a.W;
+        // fp32 input is 32 registers per thread in flight; loading it here instead of one
+        // item ahead keeps the kernel out of scratch
+        if (!kPrefetch) prefetch(item);
+        __syncthreads();   // the previous item's last reads of the buffer are done
+        fill_sign_table(sh, (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
         raw_to_lds<kUnits>(sh, raw, t);
         __syncthreads();
-        float v[kRegs];
         lds_to_l1<kUnits, true>(sh, v, t);
-
-        // prefetch the next item of this workgroup while this one is rotated
-        const uint32_t next = item + G;
-        const bool has_next = next < total;
-        uint32_t p2 = 0, w2 = 0;
-        if (has_next) {
-            p2 = next / a.W;
-            w2 = next - p2 * a.W;
-            load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w2]) + ((uint64_t)p2 << kChunkLog2) * kElem,
-                                    chunk_valid(p2), t);
-        }
+        if (kPrefetch && item + G < total) prefetch(item + G);
         rotate_l1_to_l3(sh, v, lane, wave);
-
-        // this wave's share of the chunk's range
-        float m = 0.0f;
-#pragma unroll
-        for (int i = 0; i < kRegs; i += 2) m = fmaxf(m, fmaxf(fabsf(v[i]), fabsf(v[i + 1])));
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        m = m * kInvSqrtC;
-
-        // Publish: one word per wave, value | valid bit (non-negative floats order like
-        // their bit patterns and leave bit 31 free).  The words travel between workgroups
-        // only through device-scope stores and loads, which are served at the memory
-        // side, so no cache write-back or invalidate is needed.  The slots start zeroed.
-        const uint32_t nwords = 4u * a.W;   // four waves per workgroup, W workgroups per chunk
-        uint32_t* slot = a.slots + (uint64_t)p * nwords;
+        const float m = wave_absmax(v) * kInvSqrtC;
+        // One word per wave, value | valid bit (non-negative floats order like their bit
+        // patterns and leave bit 31 free).  The words travel between workgroups only
+        // through device-scope stores and loads, which are served at the memory side, so
+        // no cache write-back or invalidate is needed.  The slots start zeroed.
         if (lane == 0)
-            __hip_atomic_store(&slot[4u * w + wave], __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
+            __hip_atomic_store(&a.slots[(uint64_t)p * nwords + kWaves * w + wave],
+                               __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        // Wait until every wave of every worker of this chunk has published, then take
-        // the largest value.  Bounded: on time-out flag the error word and carry on.
+        l3_to_l4e(sh, v, lane, wave);
+    }
+
+    // Back half: wait until every wave of every worker of the chunk has published, take
+    // the largest value as the shared scale, quantize and store.  The wait is bounded:
+    // on time-out the error word is set and the wave carries on.
+    template <int BITS>
+    __device__ __forceinline__ void back(const float (&v)[kRegs], uint32_t item) {
+        const uint32_t p = item / a.W, w = item - p * a.W;
+        const uint32_t* slot = a.slots + (uint64_t)p * nwords;
         uint32_t sbits = 0u;
         for (uint32_t spins = 0;; ++spins) {
             uint32_t all_valid = 0x80000000u, mx = 0u;
             for (uint32_t base = 0; base < nwords; base += 64u) {
                 const uint32_t i = base + lane;
-                const uint32_t val = i < nwords ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                                : 0x80000000u;
+                const uint32_t val =
+                    i < nwords ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                               : 0x80000000u;
                 all_valid &= val;
                 const uint32_t mag = val & 0x7FFFFFFFu;
                 mx = mag > mx ? mag : mx;
@@ -108,12 +112,46 @@ __global__ __launch_bounds__(kThreads, 2) void encode_all_kernel(const EncodeAll
         }
         const float s = __uint_as_float(sbits);
         if (w == 0 && t == 0) a.scale[p] = s;
-        quantize_store<BITS>(v, s, g0, w, a.key0, a.key1, ptrs.payload[w], t);
+        quantize_store<BITS>(v, s, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+    }
+};
 
-        if (!has_next) break;
-        item = next;
-        p = p2;
-        w = w2;
+// Two items are in flight per workgroup: the front half of item k+1 (rotation, publish)
+// runs between the publish of item k and the wait for item k's peers, so the round trip
+// of the publish/poll through memory is covered by useful work.  Item k waits only for
+// publishes that its peers issue before their own waits on earlier items, so with every
+// workgroup of the grid resident there is no circular wait.
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
+                                                                 const FusedWorkerPtrs ptrs) {
+    __shared__ Shared sh;
+    const uint32_t t = threadIdx.x;
+    EncodeAllCtx<BF16> c{a, ptrs, sh, {}, t, t & 63u, t >> 6, (uint32_t)a.chunks * a.W, gridDim.x,
+                         kWaves * a.W};
+    uint32_t item = blockIdx.x;
+    if (item >= c.total) return;
+    if (EncodeAllCtx<BF16>::kPrefetch) c.prefetch(item);
+    if constexpr (kTwoInFlight) {
+        float va[kRegs], vb[kRegs];
+        c.front(va, item);
+        for (;;) {
+            const bool has_b = item + c.G < c.total;
+            if (has_b) c.front(vb, item + c.G);
+            c.template back<BITS>(va, item);
+            if (!has_b) break;
+            item += c.G;
+            const bool has_a = item + c.G < c.total;
+            if (has_a) c.front(va, item + c.G);
+            c.template back<BITS>(vb, item);
+            if (!has_a) break;
+            item += c.G;
+        }
+    } else {
+        for (; item < c.total; item += c.G) {
+            float v[kRegs];
+            c.front(v, item);
+            c.template back<BITS>(v, item);
+        }
     }
 }
 
@@ -123,15 +161,38 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* dst, uint64_t
 }
 
 // ------------------------------------------------------------- aggregate_decode
-// One chunk per work item, persistent grid.  Thread t owns coordinates 64 t .. 64 t + 63
-// (layout L1): 8 * BITS payload bytes per worker.
+// One chunk per work item, persistent grid.  Thread t owns coordinates 32 t .. 32 t + 31
+// (layout L1): 4 * BITS payload bytes (BITS dwords) per worker.
 template <int BITS>
-__global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const AggDecodeArgs a,
-                                                                    const FusedPayloadPtrs ptrs) {
+struct PayloadWords {
+    uint32_t w[BITS];
+};
+template <int BITS>
+__device__ __forceinline__ PayloadWords<BITS> load_payload_words(const uint8_t* p) {
+    PayloadWords<BITS> r;
+    if (BITS == 2) {
+        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        r.w[0] = q.x;
+        r.w[1] = q.y;
+    } else {
+#pragma unroll
+        for (int k = 0; k < BITS / 4; ++k) {
+            const uint4 q = reinterpret_cast<const uint4*>(p)[k];
+            r.w[4 * k] = q.x;
+            r.w[4 * k + 1] = q.y;
+            r.w[4 * k + 2] = q.z;
+            r.w[4 * k + 3] = q.w;
+        }
+    }
+    return r;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kernel(const AggDecodeArgs a,
+                                                                       const FusedPayloadPtrs ptrs) {
     __shared__ Shared sh;
-    constexpr int kVec = BITS / 2;            // uint4 loads per worker per thread
-    constexpr int kWords = 4 * kVec;          // payload dwords per worker per thread
-    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;   // sub-word accumulators per dword
+    constexpr int kWords = BITS;                        // payload dwords per worker per thread
+    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;    // sub-word accumulators per dword
     constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const float Lf = (float)((1u << BITS) - 1u);
@@ -141,6 +202,7 @@ __global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const Agg
         const uint64_t g0 = p << kChunkLog2;
         const uint64_t left = a.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        __syncthreads();   // the previous item's last reads of the buffer and sign table are done
         fill_sign_table(sh, g0, a.key0, a.key1, t);
 
         uint32_t acc[kWords][kLanes];
@@ -148,31 +210,20 @@ __global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const Agg
         for (int d = 0; d < kWords; ++d)
 #pragma unroll
             for (int k = 0; k < kLanes; ++k) acc[d][k] = 0u;
-        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (8u * BITS);
+        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (4u * BITS);
         for (uint32_t w0 = 0; w0 < a.W; w0 += 4) {
-            uint4 x[4][kVec];
+            PayloadWords<BITS> x[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (w0 + j < a.W) {
-                    const uint4* src = reinterpret_cast<const uint4*>(ptrs.p[w0 + j] + byte0);
+            for (int j = 0; j < 4; ++j)
+                if (w0 + j < a.W) x[j] = load_payload_words<BITS>(ptrs.p[w0 + j] + byte0);
 #pragma unroll
-                    for (int k = 0; k < kVec; ++k) x[j][k] = src[k];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j)
                 if (w0 + j < a.W) {
 #pragma unroll
-                    for (int k = 0; k < kVec; ++k) {
-                        const uint32_t ww[4] = {x[j][k].x, x[j][k].y, x[j][k].z, x[j][k].w};
+                    for (int d = 0; d < kWords; ++d)
 #pragma unroll
-                        for (int d = 0; d < 4; ++d)
-#pragma unroll
-                            for (int q = 0; q < kLanes; ++q)
-                                acc[4 * k + d][q] += (ww[d] >> (BITS * q)) & kMask;
-                    }
+                        for (int q = 0; q < kLanes; ++q) acc[d][q] += (x[j].w[d] >> (BITS * q)) & kMask;
                 }
-            }
         }
 
         // sums -> rotated-domain estimate of the mean, layout L1
@@ -202,16 +253,16 @@ __global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const Agg
 
         if (a.sums) {   // the caller also wants the integer aggregate
             if (BITS == 8) {
-                uint16_t* dst = static_cast<uint16_t*>(a.sums) + g0 + 64u * t;
+                uint16_t* dst = static_cast<uint16_t*>(a.sums) + g0 + 32u * t;
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
+                for (int k = 0; k < 4; ++k)
                     *reinterpret_cast<uint4*>(dst + 8 * k) =
                         make_uint4(S[8 * k] | (S[8 * k + 1] << 16), S[8 * k + 2] | (S[8 * k + 3] << 16),
                                    S[8 * k + 4] | (S[8 * k + 5] << 16), S[8 * k + 6] | (S[8 * k + 7] << 16));
             } else {
-                uint8_t* dst = static_cast<uint8_t*>(a.sums) + g0 + 64u * t;
+                uint8_t* dst = static_cast<uint8_t*>(a.sums) + g0 + 32u * t;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
+                for (int k = 0; k < 2; ++k) {
                     uint32_t o[4];
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
@@ -223,8 +274,8 @@ __global__ __launch_bounds__(kThreads, 2) void aggregate_decode_kernel(const Agg
             }
         }
         rotate_l1_to_l3(sh, v, lane, wave);
-        store_signed_l3(sh, v, a.out + g0, valid, t);
-        __syncthreads();   // the sign table is rewritten by the next item
+        l3_to_l4d(sh, v, lane, wave);
+        store_signed_l4d(sh, v, a.out + g0, valid, t);
     }
 }
 
@@ -306,18 +357,25 @@ int device_cus() {
     return g_cus;
 }
 
-template <typename K>
-uint32_t resident_grid(K kernel) {
-    int occ = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, kThreads, 0) != hipSuccess || occ < 1)
-        return 0;
-    const int cus = device_cus();
-    return cus > 0 ? (uint32_t)(occ * cus) : 0;
+// Workgroups of `kernel` that are resident at once on the whole device.  The occupancy
+// query is slow (tens of microseconds), so the answer is kept per kernel.
+template <auto kernel>
+uint32_t resident_grid() {
+    static uint32_t cached = 0;   // one per kernel
+    if (cached == 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, kThreads, 0) != hipSuccess || occ < 1)
+            return 0;
+        const int cus = device_cus();
+        if (cus <= 0) return 0;
+        cached = (uint32_t)(occ * cus);
+    }
+    return cached;
 }
 
 template <bool BF16, int BITS>
 hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid(encode_all_kernel<BF16, BITS>);
+    uint32_t G = resident_grid<encode_all_kernel<BF16, BITS>>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
@@ -328,6 +386,8 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
 
 }  // namespace
 }  // namespace k14
+
+uint32_t encode_all_slot_words(uint32_t W) { return k14::kWaves * W; }
 
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2) {
     if (chunk_log2 != 14 || a.W > (uint32_t)kMaxFusedWorkers) return false;
@@ -370,9 +430,9 @@ hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayl
     using namespace k14;
     if (a.chunks == 0) return hipSuccess;
     uint32_t G = 0;
-    if (bits == 2) G = resident_grid(aggregate_decode_kernel<2>);
-    else if (bits == 4) G = resident_grid(aggregate_decode_kernel<4>);
-    else G = resident_grid(aggregate_decode_kernel<8>);
+    if (bits == 2) G = resident_grid<aggregate_decode_kernel<2>>();
+    else if (bits == 4) G = resident_grid<aggregate_decode_kernel<4>>();
+    else G = resident_grid<aggregate_decode_kernel<8>>();
     if (G == 0) return hipErrorInvalidValue;
     if (G > a.chunks) G = (uint32_t)a.chunks;
     if (bits == 2)

@@ -55,9 +55,11 @@ struct EncodeAllArgs {
     uint32_t key0, key1;
     uint32_t max_spins;  // bound on the polls of one wait
     float* scale;        // out: chunks shared scales
-    uint32_t* slots;     // zeroed: chunks x 4W words, one per wave of every worker
+    uint32_t* slots;     // zeroed: chunks x encode_all_slot_words(W) words
     uint32_t* error;     // zeroed: set to 1 if a wait timed out
 };
+// Words per chunk in `slots`: one for every wave of every worker's workgroup.
+uint32_t encode_all_slot_words(uint32_t W);
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs,
                                  uint32_t chunk_log2);
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,

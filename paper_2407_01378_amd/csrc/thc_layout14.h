@@ -1,22 +1,25 @@
-// LDS address maps of the chunk-2^14 kernels (256 threads = 4 waves of 64 lanes, 64
-// coordinates per thread).  i = 14-bit position inside the chunk, bits i0..i13.
+// LDS address maps of the chunk-2^14 kernels: 512 threads = 8 waves of 64 lanes, 32
+// coordinates per thread.  i = 14-bit position inside the chunk, bits i0..i13.
 //
 // The rotation runs its 14 butterfly stages in stride order 1, 2, 4, ... as three
-// register-resident groups; between groups the (lane, register) assignment of the
-// chunk is re-shuffled through LDS:
+// register-resident groups (5 + 5 + 4 stages); between groups, and once more at the
+// end, the (wave, lane, register) assignment of the chunk is re-shuffled through LDS:
 //
-//   layout L1  register = i0..i5,              lane = i6..i11, wave = i12..i13   (stages 0-5)
-//   layout L2  register = i6..i11,             lane = i0..i5,  wave = i12..i13   (stages 6-11)
-//   layout L3  register = i0..i3 + 16*(i12,i13), lane = i4..i9, wave = i10..i11  (stages 12-13)
+//   L1   register = i0..i4        lane = i5..i10               wave = i11..i13   stages 0-4
+//   L2   register = i5..i9        lane = i0..i4, i10           wave = i11..i13   stages 5-9
+//   L3   register = i9, i10..i13  lane = i5, i6, i0, i1, i2, i3  wave = i4, i7, i8   stages 10-13
+//   L4e  = L1: 32 consecutive coordinates per thread (quantize, pack, 16-byte payload store)
+//   L4d  register = i0, i1, i11..i13   lane = i2..i7   wave = i8..i10   (coalesced fp32 store)
 //
-// In L3 a thread owns four runs of 16 consecutive coordinates, which is what the
-// quantizer (one Philox block per 16 coordinates), the bit-packer and the stores want.
+// Eight waves per chunk keep four waves resident per SIMD with two chunks per CU in
+// flight (LDS holds one 64 KB chunk per workgroup), which the VALU needs to run its
+// double-rate fp32/logic instructions back to back.
 //
-// Every map below is a bijection of the index bits onto dword addresses, chosen so
-// that the 128-bit side of an exchange has 8 consecutive lanes on 8 distinct 16-byte
-// bank groups and the 32-bit side has 32 consecutive lanes on 32 distinct banks.  The
-// XOR terms only involve low register bits, so a thread needs at most 8 base addresses
-// per exchange and every access is base + immediate offset.
+// Every map is a bijection of the index bits onto dword addresses such that the 128-bit
+// side of an exchange has 8 consecutive lanes on 8 distinct 16-byte bank groups and the
+// 32-bit side has 32 consecutive lanes on 32 distinct banks.  XOR terms involve at most
+// three register bits, so a thread needs at most 8 base addresses per exchange and every
+// access is base + immediate offset.
 #pragma once
 
 #include <stdint.h>
@@ -31,44 +34,70 @@ namespace thc {
 namespace lay14 {
 
 // ---- E0: raw input units (16 bytes each) from load order to L1 order -------------------
-// Unit u = i / (coordinates per unit).  Load order: thread t, round j holds unit 256 j + t.
-// L1 order: thread T needs units per*T .. per*T + per-1 (per = 8 for bf16, 16 for fp32).
-// Unit u is kept at unit address u ^ ((u >> shift) & 7), shift = log2(per).
-THC_HD uint32_t e0_store_unit(uint32_t t, uint32_t j, uint32_t shift) {
-    return j * 256u + (t ^ ((t >> shift) & 7u));
+// Load order: thread t (0..511), round j holds unit 512 j + t.  L1 order: thread T needs
+// units per*T .. per*T + per-1 (per = 4 for bf16: 8 coordinates a unit; 8 for fp32: 4 a unit).
+// Unit u is kept at unit address u ^ swz(u): bf16 swz = (u >> 3) & 3, fp32 swz = (u >> 3) & 7.
+THC_HD uint32_t e0_store_unit(uint32_t t, uint32_t j, uint32_t per) {
+    const uint32_t swz = per == 4 ? ((t >> 3) & 3u) : ((t >> 3) & 7u);
+    return j * 512u + (t ^ swz);
 }
 THC_HD uint32_t e0_load_unit(uint32_t T, uint32_t k, uint32_t per) {
-    return per * T + (k ^ (T & 7u));
+    const uint32_t swz = per == 4 ? ((T >> 1) & 3u) : (T & 7u);
+    return per * T + (k ^ swz);
 }
 
-// ---- X1: L1 -> L2, inside one wave's 4096-dword region ---------------------------------
-// dword address of (i0..i11): (i6..i11) << 6 | (i0..i5) ^ ((i6..i8) << 2)
-// writer (L1): lane = i6..i11 stores registers 4q..4q+3 as one 128-bit word
-THC_HD uint32_t x1_store(uint32_t lane, uint32_t q) {  // q = 0..15
-    return (lane << 6) | (((q & 7u) ^ (lane & 7u)) << 2) | ((q >> 3) << 5);
+// ---- X1: L1 -> L2, inside one wave's 2048-dword region ----------------------------------
+// dword address of (i0..i10): a0 a1 = i0 i1 | a2 a3 a4 = i2^i5, i3^i6, i4^i7 | a5..a10 = i5..i10
+// writer (L1): lane = i5..i10 stores registers 4q..4q+3 (q = i2..i4) as one 128-bit word
+THC_HD uint32_t x1_store(uint32_t lane, uint32_t q) {  // q = 0..7
+    return (lane << 5) | ((q ^ (lane & 7u)) << 2);
 }
-// reader (L2): lane = i0..i5 loads register r = i6..i11
-THC_HD uint32_t x1_load(uint32_t lane, uint32_t r) {  // r = 0..63
-    return (lane ^ ((r & 7u) << 2)) + (r << 6);
+// reader (L2): lane = (i0..i4, i10) loads register r = i5..i9
+THC_HD uint32_t x1_load(uint32_t lane, uint32_t r) {  // r = 0..31
+    const uint32_t low = lane & 31u;                 // i0..i4
+    return (low ^ ((r & 7u) << 2)) | (r << 5) | ((lane >> 5) << 10);
 }
 
-// ---- X2: L2 -> L3, whole 16384-dword buffer ----------------------------------------------
-// address bits: a0 a1 = i6 i7 | a2 a3 a4 = i0^i4, i1^i5, i2^i8 | a5 = i3 | a6 a7 = i4 i5 |
-//               a8 a9 a10 a11 = i8 i9 i10 i11 | a12 a13 = i12 i13
-// writer (L2): wave = i12..i13, lane = i0..i5, stores registers 4q..4q+3 (r = i6..i11)
-THC_HD uint32_t x2_store(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..15 = i8..i11
-    const uint32_t e8 = q & 1u;
-    const uint32_t base = (((lane & 7u) ^ (((lane >> 4) & 3u) | (e8 << 2))) << 2) |
-                          (((lane >> 3) & 7u) << 5) | (e8 << 8) | (wave << 12);
-    return base + ((q >> 1) << 9);
+// ---- X2: L2 -> L3, whole 16384-dword buffer, no XOR needed -------------------------------
+// a0 a1 = i5 i6 | a2..a6 = i0..i4 | a7 a8 = i7 i8 | a9..a13 = i9..i13
+// writer (L2): wave = i11..i13, lane = (i0..i4, i10), stores registers 4q..4q+3, q = (i7,i8,i9)
+THC_HD uint32_t x2_store(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..7
+    return ((lane & 31u) << 2) | ((lane >> 5) << 10) | (wave << 11) | ((q & 3u) << 7) | ((q >> 2) << 9);
 }
-// reader (L3): wave = i10..i11, lane = i4..i9, loads register e + 16 s (e = i0..i3, s = i12..i13)
-THC_HD uint32_t x2_load(uint32_t wave, uint32_t lane, uint32_t e, uint32_t s) {
-    const uint32_t k = e & 7u;
-    const uint32_t base = ((lane >> 2) & 3u) |
-                          ((k ^ ((lane & 3u) | (((lane >> 4) & 1u) << 2))) << 2) |
-                          ((lane & 3u) << 6) | (((lane >> 4) & 3u) << 8) | (wave << 10);
-    return base + ((e >> 3) << 5) + (s << 12);
+// reader (L3): wave = (i4,i7,i8), lane = (i5,i6,i0,i1,i2,i3), loads register rho = (i9..i13)
+THC_HD uint32_t x2_load(uint32_t wave, uint32_t lane, uint32_t rho) {  // rho = 0..31
+    return (lane & 3u) | (((lane >> 2) & 15u) << 2) | ((wave & 1u) << 6) | ((wave >> 1) << 7) | (rho << 9);
+}
+
+// ---- X3e: L3 -> L4e (= L1), whole buffer ---------------------------------------------------
+// a0 a1 = i0 i1 | a2 a3 = i5 i6 | a4 = i2^i7 | a5 a6 = i3 i4 | a7 a8 = i7 i8 | a9..a13 = i9..i13
+// writer (L3): 32-bit stores of register rho
+THC_HD uint32_t x3e_store(uint32_t wave, uint32_t lane, uint32_t rho) {
+    const uint32_t i5i6 = lane & 3u, i0i1 = (lane >> 2) & 3u, i2 = (lane >> 4) & 1u, i3 = (lane >> 5) & 1u;
+    const uint32_t i4 = wave & 1u, i7 = (wave >> 1) & 1u, i8 = (wave >> 2) & 1u;
+    return i0i1 | (i5i6 << 2) | ((i2 ^ i7) << 4) | (i3 << 5) | (i4 << 6) | (i7 << 7) | (i8 << 8) | (rho << 9);
+}
+// reader (L4e): wave = i11..i13, lane = i5..i10, loads registers 4q..4q+3 (q = i2..i4) as 128 bits
+THC_HD uint32_t x3e_load(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..7
+    const uint32_t i5i6 = lane & 3u, i7 = (lane >> 2) & 1u, i8 = (lane >> 3) & 1u, i9i10 = lane >> 4;
+    return (i5i6 << 2) | (((q & 1u) ^ i7) << 4) | ((q >> 1) << 5) | (i7 << 7) | (i8 << 8) | (i9i10 << 9) | (wave << 11);
+}
+
+// ---- X3d: L3 -> L4d, whole buffer ----------------------------------------------------------
+// a0 a1 = i0 i1 | a2 = i2 | a3 = i3^i5 | a4 = i4^i6 | a5..a8 = i5..i8 | a9..a13 = i9..i13
+THC_HD uint32_t x3d_store(uint32_t wave, uint32_t lane, uint32_t rho) {
+    const uint32_t i5 = lane & 1u, i6 = (lane >> 1) & 1u, i0i1 = (lane >> 2) & 3u, i2 = (lane >> 4) & 1u,
+                   i3 = (lane >> 5) & 1u;
+    const uint32_t i4 = wave & 1u, i7i8 = wave >> 1;
+    return i0i1 | (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7i8 << 7) | (rho << 9);
+}
+// reader (L4d): wave = i8..i10, lane = i2..i7, loads registers (i0,i1) of group h = (i11..i13) as 128 bits
+THC_HD uint32_t x3d_load(uint32_t wave, uint32_t lane, uint32_t h) {  // h = 0..7
+    const uint32_t i2 = lane & 1u, i3 = (lane >> 1) & 1u, i4 = (lane >> 2) & 1u, i5 = (lane >> 3) & 1u,
+                   i6 = (lane >> 4) & 1u, i7 = (lane >> 5) & 1u;
+    const uint32_t i8 = wave & 1u, i9i10 = wave >> 1;
+    return (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7 << 7) | (i8 << 8) |
+           (i9i10 << 9) | (h << 11);
 }
 
 }  // namespace lay14

@@ -1,0 +1,116 @@
+// Host check of the LDS address maps of the chunk-2^14 kernels: for every exchange, each
+// coordinate is written and read at the same address, the map is a bijection, the 128-bit
+// side puts 8 consecutive lanes on 8 distinct 16-byte bank groups and the 32-bit side puts
+// 32 consecutive lanes on 32 distinct banks.  Compiled and run by tests/test_layout_host.py.
+#include <cstdio>
+#include <set>
+#include <vector>
+
+#include "thc_layout14.h"
+
+using namespace thc::lay14;
+
+static int bad = 0;
+#define CHECK(c, ...) do { if (!(c)) { if (bad < 20) { printf(__VA_ARGS__); printf("\n"); } ++bad; } } while (0)
+
+static uint32_t bit(uint32_t i, int k) { return (i >> k) & 1u; }
+static uint32_t bits(uint32_t i, int lo, int n) { return (i >> lo) & ((1u << n) - 1u); }
+
+// coordinates of position i in each layout
+struct Pos { uint32_t wave, lane, reg; };
+static Pos L1(uint32_t i) { return {bits(i, 11, 3), bits(i, 5, 6), bits(i, 0, 5)}; }
+static Pos L2(uint32_t i) { return {bits(i, 11, 3), bits(i, 0, 5) | (bit(i, 10) << 5), bits(i, 5, 5)}; }
+static Pos L3(uint32_t i) {
+    const uint32_t lane = bit(i, 5) | (bit(i, 6) << 1) | (bits(i, 0, 4) << 2);
+    const uint32_t wave = bit(i, 4) | (bits(i, 7, 2) << 1);
+    return {wave, lane, bits(i, 9, 5)};
+}
+static Pos L4d(uint32_t i) { return {bits(i, 8, 3), bits(i, 2, 6), bits(i, 0, 2) | (bits(i, 11, 3) << 2)}; }
+
+template <typename F>
+static void conflict_128(const char* what, F addr_of_lane) {   // F(lane) -> dword address of a 16-byte access
+    for (int g = 0; g < 64; g += 8) {
+        std::set<uint32_t> s;
+        for (int l = g; l < g + 8; ++l) {
+            CHECK(addr_of_lane(l) % 4 == 0, "%s: unaligned 128-bit access", what);
+            s.insert((addr_of_lane(l) >> 2) & 7u);
+        }
+        CHECK(s.size() == 8, "%s: 128-bit bank-group conflict in lanes %d..%d", what, g, g + 7);
+    }
+}
+template <typename F>
+static void conflict_32(const char* what, F addr_of_lane) {
+    for (int g = 0; g < 64; g += 32) {
+        std::set<uint32_t> s;
+        for (int l = g; l < g + 32; ++l) s.insert(addr_of_lane(l) & 31u);
+        CHECK(s.size() == 32, "%s: 32-bit bank conflict in lanes %d..%d", what, g, g + 31);
+    }
+}
+
+int main() {
+    // ---- X1 (per wave, 2048 dwords)
+    {
+        std::set<uint32_t> seen;
+        for (uint32_t i = 0; i < 2048; ++i) {
+            const Pos w = L1(i), r = L2(i);
+            const uint32_t wa = x1_store(w.lane, w.reg >> 2) + (w.reg & 3u);
+            const uint32_t ra = x1_load(r.lane, r.reg);
+            CHECK(wa == ra, "X1 mismatch at %u", i);
+            CHECK(wa < 2048, "X1 out of range");
+            seen.insert(wa);
+        }
+        CHECK(seen.size() == 2048, "X1 not a bijection");
+        for (uint32_t q = 0; q < 8; ++q) conflict_128("X1 store", [&](int l) { return x1_store(l, q); });
+        for (uint32_t r = 0; r < 32; ++r) conflict_32("X1 load", [&](int l) { return x1_load(l, r); });
+    }
+    // ---- X2, X3e, X3d (whole chunk)
+    {
+        std::set<uint32_t> s2, s3e, s3d;
+        for (uint32_t i = 0; i < 16384; ++i) {
+            const Pos a = L2(i), b = L3(i), c = L1(i), d = L4d(i);
+            const uint32_t w2 = x2_store(a.wave, a.lane, a.reg >> 2) + (a.reg & 3u);
+            CHECK(w2 == x2_load(b.wave, b.lane, b.reg), "X2 mismatch at %u", i);
+            const uint32_t w3e = x3e_store(b.wave, b.lane, b.reg);
+            CHECK(w3e == x3e_load(c.wave, c.lane, c.reg >> 2) + (c.reg & 3u), "X3e mismatch at %u", i);
+            const uint32_t w3d = x3d_store(b.wave, b.lane, b.reg);
+            CHECK(w3d == x3d_load(d.wave, d.lane, d.reg >> 2) + (d.reg & 3u), "X3d mismatch at %u", i);
+            CHECK(w2 < 16384 && w3e < 16384 && w3d < 16384, "out of range");
+            s2.insert(w2); s3e.insert(w3e); s3d.insert(w3d);
+        }
+        CHECK(s2.size() == 16384 && s3e.size() == 16384 && s3d.size() == 16384, "not a bijection");
+        for (uint32_t wv = 0; wv < 8; ++wv) {
+            for (uint32_t q = 0; q < 8; ++q) {
+                conflict_128("X2 store", [&](int l) { return x2_store(wv, l, q); });
+                conflict_128("X3e load", [&](int l) { return x3e_load(wv, l, q); });
+                conflict_128("X3d load", [&](int l) { return x3d_load(wv, l, q); });
+            }
+            for (uint32_t r = 0; r < 32; ++r) {
+                conflict_32("X2 load", [&](int l) { return x2_load(wv, l, r); });
+                conflict_32("X3e store", [&](int l) { return x3e_store(wv, l, r); });
+                conflict_32("X3d store", [&](int l) { return x3d_store(wv, l, r); });
+            }
+        }
+    }
+    // ---- E0 (units of 16 bytes)
+    for (uint32_t per : {4u, 8u}) {
+        const uint32_t nunits = per == 4 ? 2048 : 4096;
+        std::vector<int> where(nunits, -1);
+        for (uint32_t j = 0; j < nunits / 512; ++j)
+            for (uint32_t t = 0; t < 512; ++t) {
+                const uint32_t ua = e0_store_unit(t, j, per);
+                CHECK(ua < nunits && where[ua] < 0, "E0 store collision");
+                where[ua] = (int)(j * 512 + t);
+            }
+        for (uint32_t T = 0; T < 512; ++T)
+            for (uint32_t k = 0; k < per; ++k)
+                CHECK(where[e0_load_unit(T, k, per)] == (int)(per * T + k), "E0 mismatch per=%u T=%u k=%u", per, T, k);
+        for (uint32_t wv = 0; wv < 8; ++wv) {
+            for (uint32_t j = 0; j < nunits / 512; ++j)
+                conflict_128("E0 store", [&](int l) { return e0_store_unit(wv * 64 + l, j, per) << 2; });
+            for (uint32_t k = 0; k < per; ++k)
+                conflict_128("E0 load", [&](int l) { return e0_load_unit(wv * 64 + l, k, per) << 2; });
+        }
+    }
+    printf("layout check: %d problems\n", bad);
+    return bad != 0;
+}
