@@ -12,8 +12,14 @@ rotation (thc_aggregate_decode).  --unfused times the one-call-per-step form
 
 Prints ONE JSON line: gradient throughput (bytes of worker gradients consumed per
 second), the roofline of the dominant kernel (algorithmic bytes per launch / measured
-launch duration against 8 TB/s) and the CPU oracle timed on a bounded slice of the
-same inputs.
+launch duration against 8 TB/s; the same kernel's algorithmic arithmetic against the
+plain-VALU issue rate is given beside it), and the CPU oracle timed on a bounded slice
+of the same inputs.
+
+    python bench.py --probe      a few launches of each kernel of the first bucket plus a
+                                 device-to-device copy of known size; meant to run under
+                                 rocprofv3 --pmc so that counter readings of the kernels
+                                 can be scaled by what the same counter reads for the copy
 """
 import argparse
 import json
@@ -26,17 +32,30 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# Plain (unpacked, unfused) VALU issue rate: 256 CUs x 4 SIMDs x 16 lanes per clock at
+# 2.4 GHz.  The published 157.3 TFLOP/s fp32 vector figure is this rate x 2 (FMA) x 2
+# (packed fp32); the path's separately rounded adds, subtracts and integer ops can use
+# neither.
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# Arithmetic the method asks for per worker-coordinate of the encode step at chunk 2^14:
+# sign flip, 14 butterfly stages, normalisation, range, six quantizer ops, and one
+# Philox4x32-10 block (10 rounds of 2 wide multiplies + 4 xors, 18 key additions) per 16
+# coordinates.
+ENCODE_OPS_PER_COORD = 1 + 14 + 1 + 1 + 6 + (10 * 6 + 18) / 16.0
+PROBE_COPY_BYTES = 1 << 29
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt_1p3b")
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="few launches + a copy of known size, for rocprofv3 --pmc runs")
     ap.add_argument("--cpu-sample-log2", type=int, default=23,
                     help="coordinates per worker of the slice the CPU oracle is timed on (log2)")
     return ap.parse_args()
@@ -146,6 +165,29 @@ def cpu_baseline(wl, bits, xs, log2_sample):
                        f"({dt:.1f} s of NumPy, one thread)")
 
 
+def copy_bandwidth(torch, dev):
+    """GB/s of HBM traffic (read + write) of a plain device-to-device copy of 1 GiB."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ms = time_region(torch, lambda: dst.copy_(src), 10)
+    return 2.0 * src.numel() * 4 / (ms * 1e-3) / 1e9
+
+
+def probe(torch, path, dev):
+    """Three launches of every kernel of the first bucket and three copies of
+    PROBE_COPY_BYTES bytes (one elementwise kernel each)."""
+    it = path.items[0]
+    src = torch.empty(PROBE_COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        for fn, _ in path.phases.values():
+            fn(it)
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"probe": "ok", "bucket_elems": it["ln"], "copy_bytes": PROBE_COPY_BYTES}))
+
+
 def read_traffic(workload_name, bits, kernel):
     """HBM bytes per launch of a kernel, measured offline with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
@@ -183,6 +225,18 @@ def main():
     xs = [generate(wl, w, dev) for w in range(W)]
     path = Path(thc, torch, wl, bits, xs, fused=not a.unfused)
     torch.cuda.synchronize()
+    if a.probe:
+        probe(torch, path, dev)
+        return 0
+
+    # Setup, untimed: first touch of every buffer and time for the device to leave its
+    # idle power state (the first ~100 ms of work after start-up run at lower clocks).
+    path.step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter() + 0.5
+    while time.perf_counter() < t_end:
+        path.step()
+        torch.cuda.synchronize()
 
     for _ in range(a.warmup):
         path.step()
@@ -212,11 +266,15 @@ def main():
     dom_s = kernels[path.dominant]["us_per_launch"] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
 
+    dom_ops = coords_per_launch * (W if path.fused else 1) * ENCODE_OPS_PER_COORD
+    alu_achieved = dom_ops / dom_s / 1e12
+    copy_gbs = copy_bandwidth(torch, dev)
+
     sb = path.sum_bytes
     alg_bytes_per_coord = W * (s_in + bits / 8.0) + W * bits / 8.0 + 2 * sb + 4
     value = W * wl.n * s_in / (ms * 1e-3) / 1e9
     res = {
-        "metric": "gradient GB/s for encode+aggregate+decode (W workers), 1 GPU",
+        "metric": "gradient GB/s for encode+aggregate+decode (W workers) and % of HBM peak, 1 GPU",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -226,9 +284,16 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(wl.name, bits, dom_name)},
+        "roofline_alu": {"bound": "alu", "kernel": dom_name, "achieved": round(alu_achieved, 2),
+                         "peak": round(VALU_PEAK_TOPS, 2), "unit": "Top/s",
+                         "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
+                         "ops_per_worker_coord": ENCODE_OPS_PER_COORD},
+        "pct_hbm_peak": round(100.0 * wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "copy_GBps": round(copy_gbs, 1),
         "pipeline_hbm": {"algorithmic_bytes_per_coord": alg_bytes_per_coord,
                          "achieved_GBps": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9, 1),
-                         "frac_of_peak": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                         "frac_of_peak": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "frac_of_copy": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / copy_gbs, 4)},
         "kernels": kernels,
     }
     if not a.no_cpu_baseline:

@@ -22,11 +22,14 @@ constexpr int kChunk = 1 << kChunkLog2;
 constexpr int kRegs = 32;                 // coordinates per thread
 constexpr float kInvSqrtC = 0.0078125f;   // 2^-7, exact
 
-struct alignas(16) Shared {
-    float xb[kChunk];            // exchange buffer, 64 KB
-    uint32_t sgn[kChunk / 32];   // sign diagonal of the chunk, bit (i mod 32) of word i / 32
+struct alignas(16) SignTable {
+    uint32_t sgn[kChunk / 32];   // sign diagonal of a chunk, bit (i mod 32) of word i / 32
     uint32_t sgx[kChunk / 32];   // the same words with even bits gathered in the low half,
                                  // odd bits in the high half (for bf16 pairs)
+};
+struct alignas(16) Shared {
+    float xb[kChunk];            // exchange buffer, 64 KB
+    SignTable sign[2];           // persistent kernels fill the next chunk's table ahead of time
     float red[8];                // one slot per wave for workgroup-wide reductions
 };
 
@@ -59,19 +62,23 @@ __device__ __forceinline__ uint32_t unshuffle_bits(uint32_t x) {
 
 // 128 threads compute the 16384 sign bits of the chunk that starts at coordinate g0
 // (a multiple of 16384).  Needs a barrier before use.
-__device__ __forceinline__ void fill_sign_table(Shared& sh, uint64_t g0, uint32_t key0,
+__device__ __forceinline__ void fill_sign_table(SignTable& tab, uint64_t g0, uint32_t key0,
                                                 uint32_t key1, uint32_t t) {
     if (t < kChunk / 128) {
         const u32x4 s = sign_block((g0 >> 7) + t, key0, key1);
-        *reinterpret_cast<uint4*>(&sh.sgn[4 * t]) = make_uint4(s.w[0], s.w[1], s.w[2], s.w[3]);
-        *reinterpret_cast<uint4*>(&sh.sgx[4 * t]) =
+        *reinterpret_cast<uint4*>(&tab.sgn[4 * t]) = make_uint4(s.w[0], s.w[1], s.w[2], s.w[3]);
+        *reinterpret_cast<uint4*>(&tab.sgx[4 * t]) =
             make_uint4(unshuffle_bits(s.w[0]), unshuffle_bits(s.w[1]), unshuffle_bits(s.w[2]),
                        unshuffle_bits(s.w[3]));
     }
 }
 
 // ---------------------------------------------------------------- input -> layout L1
-// Raw 16-byte units in load order (thread t, round j holds unit 512 j + t).
+// Raw 16-byte units of a chunk in load order.  Coalesced order: thread t, round j holds
+// unit 512 j + t, and the chunk passes through LDS to reach layout L1.  Direct order:
+// thread t holds units UNITS t + j, its own 32 consecutive coordinates (layout L1 at
+// once; every load instruction of a wave then touches UNITS times as many cache lines,
+// each of which the wave's other loads hit again in the vector cache).
 template <int UNITS>  // 4 for bf16, 8 for fp32
 struct Raw {
     uint4 u[UNITS];
@@ -79,18 +86,18 @@ struct Raw {
 
 // Coalesced loads of one chunk.  `valid` = number of coordinates of this chunk that
 // exist (1..16384); the rest read as zero.  ELEM = bytes per coordinate.
-template <int UNITS, int ELEM>
+template <int UNITS, int ELEM, bool DIRECT = false>
 __device__ __forceinline__ void load_raw(Raw<UNITS>& raw, const void* chunk_ptr, uint32_t valid,
                                          uint32_t t) {
     constexpr uint32_t kPerUnit = 16 / ELEM;
     const uint4* src = static_cast<const uint4*>(chunk_ptr);
     if (valid == (uint32_t)kChunk) {
 #pragma unroll
-        for (int j = 0; j < UNITS; ++j) raw.u[j] = src[j * kThreads + t];
+        for (int j = 0; j < UNITS; ++j) raw.u[j] = src[DIRECT ? UNITS * t + j : j * kThreads + t];
     } else {
 #pragma unroll
         for (int j = 0; j < UNITS; ++j) {
-            const uint32_t unit = j * kThreads + t;
+            const uint32_t unit = DIRECT ? UNITS * t + j : j * kThreads + t;
             const uint32_t first = unit * kPerUnit;
             uint4 q = make_uint4(0u, 0u, 0u, 0u);
             if (first + kPerUnit <= valid) {
@@ -118,17 +125,16 @@ __device__ __forceinline__ void raw_to_lds(Shared& sh, const Raw<UNITS>& raw, ui
     for (int j = 0; j < UNITS; ++j) dst[j * kThreads] = raw.u[j];
 }
 
-// Reads this thread's 32 consecutive coordinates back (layout L1), widens bf16,
-// and applies the sign diagonal when SIGNED.
+// The thread's 32 consecutive coordinates as UNITS 16-byte units -> fp32 registers
+// (layout L1): widens bf16 and applies the sign diagonal when SIGNED.
 template <int UNITS, bool SIGNED>
-__device__ __forceinline__ void lds_to_l1(const Shared& sh, float (&v)[kRegs], uint32_t t) {
-    const uint4* src = reinterpret_cast<const uint4*>(sh.xb);
+__device__ __forceinline__ void units_to_l1(const SignTable& tab, const uint4 (&unit)[UNITS],
+                                            float (&v)[kRegs], uint32_t t) {
     if (UNITS == 4) {  // bf16: 8 coordinates per unit, two per dword
-        const uint32_t sx = SIGNED ? sh.sgx[t] : 0u;
+        const uint32_t sx = SIGNED ? tab.sgx[t] : 0u;
 #pragma unroll
         for (int k = 0; k < UNITS; ++k) {
-            const uint4 q = src[lay14::e0_load_unit(t, k, UNITS)];
-            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+            const uint32_t w[4] = {unit[k].x, unit[k].y, unit[k].z, unit[k].w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int pair = 4 * k + d;  // coordinates 2 pair, 2 pair + 1
@@ -140,11 +146,10 @@ __device__ __forceinline__ void lds_to_l1(const Shared& sh, float (&v)[kRegs], u
             }
         }
     } else {  // fp32: 4 coordinates per unit
-        const uint32_t sw = SIGNED ? sh.sgn[t] : 0u;
+        const uint32_t sw = SIGNED ? tab.sgn[t] : 0u;
 #pragma unroll
         for (int k = 0; k < UNITS; ++k) {
-            const uint4 q = src[lay14::e0_load_unit(t, k, UNITS)];
-            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+            const uint32_t w[4] = {unit[k].x, unit[k].y, unit[k].z, unit[k].w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int r = 4 * k + d;
@@ -154,6 +159,18 @@ __device__ __forceinline__ void lds_to_l1(const Shared& sh, float (&v)[kRegs], u
             }
         }
     }
+}
+
+// Reads this thread's 32 consecutive coordinates back from the buffer (after raw_to_lds
+// and a barrier) into layout L1.
+template <int UNITS, bool SIGNED>
+__device__ __forceinline__ void lds_to_l1(const Shared& sh, const SignTable& tab, float (&v)[kRegs],
+                                          uint32_t t) {
+    const uint4* src = reinterpret_cast<const uint4*>(sh.xb);
+    uint4 unit[UNITS];
+#pragma unroll
+    for (int k = 0; k < UNITS; ++k) unit[k] = src[lay14::e0_load_unit(t, k, UNITS)];
+    units_to_l1<UNITS, SIGNED>(tab, unit, v, t);
 }
 
 // ------------------------------------------------------------------ LDS exchanges
@@ -215,8 +232,10 @@ __device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], u
                                                 uint32_t wave) {
     butterflies<0, 5>(v);          // strides 1..16
     __syncthreads();
+    // the first exchange stays inside each wave's own 8 KB of the buffer, and a wave's
+    // LDS accesses execute in order: no barrier between its stores and loads
     x1_store(sh, v, lane, wave);
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     x1_load(sh, v, lane, wave);
     butterflies<0, 5>(v);          // strides 32..512
     __syncthreads();
@@ -269,15 +288,18 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 // packed and stored.  v holds the UNNORMALISED rotation; y = v * 2^-7.
 //   g0       global index of the chunk's first coordinate
 //   payload  start of this worker's payload
-template <int BITS>
-__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint64_t g0,
-                                               uint32_t worker, uint32_t key0, uint32_t key1,
-                                               uint8_t* payload, uint32_t t) {
+//   CLAMP    false only when s is the largest |y| of the chunk: then floor(t) <= L holds
+//            for every coordinate (t <= fl(L (1 + 2^-24)) + 255.5 / 256 < L + 1) and the
+//            minimum with L never binds
+//
+// FOLD: y = v * 2^-7 followed by (y + s) * inv equals (v + 2^7 s) * (2^-7 inv) bit for bit
+// as long as the power-of-two factors move no operand into or out of the subnormal or
+// overflow range, which 2^-100 <= s <= 2^100 guarantees; other chunks take the plain form.
+template <int BITS, bool CLAMP, bool FOLD>
+__device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add, float mul, uint64_t g,
+                                              uint32_t worker, uint32_t key0, uint32_t key1,
+                                              uint32_t (&pk)[BITS]) {
     constexpr uint32_t L = (1u << BITS) - 1u;
-    const float two = s + s;
-    const float inv = two != 0.0f ? (float)L / two : 0.0f;
-    const uint64_t g = g0 + (uint64_t)t * 32u;
-    uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
 #pragma unroll
     for (int i = 0; i < BITS; ++i) pk[i] = 0u;
 #pragma unroll
@@ -286,17 +308,32 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int r = 16 * half + e;
-            const float y = v[r] * kInvSqrtC;
-            const float pos = (y + s) * inv;
+            const float y = FOLD ? v[r] : v[r] * kInvSqrtC;
+            const float pos = (y + add) * mul;
             const uint32_t rnd = (rb.w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
             const float u = __builtin_fmaf((float)rnd, 0x1p-8f, 0x1p-9f);   // (r + 0.5) / 256, exact
             const float tt = pos + u;
             uint32_t q = (uint32_t)tt;                                       // tt >= 0: truncation = floor
-            q = q < L ? q : L;
+            if (CLAMP) q = q < L ? q : L;
             const int bit = r * BITS;
             pk[bit >> 5] |= q << (bit & 31);
         }
     }
+}
+
+template <int BITS, bool CLAMP>
+__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint64_t g0,
+                                               uint32_t worker, uint32_t key0, uint32_t key1,
+                                               uint8_t* payload, uint32_t t) {
+    constexpr uint32_t L = (1u << BITS) - 1u;
+    const float two = s + s;
+    const float inv = two != 0.0f ? (float)L / two : 0.0f;
+    const uint64_t g = g0 + (uint64_t)t * 32u;
+    uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
+    if (s >= 0x1p-100f && s <= 0x1p100f)   // the same for every thread of the workgroup
+        quantize_pack<BITS, CLAMP, true>(v, s * 128.0f, inv * kInvSqrtC, g, worker, key0, key1, pk);
+    else
+        quantize_pack<BITS, CLAMP, false>(v, s, inv, g, worker, key0, key1, pk);
     uint8_t* dst = payload + (g * BITS) / 8u;
     if (BITS == 8) {
         reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
@@ -310,12 +347,12 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
 
 // Output side of the inverse rotation: x = D (v * 2^-7) from layout L4d; the first
 // `valid` coordinates of the chunk are stored.
-__device__ __forceinline__ void store_signed_l4d(const Shared& sh, const float (&v)[kRegs], float* out,
+__device__ __forceinline__ void store_signed_l4d(const SignTable& tab, const float (&v)[kRegs], float* out,
                                                  uint32_t valid, uint32_t t) {
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
         const uint32_t i0 = h * 2048u + t * 4u;
-        const uint32_t sb = sh.sgn[i0 >> 5] >> (i0 & 31u);   // bits 0..3: signs of the 4 coordinates
+        const uint32_t sb = tab.sgn[i0 >> 5] >> (i0 & 31u);   // bits 0..3: signs of the 4 coordinates
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)

@@ -25,45 +25,56 @@ constexpr uint32_t kWaves = kThreads / 64;
 // Second argument of __launch_bounds__ (waves per SIMD the compiler must allow): two
 // workgroups of 8 waves per CU = 4 waves on each of the 4 SIMDs = at most 128 VGPRs.
 constexpr int kWavesPerSimd = 4;
-// encode_all can keep two items in flight per workgroup (front half of item k+1 between
-// the publish and the wait of item k).  With four waves per SIMD the other workgroup on
-// the CU already covers the wait, and one item in flight keeps the kernel out of scratch.
-constexpr bool kTwoInFlight = false;
-
 // ------------------------------------------------------------------ encode_all
 template <bool BF16>
 struct EncodeAllCtx {
     static constexpr int kUnits = BF16 ? 4 : 8;
     static constexpr int kElem = BF16 ? 2 : 4;
-    static constexpr bool kPrefetch = BF16;   // load the next item's input one item ahead
+    // bf16: every thread loads its own 64 consecutive bytes one item ahead, so the input
+    // never crosses LDS.  fp32 (128 bytes per thread, 32 registers in flight) loads in
+    // coalesced order when the item starts and goes through the buffer.
+    static constexpr bool kDirect = BF16;
     const EncodeAllArgs& a;
     const FusedWorkerPtrs& ptrs;
     Shared& sh;
     Raw<kUnits> raw;        // input of the next item to enter the pipeline, in flight
-    uint32_t t, lane, wave, total, G, nwords;
+    uint32_t t, lane, wave, nwords;
+    uint32_t w;             // worker of every item of this workgroup (the grid is a multiple of W)
+    uint32_t dp;            // chunk stride between consecutive items of this workgroup
+    uint32_t parity;        // which sign table the next front() reads
 
-    __device__ __forceinline__ void prefetch(uint32_t item) {
-        const uint32_t p = item / a.W, w = item - p * a.W;
+    __device__ __forceinline__ void load(uint32_t p) {
         const uint64_t g0 = (uint64_t)p << kChunkLog2;
         const uint64_t left = a.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-        load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem, valid, t);
+        load_raw<kUnits, kElem, kDirect>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem,
+                                         valid, t);
+    }
+    __device__ __forceinline__ void fill_signs(uint32_t p, uint32_t which) {
+        fill_sign_table(sh.sign[which], (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
     }
 
-    // Front half of an item: stage the prefetched input, rotate, publish this wave's share
-    // of the chunk's range, and bring the chunk into the quantizer's layout.  Also starts
-    // the loads of the item after it.
-    __device__ __forceinline__ void front(float (&v)[kRegs], uint32_t item) {
-        const uint32_t p = item / a.W, w = item - p * a.W;
-        // fp32 input is 32 registers per thread in flight; loading it here instead of one
-        // item ahead keeps the kernel out of scratch
-        if (!kPrefetch) prefetch(item);
-        __syncthreads();   // the previous item's last reads of the buffer are done
-        fill_sign_table(sh, (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
-        raw_to_lds<kUnits>(sh, raw, t);
-        __syncthreads();
-        lds_to_l1<kUnits, true>(sh, v, t);
-        if (kPrefetch && item + G < total) prefetch(item + G);
+    // Front half of an item: bring the input into registers (layout L1), rotate, publish
+    // this wave's share of the chunk's range, and bring the chunk into the quantizer's
+    // layout.  The direct form also fills the sign table of the workgroup's next item,
+    // which is read only after the barriers of this item's exchanges.
+    __device__ __forceinline__ void front(float (&v)[kRegs], uint32_t p) {
+        const bool more = (uint64_t)p + dp < a.chunks;
+        if (kDirect) {
+            units_to_l1<kUnits, true>(sh.sign[parity], raw.u, v, t);
+            if (more) {
+                load(p + dp);
+                fill_signs(p + dp, parity ^ 1u);
+            }
+            parity ^= 1u;
+        } else {
+            load(p);
+            __syncthreads();   // the previous item's last reads of the buffer and table are done
+            fill_signs(p, 0u);
+            raw_to_lds<kUnits>(sh, raw, t);
+            __syncthreads();
+            lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
+        }
         rotate_l1_to_l3(sh, v, lane, wave);
         const float m = wave_absmax(v) * kInvSqrtC;
         // One word per wave, value | valid bit (non-negative floats order like their bit
@@ -81,8 +92,7 @@ struct EncodeAllCtx {
     // the largest value as the shared scale, quantize and store.  The wait is bounded:
     // on time-out the error word is set and the wave carries on.
     template <int BITS>
-    __device__ __forceinline__ void back(const float (&v)[kRegs], uint32_t item) {
-        const uint32_t p = item / a.W, w = item - p * a.W;
+    __device__ __forceinline__ void back(const float (&v)[kRegs], uint32_t p) {
         const uint32_t* slot = a.slots + (uint64_t)p * nwords;
         uint32_t sbits = 0u;
         for (uint32_t spins = 0;; ++spins) {
@@ -112,46 +122,31 @@ struct EncodeAllCtx {
         }
         const float s = __uint_as_float(sbits);
         if (w == 0 && t == 0) a.scale[p] = s;
-        quantize_store<BITS>(v, s, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        quantize_store<BITS, false>(v, s, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
     }
 };
 
-// Two items are in flight per workgroup: the front half of item k+1 (rotation, publish)
-// runs between the publish of item k and the wait for item k's peers, so the round trip
-// of the publish/poll through memory is covered by useful work.  Item k waits only for
-// publishes that its peers issue before their own waits on earlier items, so with every
-// workgroup of the grid resident there is no circular wait.
+// Items are (chunk, worker) pairs; workgroup g of a grid of G (a multiple of W) takes worker
+// g mod W of chunks g / W, g / W + G / W, ...  The peers of an item are therefore items of
+// the same round of other workgroups, and with every workgroup resident no wait is circular.
 template <bool BF16, int BITS>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
                                                                  const FusedWorkerPtrs ptrs) {
     __shared__ Shared sh;
     const uint32_t t = threadIdx.x;
-    EncodeAllCtx<BF16> c{a, ptrs, sh, {}, t, t & 63u, t >> 6, (uint32_t)a.chunks * a.W, gridDim.x,
-                         kWaves * a.W};
-    uint32_t item = blockIdx.x;
-    if (item >= c.total) return;
-    if (EncodeAllCtx<BF16>::kPrefetch) c.prefetch(item);
-    if constexpr (kTwoInFlight) {
-        float va[kRegs], vb[kRegs];
-        c.front(va, item);
-        for (;;) {
-            const bool has_b = item + c.G < c.total;
-            if (has_b) c.front(vb, item + c.G);
-            c.template back<BITS>(va, item);
-            if (!has_b) break;
-            item += c.G;
-            const bool has_a = item + c.G < c.total;
-            if (has_a) c.front(va, item + c.G);
-            c.template back<BITS>(vb, item);
-            if (!has_a) break;
-            item += c.G;
-        }
-    } else {
-        for (; item < c.total; item += c.G) {
-            float v[kRegs];
-            c.front(v, item);
-            c.template back<BITS>(v, item);
-        }
+    const uint32_t p0 = blockIdx.x / a.W;
+    EncodeAllCtx<BF16> c{a, ptrs, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
+                         gridDim.x / a.W, 0u};
+    if (p0 >= a.chunks) return;
+    if (EncodeAllCtx<BF16>::kDirect) {
+        c.load(p0);
+        c.fill_signs(p0, 0u);
+        __syncthreads();
+    }
+    for (uint64_t p = p0; p < a.chunks; p += c.dp) {
+        float v[kRegs];
+        c.front(v, (uint32_t)p);
+        c.template back<BITS>(v, (uint32_t)p);
     }
 }
 
@@ -203,7 +198,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         const uint64_t left = a.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
         __syncthreads();   // the previous item's last reads of the buffer and sign table are done
-        fill_sign_table(sh, g0, a.key0, a.key1, t);
+        fill_sign_table(sh.sign[0], g0, a.key0, a.key1, t);
 
         uint32_t acc[kWords][kLanes];
 #pragma unroll
@@ -275,7 +270,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         }
         rotate_l1_to_l3(sh, v, lane, wave);
         l3_to_l4d(sh, v, lane, wave);
-        store_signed_l4d(sh, v, a.out + g0, valid, t);
+        store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
     }
 }
 

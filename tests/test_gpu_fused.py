@@ -52,6 +52,30 @@ def test_fused_path_matches_oracle_and_unfused(l, bits, W, dtype, chunks):
                                      torch.empty(n, device=DEV))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_scales_outside_and_across_the_folded_range(dtype, bits):
+    """Chunks whose scale is tiny (2^-110), huge (2^105) or ordinary side by side: the
+    kernels fold the 2^-7 normalisation into the quantizer's constants only where that
+    is exact, and both forms must reproduce the oracle bit for bit."""
+    l, W, c = 14, 3, 1 << 14
+    mags = [2.0 ** -110, 1.0, 2.0 ** 105, 2.0 ** -101, 2.0 ** 99, 2.0 ** -120]
+    n = len(mags) * c - 100
+    xs = []
+    for w in range(W):
+        x = _rand(n, torch.float32, 900 + w, scale=1.0)
+        for k, m in enumerate(mags):
+            x[k * c:(k + 1) * c] *= m
+        xs.append(x.to(dtype))
+    print(f"extreme scales dtype={dtype} bits={bits}", flush=True)
+    fused = run_path_fused(xs, l, 5, bits)
+    check_against_oracle(xs, fused, l, 5, bits)
+    plain = run_path(xs, l, 5, bits)
+    for a, b in zip(fused["payloads"], plain["payloads"]):
+        assert torch.equal(a, b)
+    assert torch.equal(fused["out"], plain["out"])
+
+
 def test_is_fused_predicate():
     assert thc.thc_aggregate_decode_is_fused(8, 14, 4)
     assert thc.thc_aggregate_decode_is_fused(17, 14, 4)
