@@ -56,7 +56,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="few launches + a copy of known size, for rocprofv3 --pmc runs")
-    ap.add_argument("--cpu-sample-log2", type=int, default=23,
+    ap.add_argument("--cpu-sample-log2", type=int, default=25,
                     help="coordinates per worker of the slice the CPU oracle is timed on (log2)")
     return ap.parse_args()
 
