@@ -12,8 +12,8 @@
 //   L4d  register = i0, i1, i11..i13   lane = i2..i7   wave = i8..i10   (coalesced fp32 store)
 //
 // Eight waves per chunk keep four waves resident per SIMD with two chunks per CU in
-// flight (LDS holds one 64 KB chunk per workgroup), which the VALU needs to run its
-// double-rate fp32/logic instructions back to back.
+// flight (LDS holds one 64 KB chunk per workgroup), so that one chunk's LDS exchanges and
+// barriers overlap the other's vector arithmetic.
 //
 // Every map is a bijection of the index bits onto dword addresses such that the 128-bit
 // side of an exchange has 8 consecutive lanes on 8 distinct 16-byte bank groups and the
