@@ -27,15 +27,15 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
 
     Raw<kUnits> raw;
     load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(a.in) + g0 * kElem, valid, t);
-    fill_sign_table(sh.sign[0], g0, a.key0, a.key1, t);
+    fill_sign_table<!BF16, BF16>(sh.sign[0], g0, a.key0, a.key1, t);
     raw_to_lds<kUnits>(sh, raw, t);
     __syncthreads();
     float v[kRegs];
     lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
-    rotate_l1_to_l3(sh, v, lane, wave);
+    rotate_l1_to_l3<false>(sh, v, lane, wave);
 
     if constexpr (MODE == Mode::Forward) {
-        l3_to_l4d(sh, v, lane, wave);
+        l3_to_l4d<false>(sh, v, lane, wave);
         float* y = static_cast<float*>(a.out) + g0;
 #pragma unroll
         for (int h = 0; h < 8; ++h)
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
             s = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
         }
         if (a.scale_out && t == 0) a.scale_out[p] = s;
-        l3_to_l4e(sh, v, lane, wave);
+        l3_to_l4e<false>(sh, v, lane, wave);
         quantize_store<BITS, true>(v, s, g0, a.worker, a.key0, a.key1, static_cast<uint8_t*>(a.out), t);
     }
 }
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     const uint64_t left = a.n - g0;
     const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
     float v[kRegs];
-    fill_sign_table(sh.sign[0], g0, a.key0, a.key1, t);
+    fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
     if constexpr (SRC == 0) {
         Raw<8> raw;   // y is complete (padded), so every unit exists
         load_raw<8, 4>(raw, static_cast<const float*>(a.in) + g0, (uint32_t)kChunk, t);
@@ -106,8 +106,8 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
             }
         }
     }
-    rotate_l1_to_l3(sh, v, lane, wave);
-    l3_to_l4d(sh, v, lane, wave);
+    rotate_l1_to_l3<false>(sh, v, lane, wave);
+    l3_to_l4d<false>(sh, v, lane, wave);
     store_signed_l4d(sh.sign[0], v, static_cast<float*>(a.out) + g0, valid, t);
 }
 

@@ -51,7 +51,7 @@ struct EncodeAllCtx {
                                          valid, t);
     }
     __device__ __forceinline__ void fill_signs(uint32_t p, uint32_t which) {
-        fill_sign_table(sh.sign[which], (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
+        fill_sign_table<!BF16, BF16>(sh.sign[which], (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
     }
 
     // Front half of an item: bring the input into registers (layout L1), rotate, publish
@@ -75,7 +75,7 @@ struct EncodeAllCtx {
             __syncthreads();
             lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
         }
-        rotate_l1_to_l3(sh, v, lane, wave);
+        rotate_l1_to_l3<true>(sh, v, lane, wave);
         const float m = wave_absmax(v) * kInvSqrtC;
         // One word per wave, value | valid bit (non-negative floats order like their bit
         // patterns and leave bit 31 free).  The words travel between workgroups only
@@ -85,7 +85,7 @@ struct EncodeAllCtx {
             __hip_atomic_store(&a.slots[(uint64_t)p * nwords + kWaves * w + wave],
                                __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        l3_to_l4e(sh, v, lane, wave);
+        l3_to_l4e<true>(sh, v, lane, wave);
     }
 
     // Back half: wait until every wave of every worker of the chunk has published, take
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         const uint64_t left = a.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
         __syncthreads();   // the previous item's last reads of the buffer and sign table are done
-        fill_sign_table(sh.sign[0], g0, a.key0, a.key1, t);
+        fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
 
         uint32_t acc[kWords][kLanes];
 #pragma unroll
@@ -268,8 +268,8 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
                 }
             }
         }
-        rotate_l1_to_l3(sh, v, lane, wave);
-        l3_to_l4d(sh, v, lane, wave);
+        rotate_l1_to_l3<false>(sh, v, lane, wave);
+        l3_to_l4d<false>(sh, v, lane, wave);
         store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
     }
 }
