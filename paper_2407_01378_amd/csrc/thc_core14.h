@@ -249,11 +249,19 @@ __device__ __forceinline__ void x3d_load(const Shared& sh, float (&v)[kRegs], ui
 
 // Stages 0..13 on a chunk that sits in layout L1 in v; result (unnormalised H_c x) in
 // layout L3.  Starts with a barrier (every thread is past its earlier reads of the
-// buffer); the buffer is still being read when it returns.
-template <bool PRIO>
+// buffer); the buffer is still being read when it returns.  hook.at<K>() is called at
+// three points that are separated by an LDS exchange each (K = 0 before the first group
+// of stages, 1 before the second, 2 before the third): a persistent kernel hangs the
+// next item's global loads there.
+struct NoHook {
+    template <int K>
+    __device__ __forceinline__ void at() {}
+};
+template <bool PRIO, class Hook>
 __device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], uint32_t lane,
-                                                uint32_t wave) {
+                                                uint32_t wave, Hook& hook) {
     set_prio<PRIO, kPrioRotateEarly>();
+    hook.template at<0>();
     butterflies<0, 5>(v);          // strides 1..16
     __syncthreads();
     // the first exchange stays inside each wave's own 8 KB of the buffer, and a wave's
@@ -263,6 +271,7 @@ __device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], u
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     x1_load(sh, v, lane, wave);
     set_prio<PRIO, kPrioRotateEarly>();
+    hook.template at<1>();
     butterflies<0, 5>(v);          // strides 32..512
     __syncthreads();
     set_prio<PRIO, kPrioExchange>();
@@ -270,7 +279,14 @@ __device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], u
     __syncthreads();
     x2_load(sh, v, lane, wave);
     set_prio<PRIO, kPrioRotateLate>();
+    hook.template at<2>();
     butterflies<1, 5>(v);          // strides 1024..8192 (register bit 0 is i9, already done)
+}
+template <bool PRIO>
+__device__ __forceinline__ void rotate_l1_to_l3(Shared& sh, float (&v)[kRegs], uint32_t lane,
+                                                uint32_t wave) {
+    NoHook none;
+    rotate_l1_to_l3<PRIO>(sh, v, lane, wave, none);
 }
 
 // max |v| over this thread's registers, then over the wave.

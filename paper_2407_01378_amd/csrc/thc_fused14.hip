@@ -182,44 +182,84 @@ __device__ __forceinline__ PayloadWords<BITS> load_payload_words(const uint8_t* 
     return r;
 }
 
+// Sum of the workers' payload words of one thread (its 32 coordinates) in sub-word lanes,
+// built up group by group: a group is the payload of kGroup workers in flight at once.
+template <int BITS>
+struct PayloadSum {
+    static constexpr int kWords = BITS;                        // payload dwords per worker per thread
+    static constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;    // sub-word accumulators per dword
+    static constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    static constexpr int kGroup = BITS == 8 ? 2 : 4;           // at most 16 registers in flight
+    const FusedPayloadPtrs& ptrs;
+    uint32_t W;
+    uint32_t acc[kWords][kLanes];
+    PayloadWords<BITS> x[kGroup];
+
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int d = 0; d < kWords; ++d)
+#pragma unroll
+            for (int k = 0; k < kLanes; ++k) acc[d][k] = 0u;
+    }
+    __device__ __forceinline__ void issue(uint64_t byte0, uint32_t group) {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j)
+            if (group * kGroup + j < W) x[j] = load_payload_words<BITS>(ptrs.p[group * kGroup + j] + byte0);
+    }
+    __device__ __forceinline__ void add(uint32_t group) {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j)
+            if (group * kGroup + j < W) {
+#pragma unroll
+                for (int d = 0; d < kWords; ++d)
+#pragma unroll
+                    for (int q = 0; q < kLanes; ++q) acc[d][q] += (x[j].w[d] >> (BITS * q)) & kMask;
+            }
+    }
+    __device__ __forceinline__ uint32_t groups() const { return (W + kGroup - 1) / kGroup; }
+};
+
+// Called from inside the rotation of the current chunk: loads and sums the first three
+// worker groups of the workgroup's NEXT chunk, one exchange of latency apart.
+template <int BITS>
+struct NextChunkLoads {
+    PayloadSum<BITS>& sum;
+    uint64_t byte0;
+    bool active;
+    template <int K>
+    __device__ __forceinline__ void at() {
+        if (!active) return;
+        if (K > 0) sum.add(K - 1);
+        sum.issue(byte0, K);
+    }
+};
+
 template <int BITS>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kernel(const AggDecodeArgs a,
                                                                        const FusedPayloadPtrs ptrs) {
     __shared__ Shared sh;
-    constexpr int kWords = BITS;                        // payload dwords per worker per thread
-    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;    // sub-word accumulators per dword
-    constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    using Sum = PayloadSum<BITS>;
+    constexpr int kWords = Sum::kWords, kLanes = Sum::kLanes;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const float Lf = (float)((1u << BITS) - 1u);
     const float Wf = (float)a.W;
+    const uint64_t thread_byte = (uint64_t)t * (4u * BITS);
 
+    Sum sum{ptrs, a.W};
+    sum.clear();
+    if (blockIdx.x < a.chunks) {   // the first chunk's payload, without overlap
+        const uint64_t byte0 = (((uint64_t)blockIdx.x << kChunkLog2) * BITS) / 8u + thread_byte;
+        for (uint32_t g = 0; g < sum.groups(); ++g) {
+            sum.issue(byte0, g);
+            sum.add(g);
+        }
+    }
     for (uint64_t p = blockIdx.x; p < a.chunks; p += gridDim.x) {
         const uint64_t g0 = p << kChunkLog2;
         const uint64_t left = a.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
         __syncthreads();   // the previous item's last reads of the buffer and sign table are done
         fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
-
-        uint32_t acc[kWords][kLanes];
-#pragma unroll
-        for (int d = 0; d < kWords; ++d)
-#pragma unroll
-            for (int k = 0; k < kLanes; ++k) acc[d][k] = 0u;
-        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (4u * BITS);
-        for (uint32_t w0 = 0; w0 < a.W; w0 += 4) {
-            PayloadWords<BITS> x[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (w0 + j < a.W) x[j] = load_payload_words<BITS>(ptrs.p[w0 + j] + byte0);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (w0 + j < a.W) {
-#pragma unroll
-                    for (int d = 0; d < kWords; ++d)
-#pragma unroll
-                        for (int q = 0; q < kLanes; ++q) acc[d][q] += (x[j].w[d] >> (BITS * q)) & kMask;
-                }
-        }
 
         // sums -> rotated-domain estimate of the mean, layout L1
         const float s = a.scale[p];
@@ -230,17 +270,17 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
 #pragma unroll
         for (int d = 0; d < kWords; ++d) {
             if (BITS == 8) {         // dword d: coordinates 4d..4d+3; lane 0 = even, lane 1 = odd
-                S[4 * d + 0] = acc[d][0] & 0xFFFFu;
-                S[4 * d + 1] = acc[d][1] & 0xFFFFu;
-                S[4 * d + 2] = acc[d][0] >> 16;
-                S[4 * d + 3] = acc[d][1] >> 16;
+                S[4 * d + 0] = sum.acc[d][0] & 0xFFFFu;
+                S[4 * d + 1] = sum.acc[d][1] & 0xFFFFu;
+                S[4 * d + 2] = sum.acc[d][0] >> 16;
+                S[4 * d + 3] = sum.acc[d][1] >> 16;
             } else {                 // dword d: 32/BITS coordinates; lane q byte b = coordinate (8/BITS) b + q
                 constexpr int per = 32 / BITS;
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
 #pragma unroll
                     for (int q = 0; q < kLanes; ++q)
-                        S[per * d + kLanes * b + q] = (acc[d][q] >> (8 * b)) & 0xFFu;
+                        S[per * d + kLanes * b + q] = (sum.acc[d][q] >> (8 * b)) & 0xFFu;
             }
         }
 #pragma unroll
@@ -268,7 +308,19 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
                 }
             }
         }
-        rotate_l1_to_l3<false>(sh, v, lane, wave);
+
+        // the next chunk's payload arrives while this one rotates
+        const uint64_t pn = p + gridDim.x;
+        NextChunkLoads<BITS> next{sum, ((pn << kChunkLog2) * BITS) / 8u + thread_byte, pn < a.chunks};
+        sum.clear();
+        rotate_l1_to_l3<false>(sh, v, lane, wave, next);
+        if (next.active) {
+            sum.add(2);
+            for (uint32_t g = 3; g < sum.groups(); ++g) {
+                sum.issue(next.byte0, g);
+                sum.add(g);
+            }
+        }
         l3_to_l4d<false>(sh, v, lane, wave);
         store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
     }
