@@ -16,6 +16,9 @@ launch duration against 8 TB/s; the same kernel's algorithmic arithmetic against
 plain-VALU issue rate is given beside it), and the CPU oracle timed on a bounded slice
 of the same inputs.
 
+    python bench.py --sat        the saturation-based aggregation variant (signed 2^b - 1 level
+                                 grid, Sat in worker order, b-bit aggregate); also reports the
+                                 overflow rate and the vNMSE next to the exact-sum path's
     python bench.py --probe      a few launches of each kernel of the first bucket plus a
                                  device-to-device copy of known size; meant to run under
                                  rocprofv3 --pmc so that counter readings of the kernels
@@ -53,6 +56,9 @@ def parse():
     ap.add_argument("--workload", default="gpt_1p3b")
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--sat", action="store_true", help="saturation-based aggregation variant")
+    ap.add_argument("--workers", type=int, default=None,
+                    help="simulate this many workers instead of the workload's own W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="few launches + a copy of known size, for rocprofv3 --pmc runs")
@@ -64,15 +70,20 @@ def parse():
 class Path:
     """Buffers and launch sequence of the path for one workload."""
 
-    def __init__(self, thc, torch, wl, bits, xs, seed=0, fused=True):
-        self.thc, self.wl, self.bits, self.fused = thc, wl, bits, fused
+    def __init__(self, thc, torch, wl, bits, xs, seed=0, fused=True, sat=False):
+        self.thc, self.wl, self.bits, self.fused, self.sat = thc, wl, bits, fused, sat
+        assert fused or not sat, "--sat is timed in its fused form"
+        self.overflow = torch.zeros(1, dtype=torch.int64, device=xs[0].device)
+        self.count_overflow = False   # the timed steps run without the optional overflow counter
         dev = xs[0].device
         self.W, self.l = wl.W, wl.chunk_log2
         W, l = self.W, self.l
         self.items = []
         self.sum_bytes = thc.thc_sum_bytes(W, bits)
         sum_dt = torch.uint8 if self.sum_bytes == 1 else torch.int16
-        self.no_sums = fused and thc.thc_aggregate_decode_is_fused(W, l, bits)
+        self.no_sums = fused and (thc.thc_sat_aggregate_decode_is_fused(W, l, bits) if sat
+                                  else thc.thc_aggregate_decode_is_fused(W, l, bits))
+        assert self.no_sums or not sat, "--sat needs a shape whose aggregate+decode runs fused"
         for k, (st, ln) in enumerate(wl.buckets()):
             P = thc.thc_num_chunks(ln, l)
             nb = thc.thc_payload_bytes(ln, l, bits)
@@ -98,12 +109,17 @@ class Path:
 
     # fused form
     def encode_all(self, it):
-        self.thc.thc_encode_all(it["grads"], self.l, it["seed"], self.bits, it["payloads"],
-                                it["scale"], it["ws"])
+        fn = self.thc.thc_sat_encode_all if self.sat else self.thc.thc_encode_all
+        fn(it["grads"], self.l, it["seed"], self.bits, it["payloads"], it["scale"], it["ws"])
 
     def aggregate_decode(self, it):
-        self.thc.thc_aggregate_decode(it["payloads"], it["scale"], it["ln"], self.l, it["seed"],
-                                      self.bits, it["sums"], it["out"])
+        if self.sat:
+            self.thc.thc_sat_aggregate_decode(it["payloads"], it["scale"], it["ln"], self.l,
+                                              it["seed"], self.bits, None,
+                                              self.overflow if self.count_overflow else None, it["out"])
+        else:
+            self.thc.thc_aggregate_decode(it["payloads"], it["scale"], it["ln"], self.l, it["seed"],
+                                          self.bits, it["sums"], it["out"])
 
     # one call per step of the method
     def absmax(self, it):
@@ -188,6 +204,16 @@ def probe(torch, path, dev):
     print(json.dumps({"probe": "ok", "bucket_elems": it["ln"], "copy_bytes": PROBE_COPY_BYTES}))
 
 
+def vnmse(torch, path, it):
+    """||estimate - mean||^2 / ||mean||^2 of one bucket, the error measure of the paper's
+    evaluation section, with the exact fp32 mean of the W workers' gradients as reference."""
+    mean = torch.zeros(it["ln"], dtype=torch.float32, device=it["out"].device)
+    for g in it["grads"]:
+        mean += g.float()
+    mean /= len(it["grads"])
+    return float(((it["out"] - mean) ** 2).sum() / (mean ** 2).sum())
+
+
 def read_traffic(workload_name, bits, kernel):
     """HBM bytes per launch of a kernel, measured offline with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
@@ -218,12 +244,15 @@ def main():
     thc.lib()
     dev = torch.device("cuda:0")
     wl = workload(a.workload)
+    if a.workers is not None:
+        import dataclasses
+        wl = dataclasses.replace(wl, W=a.workers)
     bits = a.bits if a.bits is not None else wl.bits[0]
     s_in = 2 if wl.dtype == "bf16" else 4
     W = wl.W
 
     xs = [generate(wl, w, dev) for w in range(W)]
-    path = Path(thc, torch, wl, bits, xs, fused=not a.unfused)
+    path = Path(thc, torch, wl, bits, xs, fused=not a.unfused, sat=a.sat)
     torch.cuda.synchronize()
     if a.probe:
         probe(torch, path, dev)
@@ -271,7 +300,10 @@ def main():
     copy_gbs = copy_bandwidth(torch, dev)
 
     sb = path.sum_bytes
-    alg_bytes_per_coord = W * (s_in + bits / 8.0) + W * bits / 8.0 + 2 * sb + 4
+    # the aggregate that an all-reduce would deliver is written once and read once: u8/u16
+    # sums for the exact path, b bits for the saturating one
+    agg_bytes = bits / 8.0 if a.sat else sb
+    alg_bytes_per_coord = W * (s_in + bits / 8.0) + W * bits / 8.0 + 2 * agg_bytes + 4
     value = W * wl.n * s_in / (ms * 1e-3) / 1e9
     res = {
         "metric": "gradient GB/s for encode+aggregate+decode (W workers) and % of HBM peak, 1 GPU",
@@ -280,7 +312,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "W": W, "n": wl.n, "input": wl.dtype, "bits": bits,
                    "chunk_log2": wl.chunk_log2, "buckets": nb, "bucket_elems": wl.bucket or wl.n,
-                   "form": "fused" if path.fused else "unfused"},
+                   "form": "fused" if path.fused else "unfused",
+                   "aggregation": "saturating" if a.sat else "exact"},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(wl.name, bits, dom_name)},
@@ -296,6 +329,25 @@ def main():
                          "frac_of_copy": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / copy_gbs, 4)},
         "kernels": kernels,
     }
+    if a.sat:
+        # quality of the variant on the first bucket, next to the exact-sum path's
+        it = path.items[0]
+        path.overflow.zero_()
+        path.count_overflow = True
+        path.encode_all(it)
+        path.aggregate_decode(it)
+        torch.cuda.synchronize()
+        res["sat"] = {"overflow_rate": round(int(path.overflow.item()) / it["ln"], 6),
+                      "vnmse": vnmse(torch, path, it)}
+        ref = dict(it, out=torch.empty_like(it["out"]), scale=torch.empty_like(it["scale"]),
+                   payloads=[torch.empty_like(p) for p in it["payloads"]],
+                   sums=torch.empty(it["P"] << path.l, dtype=torch.uint8 if sb == 1 else torch.int16,
+                                    device=dev))
+        thc.thc_encode_all(ref["grads"], path.l, ref["seed"], bits, ref["payloads"], ref["scale"], ref["ws"])
+        thc.thc_aggregate_decode(ref["payloads"], ref["scale"], ref["ln"], path.l, ref["seed"], bits,
+                                 ref["sums"], ref["out"])
+        torch.cuda.synchronize()
+        res["sat"]["vnmse_exact_sums"] = vnmse(torch, path, ref)
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, bits, xs, a.cpu_sample_log2)
     print(json.dumps(res))

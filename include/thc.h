@@ -140,8 +140,7 @@ int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uin
 
 /* ---- batched / fused entry points -------------------------------------------------
  * Same mathematics as the calls above and byte-identical payloads, scales, sums and
- * outputs; they exist because the path is bandwidth-bound and these forms read each
- * gradient once and never store the integer sums. */
+ * outputs; these forms read each gradient once and never store the integer sums. */
 
 /* Bytes of zero-initialisation-free scratch thc_encode_all needs for W workers of n
  * coordinates (the call clears what it uses).  0 on bad arguments. */
@@ -177,6 +176,58 @@ int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits
 int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float* scale,
                          uint64_t n, uint32_t chunk_log2, uint64_t seed, uint32_t bits,
                          void* sums, float* out, void* stream);
+
+/* ---- saturation-based aggregation ("Saturation-based aggregation" paragraph of the
+ * paper's proposed improvements to THC) ----------------------------------------------
+ * Partial aggregates are combined with Sat(x, y) = min(M, max(-M, x + y)),
+ * M = 2^(bits-1) - 1, so the aggregate never needs more than the `bits` bits a worker
+ * sends (b = q).  Readings taken where the paper is silent:
+ *   - a worker's coordinate is rounded onto the 2M + 1 evenly spaced points of
+ *     [-s_p, +s_p] (same rule and random stream as thc_encode with L = 2M); the payload
+ *     holds idx in [0, 2M] in `bits` bits, packed as for thc_encode; z = idx - M;
+ *   - Sat is not associative: a_0 = z_0, a_w = Sat(a_(w-1), z_w) in worker order
+ *     w = 1 .. W-1 (the order payloads[] is given in);
+ *   - the aggregate is stored offset binary (a + M) in `bits` bits, packed like a
+ *     payload (thc_payload_bytes bytes);
+ *   - decode: step = (s_p + s_p) / (2M), yhat = float(a) * (step / W), then the inverse
+ *     rotation as in thc_decode.
+ * W <= 64 (THC_ERR_WORKERS otherwise).  Rotation, range and scale sharing are the same
+ * as in the exact-sum path: use thc_chunk_absmax / thc_scale_reduce. */
+
+/* M = 2^(bits-1) - 1; 0 on bad bits. */
+uint32_t thc_sat_max(uint32_t bits);
+
+/* thc_encode / thc_encode_all on the 2M + 1-point grid; same arguments. */
+int thc_sat_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                   uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+                   float* scale_out, void* stream);
+int thc_sat_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                       uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                       float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Saturating aggregate of W payloads.
+ *   payloads        HOST array of W device pointers
+ *   aggregate       thc_payload_bytes(n, chunk_log2, bits) bytes, 16-byte aligned
+ *   overflow_count  NULL, or one 8-byte aligned device counter to which the number of
+ *                   coordinates (padding included) with at least one clipped Sat step is
+ *                   ADDED; the caller zeroes it */
+int thc_sat_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                      uint32_t bits, uint8_t* aggregate, unsigned long long* overflow_count,
+                      void* stream);
+
+/* Saturated aggregate -> estimate of the workers' mean gradient (n fp32). */
+int thc_sat_decode(const uint8_t* aggregate, const float* scale, uint32_t W, uint64_t n,
+                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, float* out, void* stream);
+
+/* 1 if thc_sat_aggregate_decode runs as one kernel for this shape (then `aggregate` may
+ * be NULL), 0 if it falls back to thc_sat_aggregate + thc_sat_decode. */
+int thc_sat_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits);
+
+/* thc_sat_aggregate followed by thc_sat_decode; identical results. */
+int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float* scale,
+                             uint64_t n, uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                             uint8_t* aggregate, unsigned long long* overflow_count, float* out,
+                             void* stream);
 
 #ifdef __cplusplus
 }

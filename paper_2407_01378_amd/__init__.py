@@ -27,6 +27,13 @@ from .binding import (  # noqa: F401
     thc_num_chunks,
     thc_payload_bytes,
     thc_rounding_bits,
+    thc_sat_aggregate,
+    thc_sat_aggregate_decode,
+    thc_sat_aggregate_decode_is_fused,
+    thc_sat_decode,
+    thc_sat_encode,
+    thc_sat_encode_all,
+    thc_sat_max,
     thc_scale_reduce,
     thc_sum_bytes,
     thc_version,

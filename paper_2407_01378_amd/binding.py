@@ -57,6 +57,27 @@ _SIGNATURES = {
                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]),
+    "thc_sat_max": (ctypes.c_uint32, [ctypes.c_uint32]),
+    "thc_sat_encode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                      ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p]),
+    "thc_sat_encode_all": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                          ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                          ctypes.c_void_p]),
+    "thc_sat_aggregate": (ctypes.c_int, [_u8pp, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32,
+                                         ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p]),
+    "thc_sat_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                      ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_sat_aggregate_decode_is_fused": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint32,
+                                                         ctypes.c_uint32]),
+    "thc_sat_aggregate_decode": (ctypes.c_int, [_u8pp, ctypes.c_uint32, ctypes.c_void_p,
+                                                ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                                ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_void_p]),
 }
 
 
@@ -240,4 +261,62 @@ def thc_aggregate_decode(payloads, scale, n, chunk_log2, seed, bits, sums, out, 
     _flat(out, torch.float32)
     _check(lib().thc_aggregate_decode(pp, W, _ptr(scale), n, chunk_log2, seed, bits, _ptr(sums),
                                       _ptr(out), _stream(stream)), "thc_aggregate_decode")
+    return out
+
+
+# ------------------------------------------------------ saturation-based aggregation
+def thc_sat_max(bits):
+    return lib().thc_sat_max(bits)
+
+
+def thc_sat_encode(grad, chunk_log2, seed, worker, bits, shared_scale, payload, scale_out=None,
+                   stream=None):
+    _flat(grad), _flat(payload, torch.uint8)
+    _check(lib().thc_sat_encode(_ptr(grad), _dtype_code(grad), grad.numel(), chunk_log2, seed,
+                                worker, bits, _ptr(shared_scale), _ptr(payload), _ptr(scale_out),
+                                _stream(stream)), "thc_sat_encode")
+    return payload
+
+
+def thc_sat_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+    W = len(grads)
+    n = grads[0].numel()
+    for g in grads:
+        _flat(g)
+        if g.numel() != n or g.dtype != grads[0].dtype:
+            raise ValueError("all workers must have gradients of one size and dtype")
+    keep_g, pg = _ptr_array(grads)
+    keep_p, pp = _ptr_array(payloads)
+    _check(lib().thc_sat_encode_all(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
+                                    _ptr(scale), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)),
+           "thc_sat_encode_all")
+    return payloads
+
+
+def thc_sat_aggregate(payloads, n, chunk_log2, bits, aggregate, overflow_count=None, stream=None):
+    keep_p, pp = _ptr_array(payloads)
+    _check(lib().thc_sat_aggregate(pp, len(payloads), n, chunk_log2, bits, _ptr(aggregate),
+                                   _ptr(overflow_count), _stream(stream)), "thc_sat_aggregate")
+    return aggregate
+
+
+def thc_sat_decode(aggregate, scale, W, n, chunk_log2, seed, bits, out, stream=None):
+    _flat(out, torch.float32)
+    _check(lib().thc_sat_decode(_ptr(aggregate), _ptr(scale), W, n, chunk_log2, seed, bits,
+                                _ptr(out), _stream(stream)), "thc_sat_decode")
+    return out
+
+
+def thc_sat_aggregate_decode_is_fused(W, chunk_log2, bits):
+    return bool(lib().thc_sat_aggregate_decode_is_fused(W, chunk_log2, bits))
+
+
+def thc_sat_aggregate_decode(payloads, scale, n, chunk_log2, seed, bits, aggregate, overflow_count,
+                             out, stream=None):
+    keep_p, pp = _ptr_array(payloads)
+    _flat(out, torch.float32)
+    _check(lib().thc_sat_aggregate_decode(pp, len(payloads), _ptr(scale), n, chunk_log2, seed, bits,
+                                          _ptr(aggregate), _ptr(overflow_count), _ptr(out),
+                                          _stream(stream)), "thc_sat_aggregate_decode")
     return out

@@ -136,9 +136,9 @@ int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float
         thc::launch_scale_reduce(absmax_all, W, chunks, scale, static_cast<hipStream_t>(stream)));
 }
 
-int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
-               uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
-               float* scale_out, void* stream) {
+static int encode_impl(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                       uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+                       float* scale_out, void* stream, bool sat) {
     int rc = check_common(n, chunk_log2);
     if (rc == THC_OK) rc = check_dtype(dt);
     if (rc == THC_OK) rc = check_bits(bits);
@@ -156,8 +156,16 @@ int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, 
     a.in_bf16 = dt == THC_BF16;
     a.worker = worker;
     a.bits = bits;
+    a.levels = thc::grid_levels(bits, sat);
     a.payload_bytes = (a.padded * bits + 7) / 8;
     return finish(thc::launch_chunks(Mode::Encode, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+               uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+               float* scale_out, void* stream) {
+    return encode_impl(grad, dt, n, chunk_log2, seed, worker, bits, shared_scale, payload, scale_out,
+                       stream, false);
 }
 
 int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
@@ -209,6 +217,7 @@ int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uin
     a.out = out;
     a.scale_in = scale;
     a.bits = bits;
+    a.levels = thc::grid_levels(bits, false);
     a.W = W;
     a.sum_bytes = sum_bytes;
     return finish(thc::launch_chunks(Mode::Decode, a, static_cast<hipStream_t>(stream)));
@@ -227,9 +236,10 @@ uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_l
     return 16 + 4 * (uint64_t)thc::encode_all_slot_words(W) * chunks;
 }
 
-int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
-                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
-                   float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
+static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                           uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                           float* scale, void* workspace, uint64_t workspace_bytes, void* stream,
+                           bool sat) {
     int rc = check_common(n, chunk_log2);
     if (rc == THC_OK) rc = check_dtype(dt);
     if (rc == THC_OK) rc = check_bits(bits);
@@ -254,6 +264,7 @@ int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t 
     a.key0 = (uint32_t)seed;
     a.key1 = (uint32_t)(seed >> 32);
     a.max_spins = g_spin_limit;
+    a.levels = thc::grid_levels(bits, sat);
     a.scale = scale;
     a.error = words;
     a.slots = words + 4;
@@ -278,8 +289,15 @@ int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t 
     }
     rc = thc_scale_reduce(absmax_all, W, chunks, scale, stream);
     for (uint32_t w = 0; rc == THC_OK && w < W; ++w)
-        rc = thc_encode(grads[w], dt, n, chunk_log2, seed, w, bits, scale, payloads[w], nullptr, stream);
+        rc = encode_impl(grads[w], dt, n, chunk_log2, seed, w, bits, scale, payloads[w], nullptr, stream, sat);
     return rc;
+}
+
+int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                   float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
+    return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
+                           workspace_bytes, stream, false);
 }
 
 int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
@@ -319,6 +337,114 @@ int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float
     rc = thc_aggregate(payloads, W, n, chunk_log2, bits, sums, stream);
     if (rc != THC_OK) return rc;
     return thc_decode(sums, scale, W, n, chunk_log2, seed, bits, out, stream);
+}
+
+// ------------------------------------------------- saturation-based aggregation
+uint32_t thc_sat_max(uint32_t bits) {
+    return check_bits(bits) == THC_OK ? (1u << (bits - 1)) - 1u : 0u;
+}
+
+int thc_sat_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                   uint32_t worker, uint32_t bits, const float* shared_scale, uint8_t* payload,
+                   float* scale_out, void* stream) {
+    return encode_impl(grad, dt, n, chunk_log2, seed, worker, bits, shared_scale, payload, scale_out,
+                       stream, true);
+}
+
+int thc_sat_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                       uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                       float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
+    return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
+                           workspace_bytes, stream, true);
+}
+
+static int check_sat_payloads(const uint8_t* const* payloads, uint32_t W) {
+    if (W == 0 || W > (uint32_t)thc::kMaxFusedPayloads) return THC_ERR_WORKERS;
+    if (!payloads) return THC_ERR_NULL;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!payloads[w]) return THC_ERR_NULL;
+        if (!aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+    }
+    return THC_OK;
+}
+
+int thc_sat_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                      uint32_t bits, uint8_t* aggregate, unsigned long long* overflow_count,
+                      void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (W == 0 || W > (uint32_t)thc::kMaxFusedPayloads) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    rc = check_sat_payloads(payloads, W);
+    if (rc != THC_OK) return rc;
+    if (!aggregate) return THC_ERR_NULL;
+    if (!aligned(aggregate, 16) || !aligned(overflow_count, 8)) return THC_ERR_ALIGN;
+    const uint64_t padded = padded_coords(n, chunk_log2);
+    thc::FusedPayloadPtrs ptrs{};
+    for (uint32_t w = 0; w < W; ++w) ptrs.p[w] = payloads[w];
+    return finish(thc::launch_sat_aggregate(ptrs, W, bits, (padded * bits + 7) / 8, padded, aggregate,
+                                            overflow_count, static_cast<hipStream_t>(stream)));
+}
+
+int thc_sat_decode(const uint8_t* aggregate, const float* scale, uint32_t W, uint64_t n,
+                   uint32_t chunk_log2, uint64_t seed, uint32_t bits, float* out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (W == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!aggregate || !scale || !out) return THC_ERR_NULL;
+    if (!aligned(aggregate, 16) || !aligned(scale, 4) || !aligned(out, 4)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = aggregate;
+    a.out = out;
+    a.scale_in = scale;
+    a.bits = bits;
+    a.levels = thc::grid_levels(bits, true);
+    a.W = W;
+    a.sat = 1;
+    return finish(thc::launch_chunks(Mode::Decode, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_sat_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
+    if (check_bits(bits) != THC_OK || W == 0) return 0;
+    return thc::sat_aggregate_decode_fused_applicable(W, chunk_log2) ? 1 : 0;
+}
+
+int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float* scale,
+                             uint64_t n, uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                             uint8_t* aggregate, unsigned long long* overflow_count, float* out,
+                             void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (W == 0 || W > (uint32_t)thc::kMaxFusedPayloads) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    rc = check_sat_payloads(payloads, W);
+    if (rc != THC_OK) return rc;
+    if (!scale || !out) return THC_ERR_NULL;
+    if (!aligned(scale, 4) || !aligned(out, 4) || !aligned(aggregate, 16) || !aligned(overflow_count, 8))
+        return THC_ERR_ALIGN;
+    if (thc::sat_aggregate_decode_fused_applicable(W, chunk_log2) && aligned(out, 16)) {
+        thc::FusedPayloadPtrs ptrs{};
+        for (uint32_t w = 0; w < W; ++w) ptrs.p[w] = payloads[w];
+        thc::SatAggDecodeArgs a{};
+        a.n = n;
+        a.chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+        a.W = W;
+        a.key0 = (uint32_t)seed;
+        a.key1 = (uint32_t)(seed >> 32);
+        a.scale = scale;
+        a.aggregate = aggregate;
+        a.overflow = overflow_count;
+        a.out = out;
+        return finish(thc::launch_sat_aggregate_decode_fused(a, ptrs, bits, static_cast<hipStream_t>(stream)));
+    }
+    if (!aggregate) return THC_ERR_NULL;
+    rc = thc_sat_aggregate(payloads, W, n, chunk_log2, bits, aggregate, overflow_count, stream);
+    if (rc != THC_OK) return rc;
+    return thc_sat_decode(aggregate, scale, W, n, chunk_log2, seed, bits, out, stream);
 }
 
 }  // extern "C"

@@ -336,6 +336,7 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 // --------------------------------------------------------------------- quantizer
 // Stochastic rounding of the L4e-resident chunk onto the 2^BITS-point grid of [-s, s],
 // packed and stored.  v holds the UNNORMALISED rotation; y = v * 2^-7.
+//   L        largest grid index (2^BITS - 1, or 2^BITS - 2 for the signed grid)
 //   g0       global index of the chunk's first coordinate
 //   payload  start of this worker's payload
 //   CLAMP    false only when s is the largest |y| of the chunk: then floor(t) <= L holds
@@ -346,10 +347,9 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 // as long as the power-of-two factors move no operand into or out of the subnormal or
 // overflow range, which 2^-100 <= s <= 2^100 guarantees; other chunks take the plain form.
 template <int BITS, bool CLAMP, bool FOLD>
-__device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add, float mul, uint64_t g,
-                                              uint32_t worker, uint32_t key0, uint32_t key1,
+__device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add, float mul, uint32_t L,
+                                              uint64_t g, uint32_t worker, uint32_t key0, uint32_t key1,
                                               uint32_t (&pk)[BITS]) {
-    constexpr uint32_t L = (1u << BITS) - 1u;
 #pragma unroll
     for (int i = 0; i < BITS; ++i) pk[i] = 0u;
 #pragma unroll
@@ -372,18 +372,17 @@ __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add
 }
 
 template <int BITS, bool CLAMP>
-__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint64_t g0,
+__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint32_t L, uint64_t g0,
                                                uint32_t worker, uint32_t key0, uint32_t key1,
                                                uint8_t* payload, uint32_t t) {
-    constexpr uint32_t L = (1u << BITS) - 1u;
     const float two = s + s;
     const float inv = two != 0.0f ? (float)L / two : 0.0f;
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
     if (s >= 0x1p-100f && s <= 0x1p100f)   // the same for every thread of the workgroup
-        quantize_pack<BITS, CLAMP, true>(v, s * 128.0f, inv * kInvSqrtC, g, worker, key0, key1, pk);
+        quantize_pack<BITS, CLAMP, true>(v, s * 128.0f, inv * kInvSqrtC, L, g, worker, key0, key1, pk);
     else
-        quantize_pack<BITS, CLAMP, false>(v, s, inv, g, worker, key0, key1, pk);
+        quantize_pack<BITS, CLAMP, false>(v, s, inv, L, g, worker, key0, key1, pk);
     uint8_t* dst = payload + (g * BITS) / 8u;
     if constexpr (BITS == 8) {
         reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);

@@ -54,12 +54,13 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
         }
         if (a.scale_out && t == 0) a.scale_out[p] = s;
         l3_to_l4e<false>(sh, v, lane, wave);
-        quantize_store<BITS, true>(v, s, g0, a.worker, a.key0, a.key1, static_cast<uint8_t*>(a.out), t);
+        quantize_store<BITS, true>(v, s, a.levels, g0, a.worker, a.key0, a.key1, static_cast<uint8_t*>(a.out), t);
     }
 }
 
 // Inverse direction, one chunk per workgroup.
-//   SRC 0: rotated fp32 values (rht_inverse);  1: u8 sums;  2: u16 sums (thc_decode)
+//   SRC 0: rotated fp32 values (rht_inverse);  1: u8 sums;  2: u16 sums (thc_decode);
+//       3: packed saturated aggregate, offset binary (thc_sat_decode)
 template <int SRC>
 __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     __shared__ Shared sh;
@@ -78,9 +79,26 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
         lds_to_l1<8, false>(sh, sh.sign[0], v, t);
     } else {
         const float s = a.scale_in[p];
-        const float step = (s + s) / (float)((1u << a.bits) - 1u);
+        const float step = (s + s) / (float)a.levels;
         const float q = step / (float)a.W;
-        if constexpr (SRC == 1) {
+        if constexpr (SRC == 3) {
+            // 32 coordinates = 4 * bits bytes per thread
+            const uint32_t bits = a.bits;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(
+                static_cast<const uint8_t*>(a.in) + (g0 * bits) / 8u + (uint64_t)t * (4u * bits));
+            const int centre = (int)(a.levels >> 1);
+            uint32_t word[8];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) word[d] = (uint32_t)d < bits ? src[d] : 0u;
+#pragma unroll
+            for (int r = 0; r < kRegs; ++r) {
+                uint32_t A;
+                if (bits == 2) A = (word[r >> 4] >> (2 * (r & 15))) & 3u;
+                else if (bits == 4) A = (word[r >> 3] >> (4 * (r & 7))) & 15u;
+                else A = (word[r >> 2] >> (8 * (r & 3))) & 255u;
+                v[r] = (float)((int)A - centre) * q;
+            }
+        } else if constexpr (SRC == 1) {
             const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint8_t*>(a.in) + g0) + 2 * t;
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
@@ -155,7 +173,9 @@ hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
             hipLaunchKernelGGL(inverse_kernel<0>, grid, dim3(kThreads), 0, stream, a);
             return hipGetLastError();
         case Mode::Decode:
-            if (a.sum_bytes == 1)
+            if (a.sat)
+                hipLaunchKernelGGL(inverse_kernel<3>, grid, dim3(kThreads), 0, stream, a);
+            else if (a.sum_bytes == 1)
                 hipLaunchKernelGGL(inverse_kernel<1>, grid, dim3(kThreads), 0, stream, a);
             else
                 hipLaunchKernelGGL(inverse_kernel<2>, grid, dim3(kThreads), 0, stream, a);

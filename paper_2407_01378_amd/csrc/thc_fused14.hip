@@ -122,7 +122,7 @@ struct EncodeAllCtx {
         }
         const float s = __uint_as_float(sbits);
         if (w == 0 && t == 0) a.scale[p] = s;
-        quantize_store<BITS, false>(v, s, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        quantize_store<BITS, false>(v, s, a.levels, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
     }
 };
 
@@ -326,6 +326,99 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
     }
 }
 
+// ------------------------------------------------- saturating aggregate + decode
+// Same shape as aggregate_decode_kernel, but the W payloads are combined coordinate by
+// coordinate with Sat in worker order (a <- clamp(a + z_w, -M, M), z = idx - M, starting
+// from a = 0, which leaves a = z_0 after the first worker), so the running value never
+// needs more than BITS bits.  Optionally stores the packed aggregate (a + M) and counts
+// the coordinates with at least one clipped step.
+template <int BITS, bool COUNT>
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_kernel(
+    const SatAggDecodeArgs a, const FusedPayloadPtrs ptrs) {
+    __shared__ Shared sh;
+    constexpr int M = (1 << (BITS - 1)) - 1;
+    constexpr int kGroup = (BITS == 8 || COUNT) ? 2 : 4;   // the counting form needs the registers
+    constexpr uint32_t kField = (1u << BITS) - 1u;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const float Lf = (float)(2 * M);
+    const float Wf = (float)a.W;
+    uint32_t clipped_total = 0u;
+
+    for (uint64_t p = blockIdx.x; p < a.chunks; p += gridDim.x) {
+        const uint64_t g0 = p << kChunkLog2;
+        const uint64_t left = a.n - g0;
+        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        __syncthreads();   // the previous item's last reads of the buffer and sign table are done
+        fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
+
+        int acc[kRegs];
+        uint32_t clip[kRegs];
+#pragma unroll
+        for (int r = 0; r < kRegs; ++r) {
+            acc[r] = 0;
+            clip[r] = 0u;
+        }
+        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (4u * BITS);
+        for (uint32_t w0 = 0; w0 < a.W; w0 += kGroup) {
+            PayloadWords<BITS> x[kGroup];
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j)
+                if (w0 + j < a.W) x[j] = load_payload_words<BITS>(ptrs.p[w0 + j] + byte0);
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j)
+                if (w0 + j < a.W) {
+#pragma unroll
+                    for (int r = 0; r < kRegs; ++r) {
+                        const int bit = r * BITS;
+                        const int raw = acc[r] + (int)((x[j].w[bit >> 5] >> (bit & 31)) & kField) - M;
+                        const int c = raw < -M ? -M : (raw > M ? M : raw);
+                        if (COUNT) clip[r] |= (uint32_t)(raw ^ c);
+                        acc[r] = c;
+                    }
+                }
+        }
+        if (COUNT) {
+#pragma unroll
+            for (int r = 0; r < kRegs; ++r) clipped_total += clip[r] != 0u ? 1u : 0u;
+        }
+        if (a.aggregate) {
+            uint32_t pk[BITS];
+#pragma unroll
+            for (int d = 0; d < BITS; ++d) pk[d] = 0u;
+#pragma unroll
+            for (int r = 0; r < kRegs; ++r) {
+                const int bit = r * BITS;
+                pk[bit >> 5] |= (uint32_t)(acc[r] + M) << (bit & 31);
+            }
+            uint8_t* dst = a.aggregate + byte0;
+            if constexpr (BITS == 8) {
+                reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                reinterpret_cast<uint4*>(dst)[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            } else if constexpr (BITS == 4) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            } else {
+                *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
+            }
+        }
+
+        // aggregate -> rotated-domain estimate of the mean, layout L1
+        const float s = a.scale[p];
+        const float step = (s + s) / Lf;
+        const float qf = step / Wf;
+        float v[kRegs];
+#pragma unroll
+        for (int r = 0; r < kRegs; ++r) v[r] = (float)acc[r] * qf;
+        rotate_l1_to_l3<false>(sh, v, lane, wave);
+        l3_to_l4d<false>(sh, v, lane, wave);
+        store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
+    }
+    if (COUNT) {   // one atomic per wave
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) clipped_total += __shfl_xor(clipped_total, off, 64);
+        if (lane == 0 && clipped_total != 0u) atomicAdd(a.overflow, (unsigned long long)clipped_total);
+    }
+}
+
 // ------------------------------------------------------------------ aggregate only
 // Streaming sum of W payloads: each thread owns 16 payload bytes per worker.
 template <int BITS, typename SumT>
@@ -488,6 +581,36 @@ hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayl
         hipLaunchKernelGGL(aggregate_decode_kernel<4>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
     else
         hipLaunchKernelGGL(aggregate_decode_kernel<8>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    return hipGetLastError();
+}
+
+bool sat_aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2) {
+    return chunk_log2 == 14 && W <= (uint32_t)kMaxFusedPayloads;
+}
+
+hipError_t launch_sat_aggregate_decode_fused(const SatAggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                             uint32_t bits, hipStream_t stream) {
+    using namespace k14;
+    if (a.chunks == 0) return hipSuccess;
+    uint32_t G = 0;
+#define THC_SATDEC(B, C)                                                                          \
+    do {                                                                                          \
+        G = resident_grid<sat_aggregate_decode_kernel<B, C>>();                                   \
+        if (G == 0) return hipErrorInvalidValue;                                                  \
+        if ((uint64_t)G > a.chunks) G = (uint32_t)a.chunks;                                       \
+        hipLaunchKernelGGL((sat_aggregate_decode_kernel<B, C>), dim3(G), dim3(kThreads), 0, stream, \
+                           a, ptrs);                                                              \
+    } while (0)
+    if (a.overflow) {
+        if (bits == 2) THC_SATDEC(2, true);
+        else if (bits == 4) THC_SATDEC(4, true);
+        else THC_SATDEC(8, true);
+    } else {
+        if (bits == 2) THC_SATDEC(2, false);
+        else if (bits == 4) THC_SATDEC(4, false);
+        else THC_SATDEC(8, false);
+    }
+#undef THC_SATDEC
     return hipGetLastError();
 }
 

@@ -65,9 +65,10 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
             const uint64_t g = g0 + j;
             v[j] = g < a.padded ? y[g] : 0.0f;
         }
-    } else {  // Decode: sums -> rotated-domain estimate of the mean
-        const float Lf = (float)((1u << a.bits) - 1u);
+    } else {  // Decode: sums (or the saturated aggregate) -> rotated-domain estimate of the mean
+        const float Lf = (float)a.levels;
         const float Wf = (float)a.W;
+        const int centre = (int)(a.levels >> 1);   // M of the signed grid
 #pragma unroll
         for (int j = 0; j < kEpt; ++j) {
             const uint64_t g = g0 + j;
@@ -76,10 +77,17 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
                 const float s = a.scale_in[g >> l];
                 const float step = (s + s) / Lf;
                 const float q = step / Wf;
-                const uint32_t S = a.sum_bytes == 1
-                                       ? (uint32_t) static_cast<const uint8_t*>(a.in)[g]
-                                       : (uint32_t) static_cast<const uint16_t*>(a.in)[g];
-                val = (float)S * q - s;
+                if (a.sat) {
+                    const uint64_t bit = g * a.bits;
+                    const uint32_t A = ((uint32_t) static_cast<const uint8_t*>(a.in)[bit >> 3] >> (bit & 7u)) &
+                                       ((1u << a.bits) - 1u);
+                    val = (float)((int)A - centre) * q;
+                } else {
+                    const uint32_t S = a.sum_bytes == 1
+                                           ? (uint32_t) static_cast<const uint8_t*>(a.in)[g]
+                                           : (uint32_t) static_cast<const uint16_t*>(a.in)[g];
+                    val = (float)S * q - s;
+                }
             }
             v[j] = val;
         }
@@ -183,8 +191,7 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
             }
             if (a.scale_out) report(a.scale_out, s_el);
 
-            const uint32_t L = (1u << a.bits) - 1u;
-            const float Lf = (float)L;
+            const float Lf = (float)a.levels;
             const u32x4 rb = round_block(g0 >> 4, a.worker, a.key0, a.key1);
             uint32_t pk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -268,6 +275,76 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const PayloadBatch batch
     }
 }
 
+// Saturating aggregation in worker order: a_0 = z_0, a_w = Sat(a_(w-1), z_w), z = idx - M.
+// Each thread owns one 16-byte slice of the payloads (128 / BITS coordinates) and writes
+// the same slice of the aggregate (offset binary, a + M).  COUNT: also count the
+// coordinates (below `padded`) for which at least one step clipped.
+template <int BITS, bool COUNT>
+__global__ __launch_bounds__(256) void sat_aggregate_kernel(const FusedPayloadPtrs ptrs, uint32_t W,
+                                                            uint64_t payload_bytes, uint64_t padded,
+                                                            uint8_t* aggregate,
+                                                            unsigned long long* overflow) {
+    constexpr int kCoords = 128 / BITS;
+    constexpr int M = (1 << (BITS - 1)) - 1;
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t byte0 = i * 16u;
+    uint32_t clipped_here = 0u;
+    if (byte0 < payload_bytes) {
+        const bool whole = byte0 + 16u <= payload_bytes;
+        int acc[kCoords];
+        uint32_t clipped[kCoords];
+        for (uint32_t w = 0; w < W; ++w) {
+            uint32_t x[4] = {0u, 0u, 0u, 0u};
+            const uint8_t* src = ptrs.p[w] + byte0;
+            if (whole) {
+                const uint4 q = *reinterpret_cast<const uint4*>(src);
+                x[0] = q.x;
+                x[1] = q.y;
+                x[2] = q.z;
+                x[3] = q.w;
+            } else {
+                for (uint32_t b = 0; byte0 + b < payload_bytes; ++b)
+                    x[b >> 2] |= (uint32_t)src[b] << (8 * (b & 3));
+            }
+#pragma unroll
+            for (int e = 0; e < kCoords; ++e) {
+                const int bit = e * BITS;
+                const int z = (int)((x[bit >> 5] >> (bit & 31)) & ((1u << BITS) - 1u)) - M;
+                if (w == 0) {
+                    acc[e] = z;
+                    clipped[e] = 0u;
+                } else {
+                    const int raw = acc[e] + z;
+                    const int a = raw < -M ? -M : (raw > M ? M : raw);
+                    if (COUNT) clipped[e] |= (uint32_t)(raw != a);
+                    acc[e] = a;
+                }
+            }
+        }
+        uint32_t o[4] = {0u, 0u, 0u, 0u};
+        const uint64_t g0 = i * kCoords;
+#pragma unroll
+        for (int e = 0; e < kCoords; ++e) {
+            const int bit = e * BITS;
+            const bool real = g0 + e < padded;
+            o[bit >> 5] |= (real ? (uint32_t)(acc[e] + M) : 0u) << (bit & 31);
+            if (COUNT && real) clipped_here += clipped[e];
+        }
+        uint8_t* dst = aggregate + byte0;
+        if (whole) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
+        } else {
+            for (uint32_t b = 0; byte0 + b < payload_bytes; ++b) dst[b] = (uint8_t)(o[b >> 2] >> (8 * (b & 3)));
+        }
+    }
+    if (COUNT) {   // one atomic per wave
+        uint32_t tot = clipped_here;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off, 64);
+        if ((threadIdx.x & 63u) == 0 && tot != 0u) atomicAdd(overflow, (unsigned long long)tot);
+    }
+}
+
 __global__ __launch_bounds__(256) void scale_reduce_kernel(const float* absmax_all, uint32_t W,
                                                            uint64_t chunks, float* scale) {
     const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -325,6 +402,30 @@ hipError_t launch_aggregate(const PayloadBatch& batch, uint32_t count, bool accu
         else THC_AGG(8, uint16_t);
     }
 #undef THC_AGG
+    return hipGetLastError();
+}
+
+hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
+                                uint64_t payload_bytes, uint64_t padded, uint8_t* aggregate,
+                                unsigned long long* overflow, hipStream_t stream) {
+    const uint64_t threads = (payload_bytes + 15u) / 16u;
+    if (threads == 0) return hipSuccess;
+    const uint64_t blocks = (threads + 255u) / 256u;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const dim3 grid((uint32_t)blocks), block(256);
+#define THC_SAT(B)                                                                              \
+    do {                                                                                        \
+        if (overflow)                                                                           \
+            hipLaunchKernelGGL((sat_aggregate_kernel<B, true>), grid, block, 0, stream, ptrs, W,  \
+                               payload_bytes, padded, aggregate, overflow);                     \
+        else                                                                                    \
+            hipLaunchKernelGGL((sat_aggregate_kernel<B, false>), grid, block, 0, stream, ptrs, W, \
+                               payload_bytes, padded, aggregate, overflow);                     \
+    } while (0)
+    if (bits == 2) THC_SAT(2);
+    else if (bits == 4) THC_SAT(4);
+    else THC_SAT(8);
+#undef THC_SAT
     return hipGetLastError();
 }
 

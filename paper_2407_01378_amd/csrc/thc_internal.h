@@ -10,6 +10,10 @@ namespace thc {
 
 enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4 };
 
+// Largest grid index of the two quantization grids: 2^bits points for exact sums,
+// 2^bits - 1 points (signed symmetric, centre M = 2^(bits-1) - 1) for saturating sums.
+inline uint32_t grid_levels(uint32_t bits, bool sat) { return (1u << bits) - (sat ? 2u : 1u); }
+
 // One description for every per-chunk kernel (rotation, range, encode, decode).
 struct ChunkArgs {
     const void* in;         // gradient (fp32/bf16), y (fp32) or sums (u8/u16)
@@ -26,6 +30,8 @@ struct ChunkArgs {
     uint32_t W;
     uint32_t in_bf16;       // 1: gradient is bf16
     uint32_t sum_bytes;     // decode: 1 or 2
+    uint32_t levels;        // encode / decode: largest grid index L
+    uint32_t sat;           // decode: 1 = `in` is the packed saturated aggregate (offset binary)
     float inv_sqrt_c;       // fp32 nearest of c^(-1/2)
 };
 
@@ -54,6 +60,7 @@ struct EncodeAllArgs {
     uint32_t W;
     uint32_t key0, key1;
     uint32_t max_spins;  // bound on the polls of one wait
+    uint32_t levels;     // largest grid index L
     float* scale;        // out: chunks shared scales
     uint32_t* slots;     // zeroed: chunks x encode_all_slot_words(W) words
     uint32_t* error;     // zeroed: set to 1 if a wait timed out
@@ -66,7 +73,7 @@ hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs
                                    uint32_t bits, hipStream_t stream);
 hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream);
 
-constexpr int kMaxFusedPayloads = 32;
+constexpr int kMaxFusedPayloads = 64;
 struct FusedPayloadPtrs {
     const uint8_t* p[kMaxFusedPayloads];
 };
@@ -85,6 +92,25 @@ hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayl
 bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes);
 hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
                                  uint64_t payload_bytes, void* sums, hipStream_t stream);
+
+// ---- saturating aggregation ----------------------------------------------------------
+struct SatAggDecodeArgs {
+    uint64_t n;
+    uint64_t chunks;
+    uint32_t W;
+    uint32_t key0, key1;
+    const float* scale;
+    uint8_t* aggregate;             // may be null: packed b-bit aggregate, offset binary
+    unsigned long long* overflow;   // may be null: += coordinates with a clipped Sat step
+    float* out;
+};
+bool sat_aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2);
+hipError_t launch_sat_aggregate_decode_fused(const SatAggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                             uint32_t bits, hipStream_t stream);
+// Any chunk size: W <= kMaxFusedPayloads payloads -> packed aggregate (+ overflow count).
+hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
+                                uint64_t payload_bytes, uint64_t padded, uint8_t* aggregate,
+                                unsigned long long* overflow, hipStream_t stream);
 
 constexpr int kMaxAggBatch = 16;
 struct PayloadBatch {

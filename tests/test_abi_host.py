@@ -134,3 +134,36 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_sat_entry_points_validate_on_the_host(L):
+    p = ctypes.c_void_p(0x1000)
+    nul = ctypes.c_void_p(0)
+    F32 = thc.THC_F32
+    assert [L.thc_sat_max(b) for b in (2, 4, 8, 3)] == [1, 7, 127, 0]
+    arr = (ctypes.c_void_p * 65)(*([0x1000] * 65))
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    # workers: 1..64
+    assert L.thc_sat_aggregate(pp, 0, 100, 10, 4, p, nul, nul) == -4
+    assert L.thc_sat_aggregate(pp, 65, 100, 10, 4, p, nul, nul) == -4
+    assert L.thc_sat_aggregate_decode(pp, 65, p, 100, 14, 0, 4, p, nul, p, nul) == -4
+    assert L.thc_sat_decode(p, p, 0, 100, 10, 0, 4, p, nul) == -4
+    # bits, chunk, dtype
+    assert L.thc_sat_aggregate(pp, 4, 100, 10, 3, p, nul, nul) == -2
+    assert L.thc_sat_decode(p, p, 4, 100, 15, 0, 4, p, nul) == -3
+    assert L.thc_sat_encode(p, 9, 100, 10, 0, 0, 4, nul, p, nul, nul) == -5
+    # null / alignment
+    assert L.thc_sat_aggregate(pp, 4, 100, 10, 4, nul, nul, nul) == -1
+    assert L.thc_sat_aggregate(pp, 4, 100, 10, 4, ctypes.c_void_p(0x1008), nul, nul) == -8
+    assert L.thc_sat_aggregate(pp, 4, 100, 10, 4, p, ctypes.c_void_p(0x1004), nul) == -8
+    assert L.thc_sat_decode(nul, p, 4, 100, 10, 0, 4, p, nul) == -1
+    assert L.thc_sat_aggregate_decode(pp, 4, p, 100, 10, 0, 4, nul, nul, p, nul) == -1   # unfused shape needs it
+    assert L.thc_sat_aggregate_decode(pp, 4, nul, 100, 14, 0, 4, nul, nul, p, nul) == -1
+    # n == 0
+    assert L.thc_sat_aggregate(pp, 4, 0, 10, 4, nul, nul, nul) == 0
+    assert L.thc_sat_decode(nul, nul, 4, 0, 10, 0, 4, nul, nul) == 0
+    assert L.thc_sat_aggregate_decode(pp, 4, nul, 0, 14, 0, 4, nul, nul, nul, nul) == 0
+    assert L.thc_sat_encode(nul, F32, 0, 10, 0, 0, 4, nul, nul, nul, nul) == 0
+    assert L.thc_sat_aggregate_decode_is_fused(8, 14, 4) == 1
+    assert L.thc_sat_aggregate_decode_is_fused(8, 10, 4) == 0
+    assert L.thc_sat_aggregate_decode_is_fused(65, 14, 4) == 0

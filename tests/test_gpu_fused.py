@@ -82,7 +82,8 @@ def test_is_fused_predicate():
     assert not thc.thc_aggregate_decode_is_fused(18, 14, 4)
     assert thc.thc_aggregate_decode_is_fused(8, 14, 8)
     assert not thc.thc_aggregate_decode_is_fused(8, 10, 4)
-    assert not thc.thc_aggregate_decode_is_fused(33, 14, 2)
+    assert thc.thc_aggregate_decode_is_fused(64, 14, 2)
+    assert not thc.thc_aggregate_decode_is_fused(65, 14, 2)
 
 
 def test_workspace_is_reusable_and_small_inputs_work():
