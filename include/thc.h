@@ -229,6 +229,44 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
                              uint8_t* aggregate, unsigned long long* overflow_count, float* out,
                              void* stream);
 
+/* ---- full rotation (l' = l): the baseline the paper's "Partial rotation" paragraph and
+ * its THC throughput table compare against ---------------------------------------------
+ * The whole gradient, zero-padded to 2^log2_size coordinates ("Gradients are padded to
+ * size 2^l", notation table), is ONE chunk: y = 2^(-l/2) H_(2^l) D x with the same stage
+ * order, sign diagonal and rounding as the chunked path (identical to it with
+ * chunk_log2 = log2_size, which the chunked entry points do not accept above 14).
+ * Stages above 2^14 run as passes over y in global memory, in place, so rotated data is
+ * materialised and the quantizer's steps are separate elementwise calls:
+ *     rht_forward_full -> thc_full_absmax -> (thc_scale_reduce with chunks = 1)
+ *     -> thc_full_encode -> thc_aggregate(n = 2^log2_size, chunk_log2 = 14)
+ *     -> thc_full_decode -> rht_inverse_full
+ * 15 <= log2_size <= 33 (THC_ERR_CHUNK otherwise), n <= 2^log2_size (THC_ERR_SIZE);
+ * x, y, payload, sums and yhat must be 16-byte aligned. */
+
+/* Smallest valid log2_size for n coordinates (0 if n > 2^33). */
+uint32_t thc_full_log2(uint64_t n);
+
+/*   x   n values of dtype dt;   y   2^log2_size fp32, receives the rotated vector */
+int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                     float* y, void* stream);
+
+/*   y   2^log2_size fp32 rotated values, USED AS SCRATCH (garbage afterwards);
+ *   x   n fp32, receives D 2^(-l/2) H y */
+int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, float* x, void* stream);
+
+/* *absmax = max |y_g| over the 2^log2_size values (the call zeroes it first). */
+int thc_full_absmax(const float* y, uint32_t log2_size, float* absmax, void* stream);
+
+/* Stochastic rounding of rotated values onto the 2^bits-point grid of [-s, s], s = *scale
+ * (device, one float, shared by all workers); payload 2^log2_size * bits / 8 bytes. */
+int thc_full_encode(const float* y, uint32_t log2_size, uint64_t seed, uint32_t worker, uint32_t bits,
+                    const float* scale, uint8_t* payload, void* stream);
+
+/* yhat_g = float(sum_g) * (step / W) - s for the 2^log2_size sums written by
+ * thc_aggregate; feed yhat to rht_inverse_full. */
+int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t log2_size, uint32_t bits,
+                    float* yhat, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

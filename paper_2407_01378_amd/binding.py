@@ -57,6 +57,19 @@ _SIGNATURES = {
                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]),
+    "thc_full_log2": (ctypes.c_uint32, [ctypes.c_uint64]),
+    "rht_forward_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                        ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "rht_inverse_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
+                                        ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_full_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p,
+                                       ctypes.c_void_p]),
+    "thc_full_encode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64,
+                                       ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_full_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                       ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                       ctypes.c_void_p]),
     "thc_sat_max": (ctypes.c_uint32, [ctypes.c_uint32]),
     "thc_sat_encode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                       ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
@@ -320,3 +333,39 @@ def thc_sat_aggregate_decode(payloads, scale, n, chunk_log2, seed, bits, aggrega
                                           _ptr(aggregate), _ptr(overflow_count), _ptr(out),
                                           _stream(stream)), "thc_sat_aggregate_decode")
     return out
+
+
+# -------------------------------------------------------------------- full rotation
+def thc_full_log2(n):
+    return lib().thc_full_log2(n)
+
+
+def rht_forward_full(x, log2_size, seed, y, stream=None):
+    _flat(x), _flat(y, torch.float32)
+    _check(lib().rht_forward_full(_ptr(x), _dtype_code(x), x.numel(), log2_size, seed, _ptr(y),
+                                  _stream(stream)), "rht_forward_full")
+    return y
+
+
+def rht_inverse_full(y, n, log2_size, seed, x, stream=None):
+    _flat(y, torch.float32), _flat(x, torch.float32)
+    _check(lib().rht_inverse_full(_ptr(y), n, log2_size, seed, _ptr(x), _stream(stream)),
+           "rht_inverse_full")
+    return x
+
+
+def thc_full_absmax(y, log2_size, absmax, stream=None):
+    _check(lib().thc_full_absmax(_ptr(y), log2_size, _ptr(absmax), _stream(stream)), "thc_full_absmax")
+    return absmax
+
+
+def thc_full_encode(y, log2_size, seed, worker, bits, scale, payload, stream=None):
+    _check(lib().thc_full_encode(_ptr(y), log2_size, seed, worker, bits, _ptr(scale), _ptr(payload),
+                                 _stream(stream)), "thc_full_encode")
+    return payload
+
+
+def thc_full_decode(sums, scale, W, log2_size, bits, yhat, stream=None):
+    _check(lib().thc_full_decode(_ptr(sums), _ptr(scale), W, log2_size, bits, _ptr(yhat),
+                                 _stream(stream)), "thc_full_decode")
+    return yhat

@@ -447,4 +447,92 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
     return thc_sat_decode(aggregate, scale, W, n, chunk_log2, seed, bits, out, stream);
 }
 
+// --------------------------------------------------------------------- full rotation
+static int check_full(uint64_t n, uint32_t log2_size) {
+    if (log2_size < 15 || log2_size > 33) return THC_ERR_CHUNK;
+    if (n > (1ull << log2_size)) return THC_ERR_SIZE;
+    return THC_OK;
+}
+
+static float full_factor(uint32_t log2_size) {
+    // the chunk kernels already multiply by 2^-7; what is left of fl(2^(-l/2)) is that
+    // constant times 2^7 (exact), so the product equals a single multiplication by it
+    return (float)(1.0 / sqrt((double)(1ull << log2_size))) * 128.0f;
+}
+
+uint32_t thc_full_log2(uint64_t n) {
+    uint32_t l = 15;
+    while (l < 33 && (1ull << l) < n) ++l;
+    return (1ull << l) >= n ? l : 0;
+}
+
+int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                     float* y, void* stream) {
+    int rc = check_full(n, log2_size);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (!y || (n != 0 && !x)) return THC_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(y, 16)) return THC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ChunkArgs a = base_args(n, 14, seed);
+    a.in = x;
+    a.out = y;
+    a.in_bf16 = dt == THC_BF16;
+    if (n != 0 && thc::launch_fast14(Mode::Forward, a, st) != hipSuccess) return THC_ERR_HIP;
+    const uint64_t total = 1ull << log2_size;
+    if (total > a.padded &&
+        thc::launch_zero_words(reinterpret_cast<uint32_t*>(y + a.padded), total - a.padded, st) != hipSuccess)
+        return THC_ERR_HIP;
+    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), nullptr, 0, a.key0,
+                                          a.key1, st));
+}
+
+int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, float* x, void* stream) {
+    int rc = check_full(n, log2_size);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!y || !x) return THC_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(y, 16)) return THC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint64_t total = 1ull << log2_size;
+    ChunkArgs a = base_args(total, 14, seed);
+    a.in = y;
+    a.out = y;
+    if (thc::launch_fast14(Mode::Plain, a, st) != hipSuccess) return THC_ERR_HIP;
+    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), x, n, a.key0, a.key1, st));
+}
+
+int thc_full_absmax(const float* y, uint32_t log2_size, float* absmax, void* stream) {
+    int rc = check_full(0, log2_size);
+    if (rc != THC_OK) return rc;
+    if (!y || !absmax) return THC_ERR_NULL;
+    if (!aligned(y, 16) || !aligned(absmax, 4)) return THC_ERR_ALIGN;
+    return finish(thc::launch_full_absmax(y, log2_size, absmax, static_cast<hipStream_t>(stream)));
+}
+
+int thc_full_encode(const float* y, uint32_t log2_size, uint64_t seed, uint32_t worker, uint32_t bits,
+                    const float* scale, uint8_t* payload, void* stream) {
+    int rc = check_full(0, log2_size);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (!y || !scale || !payload) return THC_ERR_NULL;
+    if (!aligned(y, 16) || !aligned(scale, 4) || !aligned(payload, 16)) return THC_ERR_ALIGN;
+    return finish(thc::launch_full_encode(y, log2_size, scale, thc::grid_levels(bits, false), bits, worker,
+                                          (uint32_t)seed, (uint32_t)(seed >> 32), payload,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t log2_size, uint32_t bits,
+                    float* yhat, void* stream) {
+    int rc = check_full(0, log2_size);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    const uint32_t sum_bytes = thc_sum_bytes(W, bits);
+    if (sum_bytes == 0) return THC_ERR_WORKERS;
+    if (!sums || !scale || !yhat) return THC_ERR_NULL;
+    if (!aligned(sums, 16) || !aligned(scale, 4) || !aligned(yhat, 16)) return THC_ERR_ALIGN;
+    return finish(thc::launch_full_decode(sums, sum_bytes, log2_size, scale, thc::grid_levels(bits, false), W,
+                                          yhat, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -396,12 +396,13 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
 
 // Output side of the inverse rotation: x = D (v * 2^-7) from layout L4d; the first
 // `valid` coordinates of the chunk are stored.
+template <bool SIGNED = true>
 __device__ __forceinline__ void store_signed_l4d(const SignTable& tab, const float (&v)[kRegs], float* out,
                                                  uint32_t valid, uint32_t t) {
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
         const uint32_t i0 = h * 2048u + t * 4u;
-        const uint32_t sb = tab.sgn[i0 >> 5] >> (i0 & 31u);   // bits 0..3: signs of the 4 coordinates
+        const uint32_t sb = SIGNED ? tab.sgn[i0 >> 5] >> (i0 & 31u) : 0u;   // bits 0..3: signs of the 4 coordinates
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)

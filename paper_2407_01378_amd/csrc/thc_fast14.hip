@@ -61,7 +61,8 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
 // Inverse direction, one chunk per workgroup.
 //   SRC 0: rotated fp32 values (rht_inverse);  1: u8 sums;  2: u16 sums (thc_decode);
 //       3: packed saturated aggregate, offset binary (thc_sat_decode)
-template <int SRC>
+//   SIGNED false: no sign diagonal on output (a pass of the full rotation)
+template <int SRC, bool SIGNED = true>
 __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     __shared__ Shared sh;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     const uint64_t left = a.n - g0;
     const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
     float v[kRegs];
-    fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
+    if (SIGNED) fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
     if constexpr (SRC == 0) {
         Raw<8> raw;   // y is complete (padded), so every unit exists
         load_raw<8, 4>(raw, static_cast<const float*>(a.in) + g0, (uint32_t)kChunk, t);
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     }
     rotate_l1_to_l3<false>(sh, v, lane, wave);
     l3_to_l4d<false>(sh, v, lane, wave);
-    store_signed_l4d(sh.sign[0], v, static_cast<float*>(a.out) + g0, valid, t);
+    store_signed_l4d<SIGNED>(sh.sign[0], v, static_cast<float*>(a.out) + g0, valid, t);
 }
 
 template <bool BF16, Mode MODE>
@@ -171,6 +172,9 @@ hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
                              : launch_bits<false, Mode::Encode>(a, grid, stream);
         case Mode::Inverse:
             hipLaunchKernelGGL(inverse_kernel<0>, grid, dim3(kThreads), 0, stream, a);
+            return hipGetLastError();
+        case Mode::Plain:
+            hipLaunchKernelGGL((inverse_kernel<0, false>), grid, dim3(kThreads), 0, stream, a);
             return hipGetLastError();
         case Mode::Decode:
             if (a.sat)

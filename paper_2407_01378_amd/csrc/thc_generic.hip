@@ -377,6 +377,8 @@ hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream) {
         case Mode::Decode:
             hipLaunchKernelGGL(generic_kernel<Mode::Decode>, grid, block, 0, stream, a);
             break;
+        case Mode::Plain:
+            return hipErrorInvalidValue;   // only the tuned chunk-2^14 kernels implement it
     }
     return hipGetLastError();
 }

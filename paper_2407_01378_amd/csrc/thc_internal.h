@@ -8,7 +8,8 @@
 
 namespace thc {
 
-enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4 };
+// Plain: unsigned, fp32 to fp32 chunk transform (first pass of the full inverse rotation).
+enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4, Plain = 5 };
 
 // Largest grid index of the two quantization grids: 2^bits points for exact sums,
 // 2^bits - 1 points (signed symmetric, centre M = 2^(bits-1) - 1) for saturating sums.
@@ -111,6 +112,16 @@ hipError_t launch_sat_aggregate_decode_fused(const SatAggDecodeArgs& a, const Fu
 hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
                                 uint64_t payload_bytes, uint64_t padded, uint8_t* aggregate,
                                 unsigned long long* overflow, hipStream_t stream);
+
+// ---- full rotation (thc_full.hip) -----------------------------------------------------
+hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
+                              uint32_t key0, uint32_t key1, hipStream_t stream);
+hipError_t launch_full_absmax(const float* y, uint32_t log2_size, float* absmax, hipStream_t stream);
+hipError_t launch_full_encode(const float* y, uint32_t log2_size, const float* scale, uint32_t levels,
+                              uint32_t bits, uint32_t worker, uint32_t key0, uint32_t key1,
+                              uint8_t* payload, hipStream_t stream);
+hipError_t launch_full_decode(const void* sums, uint32_t sum_bytes, uint32_t log2_size, const float* scale,
+                              uint32_t levels, uint32_t W, float* yhat, hipStream_t stream);
 
 constexpr int kMaxAggBatch = 16;
 struct PayloadBatch {

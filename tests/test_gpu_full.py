@@ -1,0 +1,102 @@
+"""Full rotation (one chunk = the whole padded gradient) on the GPU against the oracle run
+with chunk_log2 = log2_size: rotated values, payloads, sums and output bit-identical to
+the fp32 canonical order; output within 1e-5 relative L2 of the float64 definition."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import thc as O
+from synth import to_numpy_bits
+
+from gpu_util import DEV, sums_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(n, dtype, seed, scale=1e-3):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    x = torch.randn(n, generator=g, device=DEV)
+    x = x / torch.sqrt((torch.randn(3, n, generator=g, device=DEV) ** 2).mean(dim=0))
+    return (x * scale).to(dtype)
+
+
+@pytest.mark.parametrize("l,n,dtype", [
+    (15, 1 << 15, torch.float32), (15, 20_001, torch.bfloat16), (16, 40_000, torch.float32),
+    (17, 100_003, torch.bfloat16), (20, 777_777, torch.float32), (23, (1 << 23) - 5, torch.bfloat16),
+    (24, 9_000_001, torch.float32), (18, 1, torch.float32), (19, (1 << 14) + 1, torch.bfloat16),
+])
+def test_full_rotation_forward_and_inverse(l, n, dtype):
+    print(f"full rotation l={l} n={n} dtype={dtype}", flush=True)
+    assert thc.thc_full_log2(n) <= l
+    x = _rand(n, dtype, 11 * l)
+    size = 1 << l
+    y = torch.full((size,), float("nan"), device=DEV)
+    thc.rht_forward_full(x, l, 7, y)
+    torch.cuda.synchronize()
+    hx = to_numpy_bits(x)
+    bf16 = dtype == torch.bfloat16
+    ref = O.rht_forward(hx, l, 7, dtype=np.float32, bf16=bf16)
+    got = y.cpu().numpy()
+    assert (got == ref).all(), f"{int((got != ref).sum())} rotated values differ"
+    y64 = O.rht_forward(hx, l, 7, dtype=np.float64, bf16=bf16)
+    assert np.linalg.norm(got - y64) <= 1e-5 * np.linalg.norm(y64)
+
+    back = torch.full((n,), float("nan"), device=DEV)
+    thc.rht_inverse_full(y, n, l, 7, back)     # y is scratch from here on
+    torch.cuda.synchronize()
+    ref_back = O.rht_inverse(ref, n, l, 7, dtype=np.float32)
+    assert (back.cpu().numpy() == ref_back).all()
+    xf = x.float().cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(back.cpu().numpy() - xf) <= 1e-5 * max(np.linalg.norm(xf), 1e-30)
+
+
+@pytest.mark.parametrize("l,n,W,bits,dtype", [
+    (15, 30_000, 3, 4, torch.float32), (18, 200_001, 4, 4, torch.bfloat16),
+    (21, 1_500_000, 2, 8, torch.bfloat16), (16, 1 << 16, 18, 4, torch.float32), (17, 99_999, 3, 2, torch.float32),
+])
+def test_full_rotation_pipeline_matches_oracle(l, n, W, bits, dtype):
+    print(f"full pipeline l={l} n={n} W={W} bits={bits} dtype={dtype}", flush=True)
+    size = 1 << l
+    xs = [_rand(n, dtype, 100 * l + w, scale=10.0 ** (-1 - (w % 3))) for w in range(W)]
+    absmax = torch.empty(W, device=DEV)
+    scale = torch.empty(1, device=DEV)
+    ys = [torch.empty(size, device=DEV) for _ in range(W)]
+    nb = size * bits // 8
+    payloads = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    sb = thc.thc_sum_bytes(W, bits)
+    sums = torch.empty(size, dtype=torch.uint8 if sb == 1 else torch.int16, device=DEV)
+    out = torch.empty(n, device=DEV)
+    for w in range(W):
+        thc.rht_forward_full(xs[w], l, 9, ys[w])
+        thc.thc_full_absmax(ys[w], l, absmax[w:w + 1])
+    thc.thc_scale_reduce(absmax, W, 1, scale)
+    for w in range(W):
+        thc.thc_full_encode(ys[w], l, 9, w, bits, scale, payloads[w])
+    thc.thc_aggregate(payloads, size, 14, bits, sums)
+    yhat = ys[0]
+    thc.thc_full_decode(sums, scale, W, l, bits, yhat)
+    thc.rht_inverse_full(yhat, n, l, 9, out)
+    torch.cuda.synchronize()
+
+    bf16 = dtype == torch.bfloat16
+    ref = O.pipeline([to_numpy_bits(x) for x in xs], l, 9, bits, dtype=np.float32, bf16=bf16)
+    assert scale.cpu().numpy()[0] == ref["scale"][0]
+    for w in range(W):
+        assert (payloads[w].cpu().numpy() == ref["payloads"][w]).all(), f"payload {w}"
+    assert (sums_to_numpy(sums) == ref["sums"]).all()
+    assert (out.cpu().numpy() == ref["out"]).all()
+    d64 = O.decode(ref["sums"], ref["scale"].astype(np.float64), W, n, l, 9, bits)
+    assert np.linalg.norm(out.cpu().numpy() - d64) <= 1e-5 * np.linalg.norm(d64)
+
+
+def test_full_rotation_argument_checks():
+    y = torch.empty(1 << 15, device=DEV)
+    x = torch.empty(100, device=DEV)
+    with pytest.raises(thc.ThcError):
+        thc.rht_forward_full(x, 14, 0, y)          # log2_size below 15
+    with pytest.raises(thc.ThcError):
+        thc.rht_forward_full(torch.empty((1 << 15) + 4, device=DEV), 15, 0, y)   # n > 2^l
+    with pytest.raises(thc.ThcError):
+        thc.rht_forward_full(x[1:], 15, 0, y)      # x not 16-byte aligned

@@ -197,3 +197,26 @@ def test_rotation_makes_heavy_tails_look_normal():
     assert k_in > 6
     assert abs(k_out - 3) < 0.3
     assert np.abs(y).max() < np.abs(x).max()
+
+
+def test_full_rotation_splits_into_chunk_stages_then_a_small_hadamard_across_chunks():
+    """H_(2^17) = H_8 (x) H_(2^14): the 17 stages of a full rotation are the 14 stages inside
+    every 2^14 chunk followed by an 8-point Hadamard matrix (closed form) across the 8
+    chunks.  Pins the oracle's stage structure above the largest chunk size."""
+    rng = np.random.default_rng(17)
+    x = rng.normal(size=1 << 17)
+    full = fwht(x.copy())
+    per_chunk = fwht(x.copy().reshape(8, 1 << 14))              # stages 0..13, chunk by chunk
+    H8 = np.array([[(-1) ** bin(i & j).count("1") for j in range(8)] for i in range(8)], dtype=np.float64)
+    want = (H8 @ per_chunk).reshape(-1)
+    assert np.allclose(full, want, rtol=0, atol=1e-9 * np.abs(want).max())
+
+
+def test_full_rotation_through_the_public_functions_is_an_isometry_and_inverts():
+    rng = np.random.default_rng(5)
+    n, l = 100_000, 17
+    x = rng.normal(size=n).astype(np.float32)
+    y = rht_forward(x, l, 3)
+    assert y.size == 1 << l
+    assert abs(np.linalg.norm(y) - np.linalg.norm(x.astype(np.float64))) < 1e-9 * np.linalg.norm(x)
+    assert np.allclose(rht_inverse(y, n, l, 3), x, rtol=0, atol=1e-12)
