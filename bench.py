@@ -19,6 +19,9 @@ of the same inputs.
     python bench.py --sat        the saturation-based aggregation variant (signed 2^b - 1 level
                                  grid, Sat in worker order, b-bit aggregate); also reports the
                                  overflow rate and the vNMSE next to the exact-sum path's
+    python bench.py --full-rotation   the paper's baseline: one rotation over the whole gradient
+                                 padded to 2^l (rotated data goes through HBM; separate
+                                 range / encode / aggregate / decode calls); no buckets
     python bench.py --probe      a few launches of each kernel of the first bucket plus a
                                  device-to-device copy of known size; meant to run under
                                  rocprofv3 --pmc so that counter readings of the kernels
@@ -57,6 +60,8 @@ def parse():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--sat", action="store_true", help="saturation-based aggregation variant")
+    ap.add_argument("--full-rotation", action="store_true",
+                    help="full rotation baseline (l' = l) instead of the chunked path")
     ap.add_argument("--workers", type=int, default=None,
                     help="simulate this many workers instead of the workload's own W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -147,6 +152,60 @@ class Path:
 
     def timed_out(self):
         return self.fused and any(self.thc.thc_encode_all_timed_out(it["ws"]) for it in self.items)
+
+
+class FullPath:
+    """The same method with ONE rotation over the whole gradient (l' = l)."""
+
+    def __init__(self, thc, torch, wl, bits, xs):
+        self.thc, self.torch, self.wl, self.bits, self.xs = thc, torch, wl, bits, xs
+        dev = xs[0].device
+        self.W, self.n = wl.W, wl.n
+        self.l = thc.thc_full_log2(wl.n)
+        size = 1 << self.l
+        self.size = size
+        self.ys = [torch.empty(size, dtype=torch.float32, device=dev) for _ in range(self.W)]
+        self.absmax = torch.empty(self.W, dtype=torch.float32, device=dev)
+        self.scale = torch.empty(1, dtype=torch.float32, device=dev)
+        self.payloads = [torch.empty(size * bits // 8, dtype=torch.uint8, device=dev) for _ in range(self.W)]
+        self.sum_bytes = thc.thc_sum_bytes(self.W, bits)
+        self.sums = torch.empty(size, dtype=torch.uint8 if self.sum_bytes == 1 else torch.int16, device=dev)
+        self.out = torch.empty(self.n, dtype=torch.float32, device=dev)
+        self.fused, self.sat = False, False
+        self.phases = {"rht_forward_full": (self.rotate, self.W), "full_absmax": (self.ranges, self.W),
+                       "full_encode": (self.encode, self.W), "aggregate": (self.aggregate, 1),
+                       "full_decode": (self.decode, 1), "rht_inverse_full": (self.inverse, 1)}
+        self.dominant = "rht_forward_full"
+        self.items = [None]
+
+    def rotate(self, _=None):
+        for w in range(self.W):
+            self.thc.rht_forward_full(self.xs[w], self.l, 0, self.ys[w])
+
+    def ranges(self, _=None):
+        for w in range(self.W):
+            self.thc.thc_full_absmax(self.ys[w], self.l, self.absmax[w:w + 1])
+        self.thc.thc_scale_reduce(self.absmax, self.W, 1, self.scale)
+
+    def encode(self, _=None):
+        for w in range(self.W):
+            self.thc.thc_full_encode(self.ys[w], self.l, 0, w, self.bits, self.scale, self.payloads[w])
+
+    def aggregate(self, _=None):
+        self.thc.thc_aggregate(self.payloads, self.size, 14, self.bits, self.sums)
+
+    def decode(self, _=None):
+        self.thc.thc_full_decode(self.sums, self.scale, self.W, self.l, self.bits, self.ys[0])
+
+    def inverse(self, _=None):
+        self.thc.rht_inverse_full(self.ys[0], self.n, self.l, 0, self.out)
+
+    def step(self):
+        for fn, _ in self.phases.values():
+            fn()
+
+    def timed_out(self):
+        return False
 
 
 def time_region(torch, fn, reps):
@@ -252,7 +311,10 @@ def main():
     W = wl.W
 
     xs = [generate(wl, w, dev) for w in range(W)]
-    path = Path(thc, torch, wl, bits, xs, fused=not a.unfused, sat=a.sat)
+    if a.full_rotation:
+        path = FullPath(thc, torch, wl, bits, xs)
+    else:
+        path = Path(thc, torch, wl, bits, xs, fused=not a.unfused, sat=a.sat)
     torch.cuda.synchronize()
     if a.probe:
         probe(torch, path, dev)
@@ -286,7 +348,13 @@ def main():
     # Dominant kernel and its algorithmic bytes per launch.  Per worker-coordinate the
     # encode step must read the gradient once and write its payload once.
     coords_per_launch = wl.n / nb
-    if path.fused:
+    if a.full_rotation:
+        # one rht_forward_full call: gradient in, rotated fp32 out (zero padding included),
+        # then every high pass reads and writes the whole rotated array
+        high = path.l - 14
+        dom_bytes = wl.n * s_in + path.size * 4 + ((high + 8) // 9) * path.size * 8
+        dom_name = "rht_forward_full"
+    elif path.fused:
         dom_bytes = coords_per_launch * W * (s_in + bits / 8.0)
         dom_name = "thc_encode_all"
     else:
@@ -295,7 +363,8 @@ def main():
     dom_s = kernels[path.dominant]["us_per_launch"] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
 
-    dom_ops = coords_per_launch * (W if path.fused else 1) * ENCODE_OPS_PER_COORD
+    dom_ops = (path.size * (path.l + 2.0) if a.full_rotation
+               else coords_per_launch * (W if path.fused else 1) * ENCODE_OPS_PER_COORD)
     alu_achieved = dom_ops / dom_s / 1e12
     copy_gbs = copy_bandwidth(torch, dev)
 
@@ -313,7 +382,8 @@ def main():
         "config": {"workload": wl.name, "W": W, "n": wl.n, "input": wl.dtype, "bits": bits,
                    "chunk_log2": wl.chunk_log2, "buckets": nb, "bucket_elems": wl.bucket or wl.n,
                    "form": "fused" if path.fused else "unfused",
-                   "aggregation": "saturating" if a.sat else "exact"},
+                   "aggregation": "saturating" if a.sat else "exact",
+                   "rotation": f"full, 2^{path.l}" if a.full_rotation else "partial"},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(wl.name, bits, dom_name)},
@@ -329,6 +399,16 @@ def main():
                          "frac_of_copy": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / copy_gbs, 4)},
         "kernels": kernels,
     }
+    if a.full_rotation:
+        path.step()   # the per-kernel loops above left scratch in the buffers: one clean pass
+        torch.cuda.synchronize()
+        mean = torch.zeros(wl.n, dtype=torch.float32, device=dev)
+        for x in xs:
+            mean += x.float()
+        mean /= W
+        res["vnmse"] = float(((path.out - mean) ** 2).sum() / (mean ** 2).sum())
+    if path.fused and not a.sat:
+        res["vnmse_first_bucket"] = vnmse(torch, path, path.items[0])
     if a.sat:
         # quality of the variant on the first bucket, next to the exact-sum path's
         it = path.items[0]
