@@ -229,6 +229,34 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
                              uint8_t* aggregate, unsigned long long* overflow_count, float* out,
                              void* stream);
 
+/* ---- min/max range (the paper's literal wording: "the value range between the minimum
+ * and maximum gradient values is equally split", "the value range max_p - min_p of each
+ * chunk p"), with the rotation optional (the "No Rotation" column of the THC throughput
+ * table) and an optional bf16 output -----------------------------------------------------
+ * range arrays hold (lo, hi) pairs, 2 floats per chunk, 8-byte aligned.  The grid of a chunk
+ * has 2^bits points, index 0 at lo and index L at hi, shared by all workers:
+ *     inv = L / (hi - lo)  (0 when hi == lo),  idx = min(floor((y - lo) * inv + u), L)
+ *     step = (hi - lo) / L,  yhat = float(sum) * (step / W) + lo
+ * rotate != 0: y is the chunk's rotated gradient as in thc_encode; rotate == 0: y is the
+ * zero-padded gradient itself (no sign diagonal, no butterflies, no normalisation).
+ * Payloads and sums have the formats of thc_encode / thc_aggregate (use thc_aggregate). */
+
+/* range[2p], range[2p+1] = min, max over chunk p of one worker's y. */
+int thc_chunk_minmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                     int rotate, float* range, void* stream);
+
+/* Shared ranges: range_all holds W arrays of `chunks` pairs back to back; range receives
+ * (min over workers of lo, max over workers of hi) per chunk. */
+int thc_range_reduce(const float* range_all, uint32_t W, uint64_t chunks, float* range, void* stream);
+
+int thc_encode_minmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                      uint32_t worker, uint32_t bits, int rotate, const float* range, uint8_t* payload,
+                      void* stream);
+
+/*   out_dt  THC_F32 or THC_BF16 (fp32 result rounded to nearest, ties to even);  out  n values */
+int thc_decode_minmax(const void* sums, const float* range, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                      uint64_t seed, uint32_t bits, int rotate, thc_dtype out_dt, void* out, void* stream);
+
 /* ---- full rotation (l' = l): the baseline the paper's "Partial rotation" paragraph and
  * its THC throughput table compare against ---------------------------------------------
  * The whole gradient, zero-padded to 2^log2_size coordinates ("Gradients are padded to

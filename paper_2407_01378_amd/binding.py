@@ -57,6 +57,17 @@ _SIGNATURES = {
                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]),
+    "thc_chunk_minmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                        ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_range_reduce": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64,
+                                        ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_encode_minmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                         ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_decode_minmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                         ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                         ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_void_p]),
     "thc_full_log2": (ctypes.c_uint32, [ctypes.c_uint64]),
     "rht_forward_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
@@ -369,3 +380,33 @@ def thc_full_decode(sums, scale, W, log2_size, bits, yhat, stream=None):
     _check(lib().thc_full_decode(_ptr(sums), _ptr(scale), W, log2_size, bits, _ptr(yhat),
                                  _stream(stream)), "thc_full_decode")
     return yhat
+
+
+# -------------------------------------------------------------------- min/max range
+def thc_chunk_minmax(grad, chunk_log2, seed, rotate, range_out, stream=None):
+    _flat(grad), _flat(range_out, torch.float32)
+    _check(lib().thc_chunk_minmax(_ptr(grad), _dtype_code(grad), grad.numel(), chunk_log2, seed,
+                                  int(bool(rotate)), _ptr(range_out), _stream(stream)), "thc_chunk_minmax")
+    return range_out
+
+
+def thc_range_reduce(range_all, W, chunks, range_out, stream=None):
+    _check(lib().thc_range_reduce(_ptr(range_all), W, chunks, _ptr(range_out), _stream(stream)),
+           "thc_range_reduce")
+    return range_out
+
+
+def thc_encode_minmax(grad, chunk_log2, seed, worker, bits, rotate, range_, payload, stream=None):
+    _flat(grad), _flat(payload, torch.uint8)
+    _check(lib().thc_encode_minmax(_ptr(grad), _dtype_code(grad), grad.numel(), chunk_log2, seed, worker,
+                                   bits, int(bool(rotate)), _ptr(range_), _ptr(payload), _stream(stream)),
+           "thc_encode_minmax")
+    return payload
+
+
+def thc_decode_minmax(sums, range_, W, n, chunk_log2, seed, bits, rotate, out, stream=None):
+    _flat(out)
+    _check(lib().thc_decode_minmax(_ptr(sums), _ptr(range_), W, n, chunk_log2, seed, bits,
+                                   int(bool(rotate)), _dtype_code(out), _ptr(out), _stream(stream)),
+           "thc_decode_minmax")
+    return out

@@ -447,6 +447,81 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
     return thc_sat_decode(aggregate, scale, W, n, chunk_log2, seed, bits, out, stream);
 }
 
+// ------------------------------------------------------------------ min/max range
+int thc_chunk_minmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                     int rotate, float* range, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!grad || !range) return THC_ERR_NULL;
+    if (!aligned(grad, dt == THC_F32 ? 4 : 2) || !aligned(range, 8)) return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = grad;
+    a.out = range;
+    a.in_bf16 = dt == THC_BF16;
+    a.no_rotate = rotate ? 0u : 1u;
+    return finish(thc::launch_chunks(Mode::MinMax, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_range_reduce(const float* range_all, uint32_t W, uint64_t chunks, float* range, void* stream) {
+    if (W == 0) return THC_ERR_WORKERS;
+    if (chunks > kMaxCoords || (uint64_t)W * chunks > kMaxCoords) return THC_ERR_SIZE;
+    if (chunks == 0) return THC_OK;
+    if (!range_all || !range) return THC_ERR_NULL;
+    if (!aligned(range_all, 8) || !aligned(range, 8)) return THC_ERR_ALIGN;
+    return finish(thc::launch_range_reduce(range_all, W, chunks, range, static_cast<hipStream_t>(stream)));
+}
+
+int thc_encode_minmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
+                      uint32_t worker, uint32_t bits, int rotate, const float* range, uint8_t* payload,
+                      void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!grad || !payload || !range) return THC_ERR_NULL;
+    if (!aligned(grad, dt == THC_F32 ? 4 : 2) || !aligned(payload, 16) || !aligned(range, 8))
+        return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = grad;
+    a.out = payload;
+    a.range_in = range;
+    a.in_bf16 = dt == THC_BF16;
+    a.worker = worker;
+    a.bits = bits;
+    a.levels = thc::grid_levels(bits, false);
+    a.payload_bytes = (a.padded * bits + 7) / 8;
+    a.no_rotate = rotate ? 0u : 1u;
+    return finish(thc::launch_chunks(Mode::Encode, a, static_cast<hipStream_t>(stream)));
+}
+
+int thc_decode_minmax(const void* sums, const float* range, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                      uint64_t seed, uint32_t bits, int rotate, thc_dtype out_dt, void* out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc == THC_OK) rc = check_dtype(out_dt);
+    if (rc != THC_OK) return rc;
+    const uint32_t sum_bytes = thc_sum_bytes(W, bits);
+    if (sum_bytes == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!sums || !range || !out) return THC_ERR_NULL;
+    if (!aligned(sums, 16) || !aligned(range, 8) || !aligned(out, out_dt == THC_F32 ? 4 : 2))
+        return THC_ERR_ALIGN;
+    ChunkArgs a = base_args(n, chunk_log2, seed);
+    a.in = sums;
+    a.out = out;
+    a.range_in = range;
+    a.bits = bits;
+    a.levels = thc::grid_levels(bits, false);
+    a.W = W;
+    a.sum_bytes = sum_bytes;
+    a.no_rotate = rotate ? 0u : 1u;
+    a.out_bf16 = out_dt == THC_BF16;
+    return finish(thc::launch_chunks(Mode::Decode, a, static_cast<hipStream_t>(stream)));
+}
+
 // --------------------------------------------------------------------- full rotation
 static int check_full(uint64_t n, uint32_t log2_size) {
     if (log2_size < 15 || log2_size > 33) return THC_ERR_CHUNK;

@@ -312,6 +312,38 @@ __device__ __forceinline__ float chunk_absmax(Shared& sh, const float (&v)[kRegs
     return m;
 }
 
+// (min, max) of v over the whole chunk (every thread returns both).  Two barriers.
+struct MinMax {
+    float lo, hi;
+};
+__device__ __forceinline__ MinMax chunk_minmax(Shared& sh, const float (&v)[kRegs], uint32_t lane,
+                                               uint32_t wave) {
+    float lo = v[0], hi = v[0];
+#pragma unroll
+    for (int i = 1; i < kRegs; ++i) {
+        lo = fminf(lo, v[i]);
+        hi = fmaxf(hi, v[i]);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, o, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+    }
+    float* red_lo = reinterpret_cast<float*>(sh.sign[1].sgn);   // second table: free in one-chunk kernels
+    if (lane == 0) {
+        sh.red[wave] = hi;
+        red_lo[wave] = lo;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        hi = fmaxf(hi, sh.red[k]);
+        lo = fminf(lo, red_lo[k]);
+    }
+    __syncthreads();
+    return MinMax{lo, hi};
+}
+
 // L3 -> L4e through the buffer (two barriers); v then holds coordinates 32 t .. 32 t + 31.
 template <bool PRIO>
 __device__ __forceinline__ void l3_to_l4e(Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
@@ -383,6 +415,27 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
         quantize_pack<BITS, CLAMP, true>(v, s * 128.0f, inv * kInvSqrtC, L, g, worker, key0, key1, pk);
     else
         quantize_pack<BITS, CLAMP, false>(v, s, inv, L, g, worker, key0, key1, pk);
+    uint8_t* dst = payload + (g * BITS) / 8u;
+    if constexpr (BITS == 8) {
+        reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        reinterpret_cast<uint4*>(dst)[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+    } else if constexpr (BITS == 4) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    } else {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
+    }
+}
+
+// The same on a min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo).
+template <int BITS>
+__device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], float lo, float hi, uint32_t L,
+                                                     uint64_t g0, uint32_t worker, uint32_t key0,
+                                                     uint32_t key1, uint8_t* payload, uint32_t t) {
+    const float width = hi - lo;
+    const float inv = width != 0.0f ? (float)L / width : 0.0f;
+    const uint64_t g = g0 + (uint64_t)t * 32u;
+    uint32_t pk[BITS];
+    quantize_pack<BITS, true, false>(v, -lo, inv, L, g, worker, key0, key1, pk);   // y + (-lo) == y - lo
     uint8_t* dst = payload + (g * BITS) / 8u;
     if constexpr (BITS == 8) {
         reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);

@@ -45,6 +45,17 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
     } else if constexpr (MODE == Mode::Absmax) {
         const float m = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
         if (t == 0) static_cast<float*>(a.out)[p] = m;
+    } else if constexpr (MODE == Mode::MinMax) {
+        const MinMax r = chunk_minmax(sh, v, lane, wave);
+        if (t == 0) {
+            static_cast<float*>(a.out)[2 * p] = r.lo * kInvSqrtC;
+            static_cast<float*>(a.out)[2 * p + 1] = r.hi * kInvSqrtC;
+        }
+    } else if (a.range_in) {   // Encode on the min/max grid
+        const float lo = a.range_in[2 * p], hi = a.range_in[2 * p + 1];
+        l3_to_l4e<false>(sh, v, lane, wave);
+        quantize_store_range<BITS>(v, lo, hi, a.levels, g0, a.worker, a.key0, a.key1,
+                                   static_cast<uint8_t*>(a.out), t);
     } else {
         float s;
         if (a.scale_in) {
@@ -79,8 +90,11 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
         __syncthreads();
         lds_to_l1<8, false>(sh, sh.sign[0], v, t);
     } else {
-        const float s = a.scale_in[p];
-        const float step = (s + s) / (float)a.levels;
+        // symmetric grid: yhat = S q - s;  min/max grid: yhat = S q + lo
+        const bool ranged = a.range_in != nullptr;
+        const float lo = ranged ? a.range_in[2 * p] : 0.0f;
+        const float s = ranged ? -lo : a.scale_in[p];
+        const float step = (ranged ? a.range_in[2 * p + 1] - lo : s + s) / (float)a.levels;
         const float q = step / (float)a.W;
         if constexpr (SRC == 3) {
             // 32 coordinates = 4 * bits bytes per thread
@@ -153,6 +167,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool fast14_applicable(Mode mode, const ChunkArgs& a) {
     if (a.chunk_log2 != 14) return false;
     if ((a.padded >> 14) > 0x7FFFFFFFull) return false;
+    if (a.no_rotate || a.out_bf16 || mode == Mode::Plain) return false;
     return k14::aligned16(a.in) && k14::aligned16(a.out);
 }
 
@@ -167,6 +182,9 @@ hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
         case Mode::Absmax:
             return a.in_bf16 ? launch_bits<true, Mode::Absmax>(a, grid, stream)
                              : launch_bits<false, Mode::Absmax>(a, grid, stream);
+        case Mode::MinMax:
+            return a.in_bf16 ? launch_bits<true, Mode::MinMax>(a, grid, stream)
+                             : launch_bits<false, Mode::MinMax>(a, grid, stream);
         case Mode::Encode:
             return a.in_bf16 ? launch_bits<true, Mode::Encode>(a, grid, stream)
                              : launch_bits<false, Mode::Encode>(a, grid, stream);

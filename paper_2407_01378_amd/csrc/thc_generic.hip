@@ -23,6 +23,7 @@ template <Mode MODE>
 __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
     __shared__ float buf[kTile];
     __shared__ float red[kThreads];
+    __shared__ float red_lo[kThreads];
     __shared__ uint32_t sgn[kTile / 32];
 
     const uint32_t t = threadIdx.x;
@@ -32,7 +33,8 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
     const uint32_t c = 1u << l;
     const uint64_t chunks = a.padded >> l;
     constexpr bool kFromGradient =
-        MODE == Mode::Forward || MODE == Mode::Absmax || MODE == Mode::Encode;
+        MODE == Mode::Forward || MODE == Mode::Absmax || MODE == Mode::Encode || MODE == Mode::MinMax;
+    const bool rotate = a.no_rotate == 0u;
 
     // Sign diagonal of the tile: 128 Philox blocks of 128 bits each.
     if (t < kTile / 128) {
@@ -74,6 +76,16 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
             const uint64_t g = g0 + j;
             float val = 0.0f;
             if (g < a.padded) {
+                if (a.range_in) {   // min/max grid: yhat = S * (step / W) + lo
+                    const float lo = a.range_in[2 * (g >> l)], hi = a.range_in[2 * (g >> l) + 1];
+                    const float step = (hi - lo) / Lf;
+                    const float q = step / Wf;
+                    const uint32_t S = a.sum_bytes == 1
+                                           ? (uint32_t) static_cast<const uint8_t*>(a.in)[g]
+                                           : (uint32_t) static_cast<const uint16_t*>(a.in)[g];
+                    v[j] = (float)S * q + lo;
+                    continue;
+                }
                 const float s = a.scale_in[g >> l];
                 const float step = (s + s) / Lf;
                 const float q = step / Wf;
@@ -95,14 +107,16 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
     __syncthreads();  // sgn[] is complete
     const uint32_t sbits = (sgn[(t * kEpt) >> 5] >> ((t * kEpt) & 31u)) & 0xFFFFu;
     if constexpr (kFromGradient) {
+        if (rotate) {
 #pragma unroll
-        for (int j = 0; j < kEpt; ++j) v[j] = flip_sign(v[j], (sbits >> j) & 1u);
+            for (int j = 0; j < kEpt; ++j) v[j] = flip_sign(v[j], (sbits >> j) & 1u);
+        }
     }
 
     // Stages with stride 1, 2, 4, 8: both partners live in this thread.
 #pragma unroll
     for (int h = 1; h < kEpt; h <<= 1) {
-        if ((uint32_t)h < c) {
+        if ((uint32_t)h < c && rotate) {
 #pragma unroll
             for (int i = 0; i < kEpt; ++i) {
                 if ((i & h) == 0) {
@@ -114,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
         }
     }
     // Stages with stride >= 16 through LDS, one barrier per stage.
-    if (c > (uint32_t)kEpt) {
+    if (c > (uint32_t)kEpt && rotate) {
 #pragma unroll
         for (int j = 0; j < kEpt; ++j) buf[t * kEpt + j] = v[j];
         for (uint32_t h = kEpt; h < c; h <<= 1) {
@@ -132,8 +146,10 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
 #pragma unroll
         for (int j = 0; j < kEpt; ++j) v[j] = buf[t * kEpt + j];
     }
+    if (rotate) {
 #pragma unroll
-    for (int j = 0; j < kEpt; ++j) v[j] = v[j] * a.inv_sqrt_c;
+        for (int j = 0; j < kEpt; ++j) v[j] = v[j] * a.inv_sqrt_c;
+    }
 
     if constexpr (MODE == Mode::Forward) {
         float* y = static_cast<float*>(a.out);
@@ -141,10 +157,69 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
         for (int j = 0; j < kEpt; ++j)
             if (g0 + j < a.padded) y[g0 + j] = v[j];
     } else if constexpr (MODE == Mode::Inverse || MODE == Mode::Decode) {
-        float* x = static_cast<float*>(a.out);
 #pragma unroll
-        for (int j = 0; j < kEpt; ++j)
-            if (g0 + j < a.n) x[g0 + j] = flip_sign(v[j], (sbits >> j) & 1u);
+        for (int j = 0; j < kEpt; ++j) {
+            if (g0 + j < a.n) {
+                const float val = rotate ? flip_sign(v[j], (sbits >> j) & 1u) : v[j];
+                if (a.out_bf16) {   // round to nearest, ties to even
+                    const uint32_t u = __float_as_uint(val);
+                    static_cast<uint16_t*>(a.out)[g0 + j] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+                } else {
+                    static_cast<float*>(a.out)[g0 + j] = val;
+                }
+            }
+        }
+    } else if constexpr (MODE == Mode::MinMax) {
+        // (min, max) of each chunk
+        float own_lo[kEpt], own_hi[kEpt];
+        if (c >= (uint32_t)kEpt) {
+            float mn = v[0], mx = v[0];
+#pragma unroll
+            for (int j = 1; j < kEpt; ++j) {
+                mn = fminf(mn, v[j]);
+                mx = fmaxf(mx, v[j]);
+            }
+            const uint32_t tpc = c / kEpt;  // threads per chunk
+            red[t] = mx;
+            red_lo[t] = mn;
+            for (uint32_t s = tpc >> 1; s >= 1; s >>= 1) {
+                __syncthreads();
+                if ((t & (tpc - 1u)) < s) {
+                    red[t] = fmaxf(red[t], red[t + s]);
+                    red_lo[t] = fminf(red_lo[t], red_lo[t + s]);
+                }
+            }
+            __syncthreads();
+            mx = red[t & ~(tpc - 1u)];
+            mn = red_lo[t & ~(tpc - 1u)];
+#pragma unroll
+            for (int j = 0; j < kEpt; ++j) {
+                own_lo[j] = mn;
+                own_hi[j] = mx;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kEpt; ++j) {
+                float mn = v[j], mx = v[j];
+#pragma unroll
+                for (int i = 0; i < kEpt; ++i)
+                    if ((uint32_t)(i >> l) == (uint32_t)(j >> l)) {
+                        mn = fminf(mn, v[i]);
+                        mx = fmaxf(mx, v[i]);
+                    }
+                own_lo[j] = mn;
+                own_hi[j] = mx;
+            }
+        }
+        float* dst = static_cast<float*>(a.out);
+#pragma unroll
+        for (int j = 0; j < kEpt; ++j) {
+            const uint64_t g = g0 + j;
+            if ((g & (uint64_t)(c - 1u)) == 0 && (g >> l) < chunks) {
+                dst[2 * (g >> l)] = own_lo[j];
+                dst[2 * (g >> l) + 1] = own_hi[j];
+            }
+        }
     } else {
         // Range of each chunk: largest |rotated value|.
         float own[kEpt];  // own[j]: absmax of the chunk that holds coordinate j
@@ -196,10 +271,20 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
             uint32_t pk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int j = 0; j < kEpt; ++j) {
-                const float s = s_el[j];
-                const float two = s + s;
-                const float inv = two != 0.0f ? Lf / two : 0.0f;
-                const float pos = (v[j] + s) * inv;
+                float pos;
+                if (a.range_in) {   // min/max grid
+                    const uint64_t p = (g0 + j) >> l;
+                    const float lo = p < chunks ? a.range_in[2 * p] : 0.0f;
+                    const float hi = p < chunks ? a.range_in[2 * p + 1] : 0.0f;
+                    const float width = hi - lo;
+                    const float inv = width != 0.0f ? Lf / width : 0.0f;
+                    pos = (v[j] - lo) * inv;
+                } else {
+                    const float s = s_el[j];
+                    const float two = s + s;
+                    const float inv = two != 0.0f ? Lf / two : 0.0f;
+                    pos = (v[j] + s) * inv;
+                }
                 const uint32_t r = (rb.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
                 const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
                 const float tt = pos + u;
@@ -354,6 +439,19 @@ __global__ __launch_bounds__(256) void scale_reduce_kernel(const float* absmax_a
     scale[p] = m;
 }
 
+__global__ __launch_bounds__(256) void range_reduce_kernel(const float* range_all, uint32_t W,
+                                                           uint64_t chunks, float* range) {
+    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= chunks) return;
+    float lo = range_all[2 * p], hi = range_all[2 * p + 1];
+    for (uint32_t w = 1; w < W; ++w) {
+        lo = fminf(lo, range_all[2 * ((uint64_t)w * chunks + p)]);
+        hi = fmaxf(hi, range_all[2 * ((uint64_t)w * chunks + p) + 1]);
+    }
+    range[2 * p] = lo;
+    range[2 * p + 1] = hi;
+}
+
 }  // namespace
 
 hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream) {
@@ -376,6 +474,9 @@ hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream) {
             break;
         case Mode::Decode:
             hipLaunchKernelGGL(generic_kernel<Mode::Decode>, grid, block, 0, stream, a);
+            break;
+        case Mode::MinMax:
+            hipLaunchKernelGGL(generic_kernel<Mode::MinMax>, grid, block, 0, stream, a);
             break;
         case Mode::Plain:
             return hipErrorInvalidValue;   // only the tuned chunk-2^14 kernels implement it
@@ -428,6 +529,16 @@ hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32
     else if (bits == 4) THC_SAT(4);
     else THC_SAT(8);
 #undef THC_SAT
+    return hipGetLastError();
+}
+
+hipError_t launch_range_reduce(const float* range_all, uint32_t W, uint64_t chunks, float* range,
+                               hipStream_t stream) {
+    if (chunks == 0) return hipSuccess;
+    const uint64_t blocks = (chunks + 255u) / 256u;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(range_reduce_kernel, dim3((uint32_t)blocks), dim3(256), 0, stream, range_all, W,
+                       chunks, range);
     return hipGetLastError();
 }
 

@@ -9,7 +9,8 @@
 namespace thc {
 
 // Plain: unsigned, fp32 to fp32 chunk transform (first pass of the full inverse rotation).
-enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4, Plain = 5 };
+// MinMax: per-chunk (min, max) of the rotated values (the min/max-range variant).
+enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4, Plain = 5, MinMax = 6 };
 
 // Largest grid index of the two quantization grids: 2^bits points for exact sums,
 // 2^bits - 1 points (signed symmetric, centre M = 2^(bits-1) - 1) for saturating sums.
@@ -33,6 +34,9 @@ struct ChunkArgs {
     uint32_t sum_bytes;     // decode: 1 or 2
     uint32_t levels;        // encode / decode: largest grid index L
     uint32_t sat;           // decode: 1 = `in` is the packed saturated aggregate (offset binary)
+    const float* range_in;  // encode / decode: (lo, hi) per chunk -> min/max grid; null -> symmetric
+    uint32_t no_rotate;     // 1: no sign diagonal, no butterflies, no normalisation
+    uint32_t out_bf16;      // inverse / decode: 1 = output is bf16 (round to nearest even)
     float inv_sqrt_c;       // fp32 nearest of c^(-1/2)
 };
 
@@ -133,6 +137,9 @@ hipError_t launch_aggregate(const PayloadBatch& batch, uint32_t count, bool accu
                             uint64_t padded, void* sums, hipStream_t stream);
 
 hipError_t launch_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
+                               hipStream_t stream);
+// (lo, hi) pairs: min of the workers' minima, max of their maxima.
+hipError_t launch_range_reduce(const float* range_all, uint32_t W, uint64_t chunks, float* range,
                                hipStream_t stream);
 
 }  // namespace thc
