@@ -22,6 +22,9 @@ of the same inputs.
     python bench.py --full-rotation   the paper's baseline: one rotation over the whole gradient
                                  padded to 2^l (rotated data goes through HBM; separate
                                  range / encode / aggregate / decode calls); no buckets
+    python bench.py --quality    vNMSE and time of one bucket for the grid / rotation variants:
+                                 symmetric range + partial rotation (the timed path), min/max
+                                 range + partial rotation, min/max range without rotation
     python bench.py --probe      a few launches of each kernel of the first bucket plus a
                                  device-to-device copy of known size; meant to run under
                                  rocprofv3 --pmc so that counter readings of the kernels
@@ -62,6 +65,8 @@ def parse():
     ap.add_argument("--sat", action="store_true", help="saturation-based aggregation variant")
     ap.add_argument("--full-rotation", action="store_true",
                     help="full rotation baseline (l' = l) instead of the chunked path")
+    ap.add_argument("--quality", action="store_true",
+                    help="vNMSE / time comparison of the range and rotation variants on one bucket")
     ap.add_argument("--workers", type=int, default=None,
                     help="simulate this many workers instead of the workload's own W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -273,6 +278,52 @@ def vnmse(torch, path, it):
     return float(((it["out"] - mean) ** 2).sum() / (mean ** 2).sum())
 
 
+def quality(thc, torch, wl, bits, xs, dev):
+    """One bucket through three variants of the method; vNMSE against the exact fp32 mean
+    and milliseconds per pass (HIP events, 5 repetitions after one warm-up)."""
+    st, ln = wl.buckets()[0]
+    W, l = wl.W, wl.chunk_log2
+    grads = [x[st:st + ln] for x in xs]
+    P = thc.thc_num_chunks(ln, l)
+    nb = thc.thc_payload_bytes(ln, l, bits)
+    sb = thc.thc_sum_bytes(W, bits)
+    payloads = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(W)]
+    sums = torch.empty(P << l, dtype=torch.uint8 if sb == 1 else torch.int16, device=dev)
+    out = torch.empty(ln, dtype=torch.float32, device=dev)
+    scale = torch.empty(P, dtype=torch.float32, device=dev)
+    ws = torch.empty(thc.thc_encode_all_workspace_bytes(W, ln, l), dtype=torch.uint8, device=dev)
+    ranges_all = torch.empty(W * P * 2, dtype=torch.float32, device=dev)
+    rng = torch.empty(P * 2, dtype=torch.float32, device=dev)
+    mean = torch.zeros(ln, dtype=torch.float32, device=dev)
+    for g in grads:
+        mean += g.float()
+    mean /= W
+
+    def symmetric():
+        thc.thc_encode_all(grads, l, 0, bits, payloads, scale, ws)
+        thc.thc_aggregate_decode(payloads, scale, ln, l, 0, bits, sums, out)
+
+    def minmax(rotate):
+        for w in range(W):
+            thc.thc_chunk_minmax(grads[w], l, 0, rotate, ranges_all[2 * w * P:2 * (w + 1) * P])
+        thc.thc_range_reduce(ranges_all, W, P, rng)
+        for w in range(W):
+            thc.thc_encode_minmax(grads[w], l, 0, w, bits, rotate, rng, payloads[w])
+        thc.thc_aggregate(payloads, ln, l, bits, sums)
+        thc.thc_decode_minmax(sums, rng, W, ln, l, 0, bits, rotate, out)
+
+    res = {}
+    for name, fn in (("symmetric_partial_rotation", symmetric),
+                     ("minmax_partial_rotation", lambda: minmax(True)),
+                     ("minmax_no_rotation", lambda: minmax(False))):
+        fn()
+        ms = time_region(torch, fn, 5)
+        err = float(((out - mean) ** 2).sum() / (mean ** 2).sum())
+        res[name] = {"vnmse": err, "ms_per_bucket": round(ms, 4),
+                     "gradient_GBps": round(W * ln * (2 if wl.dtype == "bf16" else 4) / (ms * 1e-3) / 1e9, 1)}
+    return {"workload": wl.name, "bucket_elems": ln, "W": W, "bits": bits, "variants": res}
+
+
 def read_traffic(workload_name, bits, kernel):
     """HBM bytes per launch of a kernel, measured offline with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
@@ -311,6 +362,9 @@ def main():
     W = wl.W
 
     xs = [generate(wl, w, dev) for w in range(W)]
+    if a.quality:
+        print(json.dumps(quality(thc, torch, wl, bits, xs, dev)))
+        return 0
     if a.full_rotation:
         path = FullPath(thc, torch, wl, bits, xs)
     else:
