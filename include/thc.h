@@ -295,6 +295,51 @@ int thc_full_encode(const float* y, uint32_t log2_size, uint64_t seed, uint32_t 
 int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t log2_size, uint32_t bits,
                     float* yhat, void* stream);
 
+/* ---- TopK Chunked (TopKC), "Our proposed improvement: Chunks" of the paper's TopK case
+ * study: the all-reduce-compatible sparsifier ------------------------------------------
+ * The gradient of n coordinates is cut into P = ceil(n / C) chunks of C coordinates (C a
+ * power of two, 8 <= C <= 512, zero padding at the end).  Steps and the readings taken
+ * where the paper is silent:
+ *   1. topkc_chunk_norms  each worker: squared L2 norm of every chunk, in half precision
+ *        (squares and their sum in fp32, summed as a balanced tree over adjacent pairs,
+ *        then rounded to fp16, nearest even);
+ *   2. topkc_sum_norms    s_p = sum over workers, as an fp16 all-reduce would compute it:
+ *        fp16 accumulation in worker order, one rounding per addition;
+ *   3. topkc_select       the J chunks with the largest s_p, equal values lowest index
+ *        first; indices are returned in ascending order;
+ *   4. topkc_gather_sum   the selected chunks of every worker rounded to fp16 and summed
+ *        in fp16 in worker order (the FP16 all-reduce of the sparsified gradients);
+ *   5. topkc_scatter_mean dense fp32 estimate of the mean gradient: float(sum) / W on the
+ *        selected chunks, 0 elsewhere.
+ * Cost on the wire: 16 (J C / n + 1 / C) bits per coordinate.
+ * fp16 arrays are passed as uint16_t bit patterns.  Gradients and `values` must be
+ * 16-byte aligned.  Errors: THC_ERR_CHUNK for a bad C, THC_ERR_SIZE for P >= 2^32,
+ * J == 0 (select) or J > P. */
+
+uint64_t topkc_num_chunks(uint64_t n, uint32_t C);
+
+/*   norms   P fp16 values of ONE worker */
+int topkc_chunk_norms(const void* grad, thc_dtype dt, uint64_t n, uint32_t C, uint16_t* norms, void* stream);
+
+/*   norms_all   W arrays of P fp16 values back to back;   s   P fp16 sums */
+int topkc_sum_norms(const uint16_t* norms_all, uint32_t W, uint64_t P, uint16_t* s, void* stream);
+
+/* Scratch bytes topkc_select needs for P chunks (the call clears what it uses). */
+uint64_t topkc_select_workspace_bytes(uint64_t P);
+
+/*   s   P non-negative fp16 values;   indices   receives J chunk indices, ascending */
+int topkc_select(const uint16_t* s, uint64_t P, uint32_t J, uint32_t* indices, void* workspace,
+                 uint64_t workspace_bytes, void* stream);
+
+/*   grads   HOST array of W (<= 64) device pointers;   values   J * C fp16 values,
+ *   chunk indices[j] at values[j * C .. j * C + C) */
+int topkc_gather_sum(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n, uint32_t C,
+                     const uint32_t* indices, uint32_t J, uint16_t* values, void* stream);
+
+/*   out   n fp32 values, fully written (zeros outside the selected chunks) */
+int topkc_scatter_mean(const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C, uint32_t W,
+                       uint64_t n, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

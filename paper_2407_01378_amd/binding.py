@@ -57,6 +57,19 @@ _SIGNATURES = {
                                             ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]),
+    "topkc_num_chunks": (ctypes.c_uint64, [ctypes.c_uint64, ctypes.c_uint32]),
+    "topkc_chunk_norms": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                         ctypes.c_void_p, ctypes.c_void_p]),
+    "topkc_sum_norms": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p,
+                                       ctypes.c_void_p]),
+    "topkc_select_workspace_bytes": (ctypes.c_uint64, [ctypes.c_uint64]),
+    "topkc_select": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]),
+    "topkc_gather_sum": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                        ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p,
+                                        ctypes.c_void_p]),
+    "topkc_scatter_mean": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
+                                          ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_chunk_minmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_range_reduce": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64,
@@ -409,4 +422,47 @@ def thc_decode_minmax(sums, range_, W, n, chunk_log2, seed, bits, rotate, out, s
     _check(lib().thc_decode_minmax(_ptr(sums), _ptr(range_), W, n, chunk_log2, seed, bits,
                                    int(bool(rotate)), _dtype_code(out), _ptr(out), _stream(stream)),
            "thc_decode_minmax")
+    return out
+
+
+# ---------------------------------------------------------------------------- TopKC
+def topkc_num_chunks(n, C):
+    return lib().topkc_num_chunks(n, C)
+
+
+def topkc_chunk_norms(grad, C, norms, stream=None):
+    _flat(grad), _flat(norms, torch.float16)
+    _check(lib().topkc_chunk_norms(_ptr(grad), _dtype_code(grad), grad.numel(), C, _ptr(norms),
+                                   _stream(stream)), "topkc_chunk_norms")
+    return norms
+
+
+def topkc_sum_norms(norms_all, W, P, s, stream=None):
+    _check(lib().topkc_sum_norms(_ptr(norms_all), W, P, _ptr(s), _stream(stream)), "topkc_sum_norms")
+    return s
+
+
+def topkc_select_workspace_bytes(P):
+    return lib().topkc_select_workspace_bytes(P)
+
+
+def topkc_select(s, J, indices, workspace, stream=None):
+    _flat(s, torch.float16), _flat(indices, torch.int32)
+    _check(lib().topkc_select(_ptr(s), s.numel(), J, _ptr(indices), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), _stream(stream)), "topkc_select")
+    return indices
+
+
+def topkc_gather_sum(grads, C, indices, J, values, stream=None):
+    keep, pg = _ptr_array(grads)
+    _flat(values, torch.float16)
+    _check(lib().topkc_gather_sum(pg, _dtype_code(grads[0]), len(grads), grads[0].numel(), C, _ptr(indices), J,
+                                  _ptr(values), _stream(stream)), "topkc_gather_sum")
+    return values
+
+
+def topkc_scatter_mean(values, indices, J, C, W, out, stream=None):
+    _flat(out, torch.float32)
+    _check(lib().topkc_scatter_mean(_ptr(values), _ptr(indices), J, C, W, out.numel(), _ptr(out),
+                                    _stream(stream)), "topkc_scatter_mean")
     return out

@@ -610,4 +610,80 @@ int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t l
                                           yhat, static_cast<hipStream_t>(stream)));
 }
 
+// ----------------------------------------------------------------------------- TopKC
+static int check_topkc(uint64_t n, uint32_t C) {
+    if (C < 8 || C > 512 || (C & (C - 1)) != 0) return THC_ERR_CHUNK;
+    if (n > kMaxCoords || (n + C - 1) / C > 0xFFFFFFFFull) return THC_ERR_SIZE;
+    return THC_OK;
+}
+
+uint64_t topkc_num_chunks(uint64_t n, uint32_t C) {
+    return check_topkc(n, C) == THC_OK ? (n + C - 1) / C : 0;
+}
+
+int topkc_chunk_norms(const void* grad, thc_dtype dt, uint64_t n, uint32_t C, uint16_t* norms, void* stream) {
+    int rc = check_topkc(n, C);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (n == 0) return THC_OK;
+    if (!grad || !norms) return THC_ERR_NULL;
+    if (!aligned(grad, 16) || !aligned(norms, 2)) return THC_ERR_ALIGN;
+    return finish(thc::launch_topkc_norms(grad, dt == THC_BF16, n, C, norms, static_cast<hipStream_t>(stream)));
+}
+
+int topkc_sum_norms(const uint16_t* norms_all, uint32_t W, uint64_t P, uint16_t* s, void* stream) {
+    if (W == 0) return THC_ERR_WORKERS;
+    if (P > 0xFFFFFFFFull) return THC_ERR_SIZE;
+    if (P == 0) return THC_OK;
+    if (!norms_all || !s) return THC_ERR_NULL;
+    if (!aligned(norms_all, 2) || !aligned(s, 2)) return THC_ERR_ALIGN;
+    return finish(thc::launch_topkc_sum_norms(norms_all, W, P, s, static_cast<hipStream_t>(stream)));
+}
+
+uint64_t topkc_select_workspace_bytes(uint64_t P) {
+    return P > 0xFFFFFFFFull ? 0 : 4 * thc::topkc_select_workspace_words(P);
+}
+
+int topkc_select(const uint16_t* s, uint64_t P, uint32_t J, uint32_t* indices, void* workspace,
+                 uint64_t workspace_bytes, void* stream) {
+    if (P > 0xFFFFFFFFull || J == 0 || (uint64_t)J > P) return THC_ERR_SIZE;
+    if (!s || !indices || !workspace) return THC_ERR_NULL;
+    if (!aligned(s, 2) || !aligned(indices, 4) || !aligned(workspace, 4)) return THC_ERR_ALIGN;
+    if (workspace_bytes < topkc_select_workspace_bytes(P)) return THC_ERR_SIZE;
+    return finish(thc::launch_topkc_select(s, P, J, indices, static_cast<uint32_t*>(workspace),
+                                           static_cast<hipStream_t>(stream)));
+}
+
+int topkc_gather_sum(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n, uint32_t C,
+                     const uint32_t* indices, uint32_t J, uint16_t* values, void* stream) {
+    int rc = check_topkc(n, C);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc != THC_OK) return rc;
+    if (W == 0 || W > (uint32_t)thc::kMaxFusedWorkers) return THC_ERR_WORKERS;
+    if ((uint64_t)J > (n + C - 1) / C) return THC_ERR_SIZE;
+    if (J == 0) return THC_OK;
+    if (!grads || !indices || !values) return THC_ERR_NULL;
+    thc::FusedWorkerPtrs ptrs{};
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!grads[w]) return THC_ERR_NULL;
+        if (!aligned(grads[w], 16)) return THC_ERR_ALIGN;
+        ptrs.grad[w] = grads[w];
+    }
+    if (!aligned(indices, 4) || !aligned(values, 16)) return THC_ERR_ALIGN;
+    return finish(thc::launch_topkc_gather_sum(ptrs, dt == THC_BF16, W, n, C, indices, J, values,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int topkc_scatter_mean(const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C, uint32_t W,
+                       uint64_t n, float* out, void* stream) {
+    int rc = check_topkc(n, C);
+    if (rc != THC_OK) return rc;
+    if (W == 0) return THC_ERR_WORKERS;
+    if ((uint64_t)J > (n + C - 1) / C || n > 0x7FFFFFFFFFull) return THC_ERR_SIZE;
+    if (n == 0) return THC_OK;
+    if (!out || (J != 0 && (!values || !indices))) return THC_ERR_NULL;
+    if (!aligned(values, 16) || !aligned(indices, 4) || !aligned(out, 4)) return THC_ERR_ALIGN;
+    return finish(thc::launch_topkc_scatter(values, indices, J, C, W, n, out, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -127,6 +127,19 @@ hipError_t launch_full_encode(const float* y, uint32_t log2_size, const float* s
 hipError_t launch_full_decode(const void* sums, uint32_t sum_bytes, uint32_t log2_size, const float* scale,
                               uint32_t levels, uint32_t W, float* yhat, hipStream_t stream);
 
+// ---- TopKC (topkc.hip) ----------------------------------------------------------------
+hipError_t launch_topkc_norms(const void* grad, bool bf16, uint64_t n, uint32_t C, uint16_t* norms,
+                              hipStream_t stream);
+hipError_t launch_topkc_sum_norms(const uint16_t* norms_all, uint32_t W, uint64_t P, uint16_t* s,
+                                  hipStream_t stream);
+uint64_t topkc_select_workspace_words(uint64_t P);
+hipError_t launch_topkc_select(const uint16_t* s, uint64_t P, uint32_t J, uint32_t* indices, uint32_t* ws,
+                               hipStream_t stream);
+hipError_t launch_topkc_gather_sum(const FusedWorkerPtrs& ptrs, bool bf16, uint32_t W, uint64_t n, uint32_t C,
+                                   const uint32_t* indices, uint32_t J, uint16_t* values, hipStream_t stream);
+hipError_t launch_topkc_scatter(const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C,
+                                uint32_t W, uint64_t n, float* out, hipStream_t stream);
+
 constexpr int kMaxAggBatch = 16;
 struct PayloadBatch {
     const uint8_t* p[kMaxAggBatch];

@@ -1,0 +1,366 @@
+// TopK Chunked (TopKC): per-chunk squared norms in half precision, their sum over workers,
+// selection of the J chunks with the largest sums, and the fp16 sum of the selected chunks
+// ("Our proposed improvement: Chunks" of the paper's TopK case study).  Everything here is
+// a streaming scan; the only part that is not elementwise is the selection, a two-pass
+// radix select over the 16-bit keys followed by an ordered compaction.
+#include <hip/hip_fp16.h>
+
+#include "thc_device.h"
+#include "thc_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace thc {
+namespace {
+
+// fp32 -> fp16 bits, round to nearest even (subnormals kept, overflow to inf).
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float x) {
+    return (uint32_t)__half_as_ushort(__float2half_rn(x));
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+    return __half2float(__ushort_as_half((unsigned short)h));
+}
+// fp16 + fp16 -> fp16: the fp32 sum of two fp16 numbers is exact, so one rounding.
+__device__ __forceinline__ uint32_t add_f16_bits(uint32_t a, uint32_t b) {
+    return f32_to_f16_bits(f16_bits_to_f32(a) + f16_bits_to_f32(b));
+}
+
+// 8 consecutive coordinates starting at g (a multiple of 8), widened to fp32; zeros past n.
+template <bool BF16>
+__device__ __forceinline__ void load8(const void* grad, uint64_t g, uint64_t n, float (&x)[8]) {
+    if (g + 8u <= n) {
+        if (BF16) {
+            const uint4 q = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(grad) + g);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                x[2 * d] = __uint_as_float(w[d] << 16);
+                x[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u);
+            }
+        } else {
+            const float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(grad) + g);
+            const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(grad) + g + 4);
+            x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+            x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = 0.0f;
+            if (g + e < n)
+                v = BF16 ? bf16_bits_to_float(static_cast<const uint16_t*>(grad)[g + e])
+                         : static_cast<const float*>(grad)[g + e];
+            x[e] = v;
+        }
+    }
+}
+
+// Squared norm of every chunk of C = 8 * lanes_per_chunk coordinates: squares in fp32,
+// summed as a balanced tree over adjacent pairs (inside the thread, then across lanes
+// 1, 2, 4, ... apart), rounded to fp16.
+template <bool BF16>
+__global__ __launch_bounds__(256) void norms_kernel(const void* grad, uint64_t n, uint32_t lanes_per_chunk,
+                                                    uint64_t threads, uint16_t* norms) {
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float x[8];
+    if (tid < threads) {
+        load8<BF16>(grad, tid * 8u, n, x);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = 0.0f;
+    }
+    float s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = x[e] * x[e];
+    float t = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+    for (uint32_t o = 1; o < lanes_per_chunk; o <<= 1) t = t + __shfl_xor(t, (int)o, 64);
+    if (tid < threads && (tid & (uint64_t)(lanes_per_chunk - 1u)) == 0)
+        norms[tid / lanes_per_chunk] = (uint16_t)f32_to_f16_bits(t);
+}
+
+// s_p = fp16 sum over workers, in worker order, of norms_all[w * P + p].
+__global__ __launch_bounds__(256) void sum_norms_kernel(const uint16_t* norms_all, uint32_t W, uint64_t P,
+                                                        uint16_t* s) {
+    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    uint32_t acc = norms_all[p];
+    for (uint32_t w = 1; w < W; ++w) acc = add_f16_bits(acc, norms_all[(uint64_t)w * P + p]);
+    s[p] = (uint16_t)acc;
+}
+
+// ---- selection -----------------------------------------------------------------------------
+// Workspace words: [0,256) histogram of the keys' high bytes, [256,512) histogram of the
+// low bytes inside the threshold bucket, [512] threshold bucket, [513] still to take
+// inside it, [514] threshold key T, [515] how many keys equal to T are taken, then per
+// segment of kSegment keys the pair (keys above T, keys equal to T), scanned in place.
+constexpr uint32_t kSegment = 2048;
+constexpr uint32_t kHdr = 516;
+
+// PASS 0: histogram of key >> 8.  PASS 1: of key & 255 among keys with key >> 8 == ws[512].
+template <int PASS>
+__global__ __launch_bounds__(256) void hist_kernel(const uint16_t* s, uint64_t P, uint32_t* ws) {
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t bucket = PASS == 1 ? ws[512] : 0u;
+    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < P;
+         p += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t key = s[p];
+        if (PASS == 0) atomicAdd(&h[key >> 8], 1u);
+        else if ((key >> 8) == bucket) atomicAdd(&h[key & 255u], 1u);
+    }
+    __syncthreads();
+    const uint32_t c = h[threadIdx.x];
+    if (c) atomicAdd(&ws[256 * PASS + threadIdx.x], c);
+}
+
+// One thread walks the 256-bin histogram from the top.  PASS 0: finds the bucket in which
+// the J-th largest key lies.  PASS 1: finds the key itself and how many of its equals to take.
+template <int PASS>
+__global__ void find_kernel(uint32_t* ws, uint32_t J) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const uint32_t want = PASS == 0 ? J : ws[513];
+    uint32_t above = 0;
+    int b = 255;
+    for (; b > 0; --b) {
+        const uint32_t c = ws[256 * PASS + b];
+        if (above + c >= want) break;
+        above += c;
+    }
+    if (PASS == 0) {
+        ws[512] = (uint32_t)b;
+        ws[513] = want - above;          // still to take inside bucket b (>= 1)
+    } else {
+        ws[514] = (ws[512] << 8) | (uint32_t)b;
+        ws[515] = want - above;          // keys equal to T that are taken (>= 1)
+    }
+}
+
+__global__ __launch_bounds__(256) void seg_count_kernel(const uint16_t* s, uint64_t P, uint32_t* ws) {
+    __shared__ uint32_t cnt[2];
+    if (threadIdx.x < 2) cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t T = ws[514];
+    const uint64_t base = (uint64_t)blockIdx.x * kSegment;
+    uint32_t above = 0, equal = 0;
+    for (uint32_t i = threadIdx.x; i < kSegment; i += 256u) {
+        const uint64_t p = base + i;
+        if (p < P) {
+            const uint32_t key = s[p];
+            above += key > T;
+            equal += key == T;
+        }
+    }
+    if (above) atomicAdd(&cnt[0], above);
+    if (equal) atomicAdd(&cnt[1], equal);
+    __syncthreads();
+    if (threadIdx.x < 2) ws[kHdr + 2u * blockIdx.x + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// Exclusive scan of the per-segment pairs, one workgroup (segments are few: P / 2048).
+__global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* ws, uint32_t segments) {
+    __shared__ uint32_t tot[2][1024];
+    const uint32_t t = threadIdx.x;
+    const uint32_t per = (segments + 1023u) / 1024u;
+    const uint32_t lo = t * per, hi = min(lo + per, segments);
+    uint32_t a = 0, e = 0;
+    for (uint32_t i = lo; i < hi; ++i) {
+        a += ws[kHdr + 2u * i];
+        e += ws[kHdr + 2u * i + 1u];
+    }
+    tot[0][t] = a;
+    tot[1][t] = e;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t ra = 0, re = 0;
+        for (uint32_t i = 0; i < 1024u; ++i) {
+            const uint32_t xa = tot[0][i], xe = tot[1][i];
+            tot[0][i] = ra;
+            tot[1][i] = re;
+            ra += xa;
+            re += xe;
+        }
+    }
+    __syncthreads();
+    a = tot[0][t];
+    e = tot[1][t];
+    for (uint32_t i = lo; i < hi; ++i) {
+        const uint32_t xa = ws[kHdr + 2u * i], xe = ws[kHdr + 2u * i + 1u];
+        ws[kHdr + 2u * i] = a;
+        ws[kHdr + 2u * i + 1u] = e;
+        a += xa;
+        e += xe;
+    }
+}
+
+// Ordered compaction: chunk p is selected if its key is above T, or equal to T with fewer
+// than `need` equal keys before it; its place is (#above before) + min(#equal before, need).
+__global__ __launch_bounds__(256) void write_indices_kernel(const uint16_t* s, uint64_t P, const uint32_t* ws,
+                                                            uint32_t* indices) {
+    __shared__ uint32_t wave_tot[2][4];
+    const uint32_t T = ws[514], need = ws[515];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t base = (uint64_t)blockIdx.x * kSegment;
+    uint32_t above_before = ws[kHdr + 2u * blockIdx.x], equal_before = ws[kHdr + 2u * blockIdx.x + 1u];
+    // a thread owns 8 consecutive keys, so index order = (thread, k) order
+    uint32_t key[8];
+    uint32_t a = 0, e = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint64_t p = base + 8u * threadIdx.x + k;
+        key[k] = p < P ? (uint32_t)s[p] : 0xFFFFFFFFu;   // sentinel: neither above (masked) nor equal
+        if (p < P) {
+            a += key[k] > T;
+            e += key[k] == T;
+        }
+    }
+    // exclusive scan of (a, e) over the 256 threads
+    uint32_t ia = a, ie = e;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t ua = __shfl_up(ia, o, 64), ue = __shfl_up(ie, o, 64);
+        if (lane >= (uint32_t)o) {
+            ia += ua;
+            ie += ue;
+        }
+    }
+    if (lane == 63) {
+        wave_tot[0][wave] = ia;
+        wave_tot[1][wave] = ie;
+    }
+    __syncthreads();
+    for (uint32_t w = 0; w < wave; ++w) {
+        above_before += wave_tot[0][w];
+        equal_before += wave_tot[1][w];
+    }
+    above_before += ia - a;
+    equal_before += ie - e;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint64_t p = base + 8u * threadIdx.x + k;
+        if (p < P) {
+            const bool is_above = key[k] > T, is_equal = key[k] == T;
+            if (is_above || (is_equal && equal_before < need))
+                indices[above_before + min(equal_before, need)] = (uint32_t)p;
+            above_before += is_above;
+            equal_before += is_equal;
+        }
+    }
+}
+
+// ---- selected chunks --------------------------------------------------------------------------
+// values[j * C + e] = fp16 sum over workers, in worker order, of fp16(x_w[indices[j] * C + e]).
+template <bool BF16>
+__global__ __launch_bounds__(256) void gather_sum_kernel(const FusedWorkerPtrs ptrs, uint32_t W, uint64_t n,
+                                                         uint32_t C, const uint32_t* indices, uint64_t threads,
+                                                         uint16_t* values) {
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= threads) return;
+    const uint64_t flat = tid * 8u;                 // position in the J x C value array
+    const uint64_t j = flat / C;
+    const uint32_t e0 = (uint32_t)(flat - j * C);
+    const uint64_t g = (uint64_t)indices[j] * C + e0;
+    uint32_t acc[8];
+    for (uint32_t w = 0; w < W; ++w) {
+        float x[8];
+        load8<BF16>(ptrs.grad[w], g, n, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t h = f32_to_f16_bits(x[e]);
+            acc[e] = w == 0 ? h : add_f16_bits(acc[e], h);
+        }
+    }
+    *reinterpret_cast<uint4*>(values + flat) =
+        make_uint4(acc[0] | (acc[1] << 16), acc[2] | (acc[3] << 16), acc[4] | (acc[5] << 16), acc[6] | (acc[7] << 16));
+}
+
+// out[indices[j] * C + e] = float(values[j * C + e]) / W  (out zeroed beforehand).
+__global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* values, const uint32_t* indices, uint32_t C,
+                                                      uint32_t W, uint64_t n, uint64_t threads, float* out) {
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= threads) return;
+    const uint64_t flat = tid * 8u;
+    const uint64_t j = flat / C;
+    const uint32_t e0 = (uint32_t)(flat - j * C);
+    const uint64_t g = (uint64_t)indices[j] * C + e0;
+    const uint4 q = *reinterpret_cast<const uint4*>(values + flat);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    const float Wf = (float)W;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = f16_bits_to_f32((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu) / Wf;
+        if (g + e < n) out[g + e] = v;
+    }
+}
+
+uint32_t blocks_for(uint64_t threads, uint32_t per_block) {
+    return (uint32_t)((threads + per_block - 1) / per_block);
+}
+
+}  // namespace
+
+hipError_t launch_topkc_norms(const void* grad, bool bf16, uint64_t n, uint32_t C, uint16_t* norms,
+                              hipStream_t stream) {
+    const uint64_t P = (n + C - 1) / C;
+    const uint64_t threads = P * (C / 8u);
+    if (threads == 0) return hipSuccess;
+    const dim3 grid(blocks_for(threads, 256)), block(256);
+    if (bf16)
+        hipLaunchKernelGGL(norms_kernel<true>, grid, block, 0, stream, grad, n, C / 8u, threads, norms);
+    else
+        hipLaunchKernelGGL(norms_kernel<false>, grid, block, 0, stream, grad, n, C / 8u, threads, norms);
+    return hipGetLastError();
+}
+
+hipError_t launch_topkc_sum_norms(const uint16_t* norms_all, uint32_t W, uint64_t P, uint16_t* s,
+                                  hipStream_t stream) {
+    if (P == 0) return hipSuccess;
+    hipLaunchKernelGGL(sum_norms_kernel, dim3(blocks_for(P, 256)), dim3(256), 0, stream, norms_all, W, P, s);
+    return hipGetLastError();
+}
+
+uint64_t topkc_select_workspace_words(uint64_t P) {
+    return kHdr + 2u * ((P + kSegment - 1) / kSegment);
+}
+
+hipError_t launch_topkc_select(const uint16_t* s, uint64_t P, uint32_t J, uint32_t* indices, uint32_t* ws,
+                               hipStream_t stream) {
+    const uint32_t segments = (uint32_t)((P + kSegment - 1) / kSegment);
+    hipError_t e = launch_zero_words(ws, kHdr, stream);
+    if (e != hipSuccess) return e;
+    uint32_t hb = blocks_for(P, 256 * 16);
+    if (hb > 2048) hb = 2048;
+    hipLaunchKernelGGL(hist_kernel<0>, dim3(hb), dim3(256), 0, stream, s, P, ws);
+    hipLaunchKernelGGL(find_kernel<0>, dim3(1), dim3(64), 0, stream, ws, J);
+    hipLaunchKernelGGL(hist_kernel<1>, dim3(hb), dim3(256), 0, stream, s, P, ws);
+    hipLaunchKernelGGL(find_kernel<1>, dim3(1), dim3(64), 0, stream, ws, J);
+    hipLaunchKernelGGL(seg_count_kernel, dim3(segments), dim3(256), 0, stream, s, P, ws);
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, ws, segments);
+    hipLaunchKernelGGL(write_indices_kernel, dim3(segments), dim3(256), 0, stream, s, P, ws, indices);
+    return hipGetLastError();
+}
+
+hipError_t launch_topkc_gather_sum(const FusedWorkerPtrs& ptrs, bool bf16, uint32_t W, uint64_t n, uint32_t C,
+                                   const uint32_t* indices, uint32_t J, uint16_t* values, hipStream_t stream) {
+    const uint64_t threads = (uint64_t)J * (C / 8u);
+    if (threads == 0) return hipSuccess;
+    const dim3 grid(blocks_for(threads, 256)), block(256);
+    if (bf16)
+        hipLaunchKernelGGL(gather_sum_kernel<true>, grid, block, 0, stream, ptrs, W, n, C, indices, threads, values);
+    else
+        hipLaunchKernelGGL(gather_sum_kernel<false>, grid, block, 0, stream, ptrs, W, n, C, indices, threads, values);
+    return hipGetLastError();
+}
+
+hipError_t launch_topkc_scatter(const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C,
+                                uint32_t W, uint64_t n, float* out, hipStream_t stream) {
+    hipError_t e = launch_zero_words(reinterpret_cast<uint32_t*>(out), n, stream);
+    if (e != hipSuccess) return e;
+    const uint64_t threads = (uint64_t)J * (C / 8u);
+    if (threads == 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_kernel, dim3(blocks_for(threads, 256)), dim3(256), 0, stream, values, indices, C,
+                       W, n, threads, out);
+    return hipGetLastError();
+}
+
+}  // namespace thc

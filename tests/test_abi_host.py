@@ -25,7 +25,7 @@ def _declared():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", src)
-    return sorted({n for n in names if n.startswith(("thc_", "rht_"))})
+    return sorted({n for n in names if n.startswith(("thc_", "rht_", "topkc_"))})
 
 
 def test_every_declared_function_is_exported_and_bound(L):

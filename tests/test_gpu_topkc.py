@@ -1,0 +1,130 @@
+"""TopKC on the GPU against its oracle: per-worker norms, summed norms, selected indices,
+fp16 chunk sums and the dense estimate, all bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import topkc as K
+from synth import generate, to_numpy_bits, workload
+
+from gpu_util import DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def _data(n, dtype, W, seed, clustered=True):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    xs = []
+    seg = 1000
+    scale = 10.0 ** (torch.rand((n + seg - 1) // seg, generator=g, device=DEV) * 3 - 4)
+    scale = scale.repeat_interleave(seg)[:n] if clustered else torch.full((n,), 1e-2, device=DEV)
+    for w in range(W):
+        xs.append((torch.randn(n, generator=g, device=DEV) * scale).to(dtype))
+    return xs
+
+
+def run_topkc(xs, C, J):
+    W, n = len(xs), xs[0].numel()
+    P = thc.topkc_num_chunks(n, C)
+    norms_all = torch.full((W * P,), float("nan"), dtype=torch.float16, device=DEV)
+    s = torch.full((P,), float("nan"), dtype=torch.float16, device=DEV)
+    idx = torch.full((J,), -1, dtype=torch.int32, device=DEV)
+    ws = torch.full((thc.topkc_select_workspace_bytes(P),), 0xFF, dtype=torch.uint8, device=DEV)
+    vals = torch.full((J * C,), float("nan"), dtype=torch.float16, device=DEV)
+    out = torch.full((n,), float("nan"), device=DEV)
+    for w in range(W):
+        thc.topkc_chunk_norms(xs[w], C, norms_all[w * P:(w + 1) * P])
+    thc.topkc_sum_norms(norms_all, W, P, s)
+    thc.topkc_select(s, J, idx, ws)
+    thc.topkc_gather_sum(xs, C, idx, J, vals)
+    thc.topkc_scatter_mean(vals, idx, J, C, W, out)
+    torch.cuda.synchronize()
+    return dict(norms=norms_all.view(W, P), s=s, indices=idx, values=vals.view(J, C), out=out)
+
+
+def _bits16(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def check(xs, got, C, J):
+    bf16 = xs[0].dtype == torch.bfloat16
+    ref = K.pipeline([to_numpy_bits(x) for x in xs], C, J, bf16=bf16)
+    for w in range(len(xs)):
+        assert (_bits16(got["norms"][w]) == ref["norms"][w].view(np.uint16)).all(), f"norms of worker {w}"
+    assert (_bits16(got["s"]) == ref["s"].view(np.uint16)).all(), "summed norms"
+    assert (got["indices"].cpu().numpy().view(np.uint32) == ref["indices"]).all(), "selected indices"
+    assert (_bits16(got["values"]) == ref["values"].view(np.uint16)).all(), "chunk sums"
+    assert (got["out"].cpu().numpy() == ref["out"]).all(), "dense estimate"
+    return ref
+
+
+@pytest.mark.parametrize("n,C,J,W,dtype", [
+    (100_000, 64, 100, 4, torch.float32), (100_003, 128, 37, 8, torch.bfloat16),
+    (1 << 20, 64, 1, 3, torch.bfloat16), (1 << 20, 64, 16384, 3, torch.float32),     # J = 1 and J = P
+    (999_999, 8, 5000, 2, torch.float32), (300_000, 512, 100, 5, torch.bfloat16),
+    (70, 64, 2, 2, torch.float32), (5_000_000, 128, 3000, 8, torch.bfloat16),
+])
+def test_topkc_matches_oracle(n, C, J, W, dtype):
+    print(f"topkc n={n} C={C} J={J} W={W} dtype={dtype}", flush=True)
+    xs = _data(n, dtype, W, seed=n % 1000 + C)
+    check(xs, run_topkc(xs, C, J), C, J)
+
+
+def test_topkc_many_ties_and_zero_chunks():
+    """Most chunks are exactly zero (their fp16 norms tie at 0) and many non-zero chunks tie
+    too: the J-th place falls among equal keys and must go to the lowest indices."""
+    n, C, W = 1 << 18, 64, 3
+    P = n // C
+    xs = [torch.zeros(n, device=DEV) for _ in range(W)]
+    for w in range(W):
+        for p in range(0, P, 5):
+            xs[w][p * C] = 1.0 + (p % 3)          # three distinct non-zero norm values, repeated
+    for J in (1, 7, P // 5, P // 5 + 10, P):
+        got = run_topkc(xs, C, J)
+        ref = check(xs, got, C, J)
+        assert len(set(ref["indices"].tolist())) == J
+
+
+def test_topkc_underflowing_norms_are_kept_as_fp16_gives_them():
+    """Gradients of size 1e-5: squared chunk norms around 6e-9 are below fp16's smallest
+    subnormal and round to zero, as the paper's half-precision norms do."""
+    n, C, W, J = 1 << 16, 64, 2, 10
+    xs = [torch.full((n,), 1e-5, device=DEV) for _ in range(W)]
+    xs[0][4096:4096 + 64] = 0.5
+    got = run_topkc(xs, C, J)
+    ref = check(xs, got, C, J)
+    assert ref["indices"][0] == 0 or 64 in ref["indices"]      # the one large chunk is chunk 64
+    assert 64 in ref["indices"].tolist()
+    assert (ref["s"].astype(np.float32) == 0).sum() == n // C - 1
+
+
+def test_topkc_argument_checks():
+    x = torch.zeros(1000, device=DEV)
+    norms = torch.zeros(100, dtype=torch.float16, device=DEV)
+    with pytest.raises(thc.ThcError):
+        thc.topkc_chunk_norms(x, 48, norms)        # C not a power of two
+    with pytest.raises(thc.ThcError):
+        thc.topkc_chunk_norms(x, 1024, norms)      # C too large
+    s = torch.zeros(16, dtype=torch.float16, device=DEV)
+    idx = torch.zeros(32, dtype=torch.int32, device=DEV)
+    ws = torch.zeros(thc.topkc_select_workspace_bytes(16), dtype=torch.uint8, device=DEV)
+    with pytest.raises(thc.ThcError):
+        thc.topkc_select(s, 17, idx, ws)           # J > P
+    with pytest.raises(thc.ThcError):
+        thc.topkc_select(s, 0, idx, ws)
+    with pytest.raises(thc.ThcError):
+        thc.topkc_select(s, 4, idx, ws[:8])        # workspace too small
+
+
+def test_topkc_on_headline_workload_slice():
+    """50 M coordinates of the 1.3B workload's gradients (bf16, W = 8), C = 64, J chosen for
+    about 2 bits per coordinate: every stage compared with the oracle."""
+    wl = workload("gpt_1p3b")
+    n, C = 50_000_000, 64
+    J = int(0.11 * n / C)
+    xs = [generate(wl, w, torch.device(DEV), max_elems=n) for w in range(wl.W)]
+    got = run_topkc(xs, C, J)
+    check(xs, got, C, J)
+    print(f"bits per coordinate: {K.bits_per_coordinate(J, C, n):.3f}", flush=True)
