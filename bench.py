@@ -25,6 +25,9 @@ of the same inputs.
     python bench.py --quality    vNMSE and time of one bucket for the grid / rotation variants:
                                  symmetric range + partial rotation (the timed path), min/max
                                  range + partial rotation, min/max range without rotation
+    python bench.py --topkc      the paper's TopK Chunked sparsifier on the same gradients
+                                 (C = 64, J for about 2 bits per coordinate): time per step,
+                                 norm-kernel roofline, vNMSE
     python bench.py --probe      a few launches of each kernel of the first bucket plus a
                                  device-to-device copy of known size; meant to run under
                                  rocprofv3 --pmc so that counter readings of the kernels
@@ -67,6 +70,9 @@ def parse():
                     help="full rotation baseline (l' = l) instead of the chunked path")
     ap.add_argument("--quality", action="store_true",
                     help="vNMSE / time comparison of the range and rotation variants on one bucket")
+    ap.add_argument("--topkc", action="store_true", help="TopK Chunked sparsifier instead of THC")
+    ap.add_argument("--topkc-chunk", type=int, default=64)
+    ap.add_argument("--topkc-bits", type=float, default=2.0, help="target bits per coordinate")
     ap.add_argument("--workers", type=int, default=None,
                     help="simulate this many workers instead of the workload's own W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -324,6 +330,79 @@ def quality(thc, torch, wl, bits, xs, dev):
     return {"workload": wl.name, "bucket_elems": ln, "W": W, "bits": bits, "variants": res}
 
 
+def topkc_bench(thc, torch, wl, xs, dev, a):
+    """Whole TopKC round on the full gradient of every worker (no buckets: the selection is
+    global): norms x W, fp16 sum, selection, fp16 chunk sums, dense estimate."""
+    W, n, C = wl.W, wl.n, a.topkc_chunk
+    s_in = 2 if wl.dtype == "bf16" else 4
+    P = thc.topkc_num_chunks(n, C)
+    J = max(1, int((a.topkc_bits / 16.0 - 1.0 / C) * n / C))
+    norms_all = torch.empty(W * P, dtype=torch.float16, device=dev)
+    s = torch.empty(P, dtype=torch.float16, device=dev)
+    idx = torch.empty(J, dtype=torch.int32, device=dev)
+    ws = torch.empty(thc.topkc_select_workspace_bytes(P), dtype=torch.uint8, device=dev)
+    vals = torch.empty(J * C, dtype=torch.float16, device=dev)
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+
+    def norms():
+        for w in range(W):
+            thc.topkc_chunk_norms(xs[w], C, norms_all[w * P:(w + 1) * P])
+
+    phases = {"chunk_norms": (norms, W),
+              "sum_norms": (lambda: thc.topkc_sum_norms(norms_all, W, P, s), 1),
+              "select": (lambda: thc.topkc_select(s, J, idx, ws), 1),
+              "gather_sum": (lambda: thc.topkc_gather_sum(xs, C, idx, J, vals), 1),
+              "scatter_mean": (lambda: thc.topkc_scatter_mean(vals, idx, J, C, W, out), 1)}
+
+    def step():
+        for fn, _ in phases.values():
+            fn()
+
+    step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter() + 0.5
+    while time.perf_counter() < t_end:
+        step()
+        torch.cuda.synchronize()
+    for _ in range(a.warmup):
+        step()
+    ms = time_region(torch, step, a.steps)
+    kernels = {}
+    for name, (fn, calls) in phases.items():
+        t = time_region(torch, fn, max(2, a.steps // 2))
+        kernels[name] = dict(ms_per_step=round(t, 4), launches_per_step=calls,
+                             us_per_launch=round(1e3 * t / calls, 3))
+    step()
+    torch.cuda.synchronize()
+    mean = torch.zeros(n, dtype=torch.float32, device=dev)
+    for x in xs:
+        mean += x.float()
+    mean /= W
+    err = float(((out - mean) ** 2).sum() / (mean ** 2).sum())
+    dom_bytes = n * s_in + P * 2                      # one norms launch: gradient in, fp16 norms out
+    dom_s = kernels["chunk_norms"]["us_per_launch"] * 1e-6
+    achieved = dom_bytes / dom_s / 1e9
+    # what the method must move per coordinate: every gradient read for the norms, the
+    # selected chunks read again and their fp16 sum written, the dense estimate written
+    frac = J * C / n
+    alg = W * s_in + W * s_in * frac + 2 * frac + 4 + (W + 2) * 2.0 / C
+    return {
+        "metric": "gradient GB/s for TopKC (norms + select + chunk sums + estimate, W workers), 1 GPU",
+        "value": round(W * n * s_in / (ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "W": W, "n": n, "input": wl.dtype, "method": "topkc", "C": C, "J": J,
+                   "bits_per_coordinate": round(16.0 * (J * C / n + 1.0 / C), 4)},
+        "roofline": {"bound": "hbm", "kernel": "topkc_chunk_norms", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None},
+        "pipeline_hbm": {"algorithmic_bytes_per_coord": round(alg, 3),
+                         "achieved_GBps": round(n * alg / (ms * 1e-3) / 1e9, 1),
+                         "frac_of_peak": round(n * alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "vnmse": err, "kernels": kernels,
+    }
+
+
 def read_traffic(workload_name, bits, kernel):
     """HBM bytes per launch of a kernel, measured offline with rocprofv3 --pmc
     (FETCH_SIZE, WRITE_SIZE) and kept in profiles/hbm_traffic.txt as lines
@@ -364,6 +443,9 @@ def main():
     xs = [generate(wl, w, dev) for w in range(W)]
     if a.quality:
         print(json.dumps(quality(thc, torch, wl, bits, xs, dev)))
+        return 0
+    if a.topkc:
+        print(json.dumps(topkc_bench(thc, torch, wl, xs, dev, a)))
         return 0
     if a.full_rotation:
         path = FullPath(thc, torch, wl, bits, xs)
