@@ -156,7 +156,12 @@ uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_l
  *              aligned.  Its first 32-bit word is 0 after a good run and 1 if a bounded
  *              wait between workgroups expired (the payloads are then invalid); check it
  *              after synchronising the stream.
- * Calls that share a workspace must not overlap in time. */
+ * Calls that share a workspace must not overlap in time.  The workgroups of a chunk wait
+ * for one another, so the launch is sized to be resident on the device all at once; other
+ * kernels running at the same time only delay it (their workgroups finish and free their
+ * place), but two thc_encode_all / thc_sat_encode_all calls must not run concurrently on
+ * one device (issue them on one stream), and a device kept busy by other work for longer
+ * than the spin limit makes the call report a time-out. */
 int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
                    uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                    float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
