@@ -60,7 +60,7 @@ const char* thc_status_string(int status) {
     }
 }
 
-int thc_version(void) { return 100; }
+int thc_version(void) { return 200; }
 
 uint32_t thc_rounding_bits(void) { return 8; }
 
