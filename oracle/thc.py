@@ -29,8 +29,11 @@ implemented, independently, by the GPU library):
       |rotated value| of chunk p over ALL workers (integer sums are only
       decodable when every worker used the same grid).
   R4  Levels: L + 1 = 2^b grid points, index 0 at -s_p and index L at +s_p.
-  R5  Rounding: idx = floor(v + u), v the position in grid units, u uniform in
-      (0,1) built from RBITS random bits, centred: u = (r + 0.5) / 2^RBITS.
+  R5  Rounding: idx = floor(v + u), v = y * inv + L/2 the position in grid units
+      (inv = L / (2 s_p)), u uniform in (0,1) built from RBITS random bits, centred:
+      u = (r + 0.5) / 2^RBITS.  In the fp32 mode v + u is ONE fused operation
+      fma(y, inv, L/2 + u) (L/2 + u is exact), the form a GPU evaluates in one
+      instruction; an all-zero chunk has index 0 everywhere.
   R6  Decode returns the estimate of the workers' MEAN gradient.
   R7  All-zero chunk (s_p = 0): every index is 0 and it decodes to exactly 0.
   R8  Padding: zeros up to a multiple of the chunk only.
@@ -200,16 +203,52 @@ def scale_reduce(absmax_all):
 
 
 # ------------------------------------------------------------------------ quantizer
+def fma32(a, b, c):
+    """Correctly rounded float32 fused multiply-add a * b + c of float32 arrays, built from
+    float64 operations.  The product of two float32 numbers is exact in float64; the sum
+    p + c is computed with its exact rounding error e (TwoSum), and rounding s = fl64(p + c)
+    to float32 gives the right answer unless s sits exactly halfway between two float32
+    numbers while e != 0, in which case e decides the direction."""
+    a = np.asarray(a, dtype=np.float32).astype(np.float64)
+    b = np.asarray(b, dtype=np.float32).astype(np.float64)
+    c = np.asarray(c, dtype=np.float32).astype(np.float64)
+    a, b, c = np.broadcast_arrays(a, b, c)
+    p = a * b
+    s = p + c
+    bb = s - p                                   # TwoSum (Knuth): e = exact (p + c) - s
+    e = (p - (s - bb)) + (c - bb)
+    r = s.astype(np.float32)
+    r64 = r.astype(np.float64)
+    inexact = r64 != s
+    if inexact.any():
+        toward = np.where(s > r64, np.float32(np.inf), np.float32(-np.inf))
+        other = np.nextafter(r, toward)          # the float32 neighbour on the far side of s
+        tie = inexact & (np.abs(s - r64) == np.abs(other.astype(np.float64) - s))
+        fix = tie & (e != 0)
+        if fix.any():
+            up = np.maximum(r, other)
+            dn = np.minimum(r, other)
+            r = np.where(fix, np.where(e > 0, up, dn), r).astype(np.float32)
+    return r
+
+
+def grid_position_plus_noise(y, inv, half_plus_u, dtype):
+    """t = y * inv + (L/2 + u): one fused operation in the fp32 mode, plain arithmetic in
+    the float64 definition."""
+    if dtype == np.float32:
+        return fma32(y, inv, half_plus_u)
+    return y * inv + half_plus_u
+
+
 def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
              rbits=RBITS, return_t=False, r=None):
     """Stochastic rounding onto the 2^bits-point grid of [-s_p, s_p] (THC
     background paragraph: evenly split range, grid points at the boundaries,
     each coordinate rounded to one of its two neighbours; readings R4, R5, R7).
 
-        inv = L / (s_p + s_p)            (0 when s_p = 0)
-        v   = (y + s_p) * inv            position in grid units, 0 <= v <= L
-        t   = v + u,  u = (r + 0.5) / 2^RBITS
-        idx = min(floor(t), L)
+        inv = L / (s_p + s_p)
+        t   = y * inv + (L/2 + u),  u = (r + 0.5) / 2^RBITS     (position in grid units + noise)
+        idx = min(floor(t), L);     s_p = 0 -> idx = 0
 
     `r` (tests only) replaces the generator's RBITS-bit integers, so that every
     value of r can be enumerated by brute force.
@@ -222,15 +261,17 @@ def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
     inv = np.zeros_like(two_s)
     nz = two_s != 0
     inv[nz] = dtype(L) / two_s[nz]
-    v = (y + s) * inv
     if r is None:
         r = rounding_fields(g0, y.size, worker, seed, rbits)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -rbits)
-    t = v + u
-    idx = np.minimum(np.floor(t), dtype(L)).astype(np.uint16).reshape(-1)
+    half_plus_u = dtype(L / 2.0) + u                      # exact: L/2 and u are short binary fractions
+    t = grid_position_plus_noise(y, inv, half_plus_u, dtype)
+    idx = np.minimum(np.floor(t), dtype(L)).astype(np.uint16)
+    idx[np.broadcast_to(~nz, idx.shape)] = 0
+    idx = idx.reshape(-1)
     if return_t:
-        return idx, t.reshape(-1)
+        return idx, np.asarray(t, dtype=dtype).reshape(-1)
     return idx
 
 

@@ -12,8 +12,9 @@ Readings (the paper fixes only the idea of a min-max range):
       workers of its largest.  The header is the pair (lo_p, hi_p).
   M2  Grid: 2^b points, index 0 at lo_p, index L at hi_p; hi_p == lo_p gives inv = 0,
       all indices 0, and decodes to exactly lo_p.
-          inv = L / (hi - lo);  v = (y - lo) * inv;  t = v + u;  idx = min(floor(t), L)
-      (u as in the symmetric path, same random stream).
+          inv = L / (hi - lo);  t = (y - lo) * inv + u;  idx = min(floor(t), L)
+      (u as in the symmetric path, same random stream; in the fp32 mode the subtraction
+      is one operation and the multiply-add one fused operation).
   M3  Decode: step = (hi - lo) / L;  yhat = S * (step / W) + lo;  then the inverse
       rotation (or nothing when the rotation is off).
   M4  Without rotation the "rotated values" are the (zero-padded) gradient itself: no
@@ -61,12 +62,11 @@ def quantize_minmax(y, rng, chunk_log2, worker, seed, bits, dtype=np.float64, g0
     inv = np.zeros_like(width)
     nz = width != 0
     inv[nz] = dtype(L) / width[nz]
-    v = (y - lo) * inv
     if r is None:
         r = T.rounding_fields(g0, y.size, worker, seed)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -T.RBITS)
-    t = v + u
+    t = T.grid_position_plus_noise(y - lo, inv, u, dtype)
     return np.minimum(np.floor(t), dtype(L)).astype(np.uint16).reshape(-1)
 
 

@@ -15,7 +15,8 @@ by the GPU library):
   S1  Grid.  Sat's range is the signed symmetric set {-M, ..., M},
       M = 2^(b-1) - 1, i.e. 2^b - 1 levels.  A worker's coordinate is rounded
       onto 2M + 1 evenly spaced points of [-s_p, +s_p]: idx in [0, 2M] with the
-      same stochastic rounding rule as the exact-sum path (L replaced by 2M),
+      same stochastic rounding rule as the exact-sum path (L replaced by 2M; an all-zero
+      chunk lands on the centre index M by the rule itself),
       and z = idx - M is the signed value.  y = 0 sits exactly on a grid point.
   S2  Payload.  idx is stored in b bits (offset binary), packed as in the
       exact-sum path; the all-ones code 2^b - 1 never occurs.
@@ -48,10 +49,10 @@ def sat(x, y, bits):
 def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0, r=None):
     """Reading S1: stochastic rounding onto the 2M+1-point grid of [-s_p, s_p].
 
-        inv = 2M / (s_p + s_p)           (0 when s_p = 0)
-        v   = (y + s_p) * inv            0 <= v <= 2M
-        t   = v + u,  u = (r + 0.5) / 2^RBITS   (same random stream as the exact-sum path)
-        idx = min(floor(t), 2M)
+        inv = 2M / (s_p + s_p)
+        t   = y * inv + (M + u),  u = (r + 0.5) / 2^RBITS   (one fused operation in fp32,
+                                                             same random stream as the exact-sum path)
+        idx = min(floor(t), 2M);  s_p = 0 -> idx = M  (the grid's centre: z = 0)
     """
     c = 1 << chunk_log2
     L = 2 * sat_max(bits)
@@ -61,12 +62,11 @@ def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=
     inv = np.zeros_like(two_s)
     nz = two_s != 0
     inv[nz] = dtype(L) / two_s[nz]
-    v = (y + s) * inv
     if r is None:
         r = T.rounding_fields(g0, y.size, worker, seed)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -T.RBITS)
-    t = v + u
+    t = T.grid_position_plus_noise(y, inv, dtype(L / 2.0) + u, dtype)
     return np.minimum(np.floor(t), dtype(L)).astype(np.uint16).reshape(-1)
 
 

@@ -366,22 +366,25 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 }
 
 // --------------------------------------------------------------------- quantizer
-// Stochastic rounding of the L4e-resident chunk onto the 2^BITS-point grid of [-s, s],
-// packed and stored.  v holds the UNNORMALISED rotation; y = v * 2^-7.
-//   L        largest grid index (2^BITS - 1, or 2^BITS - 2 for the signed grid)
-//   g0       global index of the chunk's first coordinate
-//   payload  start of this worker's payload
-//   CLAMP    false only when s is the largest |y| of the chunk: then floor(t) <= L holds
-//            for every coordinate (t <= fl(L (1 + 2^-24)) + 255.5 / 256 < L + 1) and the
-//            minimum with L never binds
-//
-// FOLD: y = v * 2^-7 followed by (y + s) * inv equals (v + 2^7 s) * (2^-7 inv) bit for bit
-// as long as the power-of-two factors move no operand into or out of the subnormal or
-// overflow range, which 2^-100 <= s <= 2^100 guarantees; other chunks take the plain form.
-template <int BITS, bool CLAMP, bool FOLD>
-__device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add, float mul, uint32_t L,
-                                              uint64_t g, uint32_t worker, uint32_t key0, uint32_t key1,
-                                              uint32_t (&pk)[BITS]) {
+// Stochastic rounding of the L4e-resident chunk onto a grid of L + 1 points, packed.
+// v holds the UNNORMALISED rotation; y = v * 2^-7.  For one coordinate
+//     c   = fma(float(r), 2^-8, base)          exact; r the coordinate's random byte
+//     t   = fma(y - sub, mul, c)               ONE rounding (y - sub is rounded first when RANGED)
+//     idx = floor(t)   (clamped to L when CLAMP)
+// Symmetric grid on [-s, s]:  sub unused, mul = L / (2 s), base = L/2 + 2^-9, so that
+//     t = y * inv + L/2 + (r + 0.5) / 256.
+// Min/max grid on [lo, hi] (RANGED):  sub = lo, mul = L / (hi - lo), base = 2^-9.
+//   g        global index of the thread's first coordinate
+//   CLAMP    false only for the symmetric grid with s the largest |y| of the chunk: then
+//            0 < t < L + 1 for every coordinate (|y * inv| <= L/2 (1 + 2^-24) and
+//            2^-9 <= c - L/2 <= 255.5 / 256), so the minimum with L never binds
+//   FOLD     y = v * 2^-7 is not formed; mul already carries the factor 2^-7.  Exact as long
+//            as the power of two moves nothing into the subnormal range: the callers fold
+//            only for 2^-100 <= s <= 2^100.
+template <int BITS, bool CLAMP, bool FOLD, bool RANGED>
+__device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float sub, float mul, float base,
+                                              uint32_t L, uint64_t g, uint32_t worker, uint32_t key0,
+                                              uint32_t key1, uint32_t (&pk)[BITS]) {
 #pragma unroll
     for (int i = 0; i < BITS; ++i) pk[i] = 0u;
 #pragma unroll
@@ -390,12 +393,12 @@ __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int r = 16 * half + e;
-            const float y = FOLD ? v[r] : v[r] * kInvSqrtC;
-            const float pos = (y + add) * mul;
+            float y = FOLD ? v[r] : v[r] * kInvSqrtC;
+            if (RANGED) y = y - sub;
             const uint32_t rnd = (rb.w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
-            const float u = __builtin_fmaf((float)rnd, 0x1p-8f, 0x1p-9f);   // (r + 0.5) / 256, exact
-            const float tt = pos + u;
-            uint32_t q = (uint32_t)tt;                                       // tt >= 0: truncation = floor
+            const float c = __builtin_fmaf((float)rnd, 0x1p-8f, base);
+            const float tt = __builtin_fmaf(y, mul, c);
+            uint32_t q = (uint32_t)tt;                    // tt >= 0: truncation = floor
             if (CLAMP) q = q < L ? q : L;
             const int bit = r * BITS;
             pk[bit >> 5] |= q << (bit & 31);
@@ -403,19 +406,8 @@ __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float add
     }
 }
 
-template <int BITS, bool CLAMP>
-__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint32_t L, uint64_t g0,
-                                               uint32_t worker, uint32_t key0, uint32_t key1,
-                                               uint8_t* payload, uint32_t t) {
-    const float two = s + s;
-    const float inv = two != 0.0f ? (float)L / two : 0.0f;
-    const uint64_t g = g0 + (uint64_t)t * 32u;
-    uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
-    if (s >= 0x1p-100f && s <= 0x1p100f)   // the same for every thread of the workgroup
-        quantize_pack<BITS, CLAMP, true>(v, s * 128.0f, inv * kInvSqrtC, L, g, worker, key0, key1, pk);
-    else
-        quantize_pack<BITS, CLAMP, false>(v, s, inv, L, g, worker, key0, key1, pk);
-    uint8_t* dst = payload + (g * BITS) / 8u;
+template <int BITS>
+__device__ __forceinline__ void store_packed(const uint32_t (&pk)[BITS], uint8_t* dst) {
     if constexpr (BITS == 8) {
         reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         reinterpret_cast<uint4*>(dst)[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
@@ -426,7 +418,26 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
     }
 }
 
-// The same on a min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo).
+// Symmetric grid.  An all-zero chunk (s = 0) gets index 0 everywhere on the 2^BITS-point
+// grid (L odd) and the centre index L/2 on the signed grid (L even).
+template <int BITS, bool CLAMP>
+__device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint32_t L, uint64_t g0,
+                                               uint32_t worker, uint32_t key0, uint32_t key1,
+                                               uint8_t* payload, uint32_t t) {
+    const float two = s + s;
+    const float inv = two != 0.0f ? (float)L / two : 0.0f;
+    const float half = (two != 0.0f || (L & 1u) == 0u) ? 0.5f * (float)L : 0.0f;
+    const float base = half + 0x1p-9f;   // exact
+    const uint64_t g = g0 + (uint64_t)t * 32u;
+    uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
+    if (s >= 0x1p-100f && s <= 0x1p100f)   // the same for every thread of the workgroup
+        quantize_pack<BITS, CLAMP, true, false>(v, 0.0f, inv * kInvSqrtC, base, L, g, worker, key0, key1, pk);
+    else
+        quantize_pack<BITS, CLAMP, false, false>(v, 0.0f, inv, base, L, g, worker, key0, key1, pk);
+    store_packed<BITS>(pk, payload + (g * BITS) / 8u);
+}
+
+// Min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo) (0 for a constant chunk).
 template <int BITS>
 __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], float lo, float hi, uint32_t L,
                                                      uint64_t g0, uint32_t worker, uint32_t key0,
@@ -435,16 +446,8 @@ __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], fl
     const float inv = width != 0.0f ? (float)L / width : 0.0f;
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];
-    quantize_pack<BITS, true, false>(v, -lo, inv, L, g, worker, key0, key1, pk);   // y + (-lo) == y - lo
-    uint8_t* dst = payload + (g * BITS) / 8u;
-    if constexpr (BITS == 8) {
-        reinterpret_cast<uint4*>(dst)[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        reinterpret_cast<uint4*>(dst)[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-    } else if constexpr (BITS == 4) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-    } else {
-        *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
-    }
+    quantize_pack<BITS, true, false, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);
+    store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 
 // Output side of the inverse rotation: x = D (v * 2^-7) from layout L4d; the first

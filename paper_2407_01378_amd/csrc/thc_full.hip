@@ -171,6 +171,7 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
     const float two = s + s;
     const float Lf = (float)levels;
     const float inv = two != 0.0f ? Lf / two : 0.0f;
+    const float half = two != 0.0f ? 0.5f * Lf : 0.0f;   // an all-zero vector gets index 0
     const u32x4 rb = round_block(blk, worker, key0, key1);
     uint32_t pk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -180,10 +181,9 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = 4 * k + e;
-            const float pos = (yv[e] + s) * inv;
             const uint32_t r = (rb.w[k] >> (8 * e)) & 0xFFu;
             const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
-            const float tt = pos + u;
+            const float tt = __builtin_fmaf(yv[e], inv, half + u);   // y * inv + (L/2 + u), one rounding
             const uint32_t idx = (uint32_t)fminf(floorf(tt), Lf);
             const int bit = j * BITS;
             pk[bit >> 5] |= idx << (bit & 31);

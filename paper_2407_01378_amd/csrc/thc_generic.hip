@@ -271,23 +271,23 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
             uint32_t pk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int j = 0; j < kEpt; ++j) {
-                float pos;
-                if (a.range_in) {   // min/max grid
+                const uint32_t r = (rb.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
+                float tt;   // position in grid units + noise, one fused operation
+                if (a.range_in) {   // min/max grid: (y - lo) * inv + u
                     const uint64_t p = (g0 + j) >> l;
                     const float lo = p < chunks ? a.range_in[2 * p] : 0.0f;
                     const float hi = p < chunks ? a.range_in[2 * p + 1] : 0.0f;
                     const float width = hi - lo;
                     const float inv = width != 0.0f ? Lf / width : 0.0f;
-                    pos = (v[j] - lo) * inv;
-                } else {
+                    tt = __builtin_fmaf(v[j] - lo, inv, u);
+                } else {            // symmetric grid: y * inv + (L/2 + u)
                     const float s = s_el[j];
                     const float two = s + s;
                     const float inv = two != 0.0f ? Lf / two : 0.0f;
-                    pos = (v[j] + s) * inv;
+                    const float half = (two != 0.0f || (a.levels & 1u) == 0u) ? 0.5f * Lf : 0.0f;
+                    tt = __builtin_fmaf(v[j], inv, half + u);
                 }
-                const uint32_t r = (rb.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-                const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
-                const float tt = pos + u;
                 uint32_t q = (uint32_t)fminf(floorf(tt), Lf);
                 if (g0 + j >= a.padded) q = 0u;
                 const uint32_t bit = (uint32_t)j * a.bits;

@@ -1,13 +1,15 @@
-"""Two facts about fp32 arithmetic that the tuned kernels rely on, checked here with
-NumPy float32 (every operation separately rounded, like the kernels and the oracle):
+"""Two facts about fp32 arithmetic that the tuned kernels rely on, checked here with the
+oracle's exact float32 fused multiply-add (tests only; the kernels share no code with it):
 
-1. With |y| <= s, floor((y + s) * inv + u) never exceeds L, so the clamp of the
-   rounding rule is dead whenever s is the chunk's own largest magnitude.
+1. With |y| <= s the rounding rule's t = fma(y, inv, L/2 + u) satisfies 0 < t < L + 1, so
+   the clamp min(floor(t), L) is dead whenever s is the chunk's own largest magnitude.
 2. For 2^-100 <= s <= 2^100 the normalisation y = v * 2^-7 can be folded into the
-   quantizer's constants: (v * 2^-7 + s) * inv == (v + 2^7 s) * (2^-7 inv) bit for bit.
+   multiplier: fma(v * 2^-7, inv, c) == fma(v, 2^-7 inv, c) bit for bit.
 """
 import numpy as np
 import pytest
+
+from oracle.thc import fma32
 
 F = np.float32
 
@@ -21,42 +23,43 @@ def _random_scales(rng, count, lo_exp, hi_exp):
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_clamp_is_dead_when_scale_is_the_largest_magnitude(bits):
     L = F((1 << bits) - 1)
+    half = F(0.5) * L
     rng = np.random.default_rng(5)
-    s = _random_scales(rng, 2_000_000, -120, 120)
-    two = s + s
-    inv = L / two
-    u_max = F(255.5 / 256.0)
-    # y = s is the worst case (pos is monotone in y); also the few values just below it
+    s = _random_scales(rng, 1_000_000, -120, 120)
+    inv = L / (s + s)
+    c_max = half + F(255.5 / 256.0)
+    c_min = half + F(0.5 / 256.0)
+    # t is monotone in y: the extremes are y = +s with the largest noise, y = -s with the smallest
     for y in (s, np.nextafter(s, F(0)), s * F(0.999)):
-        t = (y + s) * inv + u_max
+        t = fma32(y, inv, c_max)
         assert t.dtype == F
         assert (np.floor(t) <= L).all()
-    # and the lower end never goes negative
-    assert ((-s + s) * inv >= 0).all()
+    for y in (-s, -np.nextafter(s, F(0))):
+        t = fma32(y, inv, c_min)
+        assert (t > 0).all()
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])
 def test_folded_normalisation_is_bit_exact_inside_its_range(bits):
     L = F((1 << bits) - 1)
     rng = np.random.default_rng(11)
-    count = 2_000_000
+    count = 1_000_000
     s = _random_scales(rng, count, -100, 100)
     s[:4] = F(2.0) ** F(-100), F(2.0) ** F(100), np.nextafter(F(2.0) ** F(100), F(0)), F(2.0) ** F(-99)
     # v = 128 y with |y| <= s, including values that are tiny next to s and exact +-s
     frac = rng.uniform(-1.0, 1.0, size=count)
     frac[::7] = rng.choice([-1.0, 1.0], size=frac[::7].shape)
     frac[3::11] *= 2.0 ** -30
-    y_exact = (s.astype(np.float64) * frac).astype(F)
-    y_exact = np.clip(y_exact, -s, s)
-    v = y_exact * F(128.0)
+    y = np.clip((s.astype(np.float64) * frac).astype(F), -s, s)
+    v = y * F(128.0)
     assert np.isfinite(v).all()
     inv = L / (s + s)
-    plain = (v * F(0.0078125) + s) * inv
-    folded = (v + s * F(128.0)) * (inv * F(0.0078125))
-    assert plain.dtype == F and folded.dtype == F
+    c = F(0.5) * L + ((rng.integers(0, 256, size=count).astype(F) + F(0.5)) * F(2.0 ** -8))
+    plain = fma32(v * F(0.0078125), inv, c)
+    folded = fma32(v, inv * F(0.0078125), c)
     assert np.array_equal(plain.view(np.uint32), folded.view(np.uint32))
     # tiny v (y underflows to subnormal or zero) changes nothing either
     v_tiny = (rng.uniform(-1, 1, size=count) * 2.0 ** -140).astype(F)
-    plain = (v_tiny * F(0.0078125) + s) * inv
-    folded = (v_tiny + s * F(128.0)) * (inv * F(0.0078125))
+    plain = fma32(v_tiny * F(0.0078125), inv, c)
+    folded = fma32(v_tiny, inv * F(0.0078125), c)
     assert np.array_equal(plain.view(np.uint32), folded.view(np.uint32))

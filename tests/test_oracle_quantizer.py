@@ -266,3 +266,48 @@ def test_scale_is_shared_max_over_workers():
     assert scale_reduce(a).tolist() == [2.0, 0.0, 3.0]
     y = np.array([1.0, -4.0, 2.0, 0.5, 0, 0, 0, -0.25])
     assert chunk_absmax(y, 2).tolist() == [4.0, 0.25]
+
+
+# ------------------------------------------------------------ fused multiply-add helper
+def _rn32(F):
+    """Correct rounding of an exact rational to float32 (nearest, ties to even)."""
+    c = np.float32(float(F))
+    cands = {np.nextafter(c, np.float32(-np.inf)), c, np.nextafter(c, np.float32(np.inf))}
+    best = None
+    for x in cands:
+        d = abs(Fraction(float(x)) - F)
+        even = (int(np.float32(x).view(np.uint32)) & 1) == 0
+        key = (d, 0 if even else 1)
+        if best is None or key < best[0]:
+            best = (key, x)
+    return best[1]
+
+
+def test_fma32_is_correctly_rounded_against_exact_rationals():
+    from oracle.thc import fma32
+    rng = np.random.default_rng(12)
+    n = 3000
+    a = (rng.normal(size=n) * 10.0 ** rng.integers(-6, 6, size=n)).astype(np.float32)
+    b = (rng.normal(size=n) * 10.0 ** rng.integers(-6, 6, size=n)).astype(np.float32)
+    c = (rng.normal(size=n) * 10.0 ** rng.integers(-6, 6, size=n)).astype(np.float32)
+    c[::3] = (-a[::3].astype(np.float64) * b[::3].astype(np.float64)).astype(np.float32)   # heavy cancellation
+    got = fma32(a, b, c)
+    for i in range(n):
+        want = _rn32(Fraction(float(a[i])) * Fraction(float(b[i])) + Fraction(float(c[i])))
+        assert got[i] == want, (a[i], b[i], c[i], got[i], want)
+
+
+def test_fma32_breaks_float64_ties_by_the_discarded_bits():
+    """a * b + c lies a hair below (above) the midpoint of two float32 numbers, but the
+    float64 sum lands exactly on it: rounding that sum to float32 would go to the even
+    neighbour, the fused operation must go down (up)."""
+    from oracle.thc import fma32
+    a = np.float32(2.0 ** -12 * (1 + 2.0 ** -23))
+    b = np.float32(2.0 ** -12 * (1 - 2.0 ** -23))            # a * b = 2^-24 (1 - 2^-46)
+    c = np.float32(1 + 2.0 ** -23)
+    exact_sum_64 = np.float64(a) * np.float64(b) + np.float64(c)
+    assert exact_sum_64 == 1 + 2.0 ** -23 + 2.0 ** -24                           # the midpoint, in float64
+    assert np.float32(exact_sum_64) == np.float32(1 + 2.0 ** -22)                # naive: ties to even, up
+    assert fma32(a, b, c) == np.float32(1 + 2.0 ** -23)                          # fused: just below -> down
+    assert fma32(-a, b, -c) == np.float32(-(1 + 2.0 ** -23))                     # mirrored: e > 0
+    assert fma32(a, b, c) == _rn32(Fraction(float(a)) * Fraction(float(b)) + Fraction(float(c)))
