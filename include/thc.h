@@ -111,9 +111,10 @@ int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float
 /* Encode one worker: rotate, then stochastically round every rotated value onto
  * the 2^bits-point grid of [-s_p, +s_p] (index 0 at -s_p, index L = 2^bits - 1 at
  * +s_p), and bit-pack:
- *     inv = L / (s_p + s_p)  (0 if s_p == 0),  v = (y + s_p) * inv,
- *     idx = min(floor(v + u), L),  u = (r + 0.5) / 256
- * every operation a separately rounded fp32 operation.
+ *     inv = L / (s_p + s_p),  u = (r + 0.5) / 256,
+ *     idx = min(floor(fma(y, inv, L/2 + u)), L);   s_p == 0: idx = 0
+ * (the position y * inv + L/2 in grid units plus the noise u, evaluated as ONE fused
+ * multiply-add: L/2 + u is exact in fp32; inv is one correctly rounded division).
  *   shared_scale  chunks fp32 (the output of thc_scale_reduce), or NULL to use
  *                 this worker's own absmax
  *   payload       thc_payload_bytes bytes; coordinate g occupies bits
@@ -188,7 +189,8 @@ int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float
  * M = 2^(bits-1) - 1, so the aggregate never needs more than the `bits` bits a worker
  * sends (b = q).  Readings taken where the paper is silent:
  *   - a worker's coordinate is rounded onto the 2M + 1 evenly spaced points of
- *     [-s_p, +s_p] (same rule and random stream as thc_encode with L = 2M); the payload
+ *     [-s_p, +s_p] (same rule and random stream as thc_encode with L = 2M, except that
+ *     an all-zero chunk, s_p = 0, gets the centre index M so that z = 0); the payload
  *     holds idx in [0, 2M] in `bits` bits, packed as for thc_encode; z = idx - M;
  *   - Sat is not associative: a_0 = z_0, a_w = Sat(a_(w-1), z_w) in worker order
  *     w = 1 .. W-1 (the order payloads[] is given in);
@@ -240,7 +242,8 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
  * table) and an optional bf16 output -----------------------------------------------------
  * range arrays hold (lo, hi) pairs, 2 floats per chunk, 8-byte aligned.  The grid of a chunk
  * has 2^bits points, index 0 at lo and index L at hi, shared by all workers:
- *     inv = L / (hi - lo)  (0 when hi == lo),  idx = min(floor((y - lo) * inv + u), L)
+ *     inv = L / (hi - lo)  (0 when hi == lo),  idx = min(floor(fma(y - lo, inv, u)), L)
+ *     (the subtraction is rounded on its own; the product and the sum are one fused op)
  *     step = (hi - lo) / L,  yhat = float(sum) * (step / W) + lo
  * rotate != 0: y is the chunk's rotated gradient as in thc_encode; rotate == 0: y is the
  * zero-padded gradient itself (no sign diagonal, no butterflies, no normalisation).
