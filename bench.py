@@ -52,9 +52,9 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # Arithmetic the method asks for per worker-coordinate of the encode step at chunk 2^14:
 # sign flip, 14 butterfly stages, range, five quantizer ops (random byte to float, noise
 # constant, fused position + noise, floor, pack; the normalisation folds into the
-# multiplier), and one Philox4x32-10 block (10 rounds of 2 wide multiplies + 4 xors, 18 key
-# additions) per 16 coordinates.
-ENCODE_OPS_PER_COORD = 1 + 14 + 1 + 5 + (10 * 6 + 18) / 16.0
+# multiplier), and one Philox4x32-10 block (10 rounds of 2 wide multiplies + 2 three-input
+# xors, 18 key additions) per 16 coordinates.
+ENCODE_OPS_PER_COORD = 1 + 14 + 1 + 5 + (10 * 4 + 18) / 16.0
 PROBE_COPY_BYTES = 1 << 29
 
 

@@ -162,7 +162,7 @@ __device__ __forceinline__ void units_to_l1(const SignTable& tab, const uint4 (&
                 const int pair = 4 * k + d;  // coordinates 2 pair, 2 pair + 1
                 uint32_t x = w[d];
                 // sign bits of the pair sit at bits `pair` and 16 + `pair` of sx
-                if (SIGNED) x ^= (pair == 15 ? sx : (sx << (15 - pair))) & 0x80008000u;
+                if (SIGNED) x = xor_masked(x, pair == 15 ? sx : (sx << (15 - pair)), 0x80008000u);
                 v[2 * pair] = __uint_as_float(x << 16);
                 v[2 * pair + 1] = __uint_as_float(x & 0xFFFF0000u);
             }
@@ -176,7 +176,7 @@ __device__ __forceinline__ void units_to_l1(const SignTable& tab, const uint4 (&
             for (int d = 0; d < 4; ++d) {
                 const int r = 4 * k + d;
                 uint32_t x = w[d];
-                if (SIGNED) x ^= (sw << (31 - r)) & 0x80000000u;
+                if (SIGNED) x = xor_masked(x, r == 31 ? sw : (sw << (31 - r)), 0x80000000u);
                 v[r] = __uint_as_float(x);
             }
         }
@@ -295,9 +295,8 @@ __device__ __forceinline__ float wave_absmax(const float (&v)[kRegs]) {
 #pragma unroll
     for (int i = 0; i < kRegs; i += 2)
         asm("v_max3_f32 %0, %1, |%2|, |%3|" : "=v"(m) : "v"(m), "v"(v[i]), "v"(v[i + 1]));
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    return m;
+    // m >= 0: floats of one sign order like their bit patterns
+    return __uint_as_float(wave_umax(__float_as_uint(m)));
 }
 
 // max |v| over the whole chunk (every thread returns it).  Two barriers.

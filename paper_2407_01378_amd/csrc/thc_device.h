@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #pragma clang fp contract(off)
 
 namespace thc {
@@ -22,6 +24,37 @@ struct u32x4 {
     uint32_t w[4];
 };
 
+// a ^ b ^ c as one three-input bitwise operation (truth table 0x96); the compiler does
+// not form it from two xors by itself.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+// a ^ (b & c) as one operation (truth table 0x78).
+__device__ __forceinline__ uint32_t xor_masked(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x78);
+}
+
+// Largest of the 64 lanes' values in unsigned order, returned to every lane.  Lane
+// exchanges are data-parallel-primitive moves inside the vector ALU (no LDS traffic):
+// within quads, within half rows, within rows of 16, then row 0 -> 1 and 2 -> 3, then
+// rows 0..1 -> 2..3, which leaves the result in lane 63.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t wave_umax(uint32_t x) {
+    auto step = [&](auto ctrl, auto rows) {
+        const uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, decltype(ctrl)::value,
+                                                                 decltype(rows)::value, 0xF, false);
+        x = y > x ? y : x;
+    };
+    using std::integral_constant;
+    step(integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});   // quad_perm [1,0,3,2]
+    step(integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});   // quad_perm [2,3,0,1]
+    step(integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});  // row_half_mirror
+    step(integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});  // row_mirror
+    step(integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast:15 into rows 1, 3
+    step(integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast:31 into rows 2, 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies and
 // a word permutation, key bumped by the Weyl constants between rounds.
 __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -30,8 +63,8 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
         const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;

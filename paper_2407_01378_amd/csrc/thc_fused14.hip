@@ -110,12 +110,7 @@ struct EncodeAllCtx {
             if (done || spins >= a.max_spins) {
                 if (!done && lane == 0)
                     __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) {
-                    const uint32_t other = __shfl_xor(mx, o, 64);
-                    mx = other > mx ? other : mx;
-                }
-                sbits = mx;
+                sbits = wave_umax(mx);
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
