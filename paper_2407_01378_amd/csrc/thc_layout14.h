@@ -66,7 +66,7 @@ THC_HD uint32_t x2_store(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..
 }
 // reader (L3): wave = (i4,i7,i8), lane = (i5,i6,i0,i1,i2,i3), loads register rho = (i9..i13)
 THC_HD uint32_t x2_load(uint32_t wave, uint32_t lane, uint32_t rho) {  // rho = 0..31
-    return (lane & 3u) | (((lane >> 2) & 15u) << 2) | ((wave & 1u) << 6) | ((wave >> 1) << 7) | (rho << 9);
+    return ((lane & 3u) | (((lane >> 2) & 15u) << 2) | ((wave & 1u) << 6) | ((wave >> 1) << 7)) + (rho << 9);
 }
 
 // ---- X3e: L3 -> L4e (= L1), whole buffer ---------------------------------------------------
@@ -75,7 +75,7 @@ THC_HD uint32_t x2_load(uint32_t wave, uint32_t lane, uint32_t rho) {  // rho = 
 THC_HD uint32_t x3e_store(uint32_t wave, uint32_t lane, uint32_t rho) {
     const uint32_t i5i6 = lane & 3u, i0i1 = (lane >> 2) & 3u, i2 = (lane >> 4) & 1u, i3 = (lane >> 5) & 1u;
     const uint32_t i4 = wave & 1u, i7 = (wave >> 1) & 1u, i8 = (wave >> 2) & 1u;
-    return i0i1 | (i5i6 << 2) | ((i2 ^ i7) << 4) | (i3 << 5) | (i4 << 6) | (i7 << 7) | (i8 << 8) | (rho << 9);
+    return (i0i1 | (i5i6 << 2) | ((i2 ^ i7) << 4) | (i3 << 5) | (i4 << 6) | (i7 << 7) | (i8 << 8)) + (rho << 9);
 }
 // reader (L4e): wave = i11..i13, lane = i5..i10, loads registers 4q..4q+3 (q = i2..i4) as 128 bits
 THC_HD uint32_t x3e_load(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..7
@@ -89,7 +89,7 @@ THC_HD uint32_t x3d_store(uint32_t wave, uint32_t lane, uint32_t rho) {
     const uint32_t i5 = lane & 1u, i6 = (lane >> 1) & 1u, i0i1 = (lane >> 2) & 3u, i2 = (lane >> 4) & 1u,
                    i3 = (lane >> 5) & 1u;
     const uint32_t i4 = wave & 1u, i7i8 = wave >> 1;
-    return i0i1 | (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7i8 << 7) | (rho << 9);
+    return (i0i1 | (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7i8 << 7)) + (rho << 9);
 }
 // reader (L4d): wave = i8..i10, lane = i2..i7, loads registers (i0,i1) of group h = (i11..i13) as 128 bits
 THC_HD uint32_t x3d_load(uint32_t wave, uint32_t lane, uint32_t h) {  // h = 0..7
