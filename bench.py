@@ -110,8 +110,11 @@ class Path:
                       payloads=[torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(W)],
                       out=torch.empty(ln, dtype=torch.float32, device=dev))
             if fused:
+                # one workspace per bucket, cleared once: the timed calls are the form that
+                # expects it clear and leaves it clear (no clearing launch per call)
                 it["ws"] = torch.empty(thc.thc_encode_all_workspace_bytes(W, ln, l),
                                        dtype=torch.uint8, device=dev)
+                thc.thc_workspace_clear(it["ws"])
             else:
                 it["absmax"] = torch.empty(W * P, dtype=torch.float32, device=dev)
             it["sums"] = None if self.no_sums else torch.empty(P << l, dtype=sum_dt, device=dev)
@@ -126,7 +129,7 @@ class Path:
 
     # fused form
     def encode_all(self, it):
-        fn = self.thc.thc_sat_encode_all if self.sat else self.thc.thc_encode_all
+        fn = self.thc.thc_sat_encode_all_cleared if self.sat else self.thc.thc_encode_all_cleared
         fn(it["grads"], self.l, it["seed"], self.bits, it["payloads"], it["scale"], it["ws"])
 
     def aggregate_decode(self, it):

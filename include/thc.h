@@ -143,8 +143,8 @@ int thc_decode(const void* sums, const float* scale, uint32_t W, uint64_t n, uin
  * Same mathematics as the calls above and byte-identical payloads, scales, sums and
  * outputs; these forms read each gradient once and never store the integer sums. */
 
-/* Bytes of zero-initialisation-free scratch thc_encode_all needs for W workers of n
- * coordinates (the call clears what it uses).  0 on bad arguments. */
+/* Bytes of scratch thc_encode_all needs for W workers of n coordinates (it may be in
+ * any state: the call clears what it uses).  0 on bad arguments. */
 uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2);
 
 /* Encode all W workers in one pass: per chunk, rotate every worker's gradient, agree
@@ -166,6 +166,22 @@ uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_l
 int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
                    uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                    float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* thc_encode_all without its clearing launch, for a caller that keeps a workspace of its
+ * own across calls (one workspace per bucket of a training step, say).
+ * thc_workspace_clear zeroes a workspace (workspace_bytes a multiple of 4, pointer 16-byte
+ * aligned); thc_encode_all_cleared expects every byte of the workspace to be zero on
+ * entry and leaves it so: inside the kernel a chunk's range words are cleared as soon as
+ * every workgroup of the chunk has read them.  Same arguments, results and rules as
+ * thc_encode_all otherwise.  Exception: after a time-out the first word is 1 (it is how
+ * the time-out is reported) and other words may be left set; clear the workspace again
+ * before the next call.  A workspace that is not
+ * all zero gives wrong payloads without any error: when in doubt use thc_encode_all,
+ * which clears what it uses itself and accepts a workspace in any state. */
+int thc_workspace_clear(void* workspace, uint64_t workspace_bytes, void* stream);
+int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                           uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                           float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
 
 /* Upper bound on the polls of one inter-workgroup wait inside thc_encode_all (default
  * 2^22, about seconds).  A tuning and test knob: with a tiny limit the waits expire, the
@@ -211,6 +227,11 @@ int thc_sat_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_lo
 int thc_sat_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
                        uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                        float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
+/* thc_encode_all_cleared on the 2M + 1-point grid. */
+int thc_sat_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                               uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                               uint8_t* const* payloads, float* scale, void* workspace,
+                               uint64_t workspace_bytes, void* stream);
 
 /* Saturating aggregate of W payloads.
  *   payloads        HOST array of W device pointers

@@ -50,6 +50,15 @@ _SIGNATURES = {
                                       ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
                                       ctypes.c_void_p]),
+    "thc_workspace_clear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]),
+    "thc_encode_all_cleared": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_void_p]),
+    "thc_sat_encode_all_cleared": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_void_p]),
     "thc_set_spin_limit": (None, [ctypes.c_uint32]),
     "thc_aggregate_decode_is_fused": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint32,
                                                      ctypes.c_uint32]),
@@ -263,7 +272,7 @@ def thc_encode_all_workspace_bytes(W, n, chunk_log2):
     return lib().thc_encode_all_workspace_bytes(W, n, chunk_log2)
 
 
-def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+def _encode_all(name, grads, chunk_log2, seed, bits, payloads, scale, workspace, stream):
     W = len(grads)
     n = grads[0].numel()
     for g in grads:
@@ -272,11 +281,27 @@ def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, st
             raise ValueError("all workers must have gradients of one size and dtype")
     keep_g, pg = _ptr_array(grads)
     keep_p, pp = _ptr_array(payloads)
-    _check(lib().thc_encode_all(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
+    _check(getattr(lib(), name)(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
                                 _ptr(scale), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)),
-           "thc_encode_all")
+           name)
     return payloads
+
+
+def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+    return _encode_all("thc_encode_all", grads, chunk_log2, seed, bits, payloads, scale, workspace, stream)
+
+
+def thc_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+    return _encode_all("thc_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
+                       workspace, stream)
+
+
+def thc_workspace_clear(workspace, stream=None):
+    _flat(workspace)
+    _check(lib().thc_workspace_clear(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "thc_workspace_clear")
+    return workspace
 
 
 def thc_encode_all_timed_out(workspace):
@@ -316,19 +341,13 @@ def thc_sat_encode(grad, chunk_log2, seed, worker, bits, shared_scale, payload, 
 
 
 def thc_sat_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
-    W = len(grads)
-    n = grads[0].numel()
-    for g in grads:
-        _flat(g)
-        if g.numel() != n or g.dtype != grads[0].dtype:
-            raise ValueError("all workers must have gradients of one size and dtype")
-    keep_g, pg = _ptr_array(grads)
-    keep_p, pp = _ptr_array(payloads)
-    _check(lib().thc_sat_encode_all(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
-                                    _ptr(scale), _ptr(workspace),
-                                    workspace.numel() * workspace.element_size(), _stream(stream)),
-           "thc_sat_encode_all")
-    return payloads
+    return _encode_all("thc_sat_encode_all", grads, chunk_log2, seed, bits, payloads, scale, workspace,
+                       stream)
+
+
+def thc_sat_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+    return _encode_all("thc_sat_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
+                       workspace, stream)
 
 
 def thc_sat_aggregate(payloads, n, chunk_log2, bits, aggregate, overflow_count=None, stream=None):

@@ -232,14 +232,23 @@ uint64_t thc_encode_all_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_l
     if (W == 0 || check_common(n, chunk_log2) != THC_OK) return 0;
     const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
     // error word (padded to 16 bytes) + one word per chunk for every wave of every
-    // worker's workgroup (the unfused fallback keeps its per-worker ranges there too)
-    return 16 + 4 * (uint64_t)thc::encode_all_slot_words(W) * chunks;
+    // worker's workgroup (the unfused fallback keeps its per-worker ranges there too) +
+    // one arrival counter per chunk
+    return 16 + 4 * ((uint64_t)thc::encode_all_slot_words(W) + 1u) * chunks;
+}
+
+int thc_workspace_clear(void* workspace, uint64_t workspace_bytes, void* stream) {
+    if (workspace_bytes == 0) return THC_OK;
+    if (!workspace) return THC_ERR_NULL;
+    if (!aligned(workspace, 16) || (workspace_bytes & 3u) != 0) return THC_ERR_ALIGN;
+    return finish(thc::launch_zero_words(static_cast<uint32_t*>(workspace), workspace_bytes / 4,
+                                         static_cast<hipStream_t>(stream)));
 }
 
 static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
                            uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                            float* scale, void* workspace, uint64_t workspace_bytes, void* stream,
-                           bool sat) {
+                           bool sat, bool cleared) {
     int rc = check_common(n, chunk_log2);
     if (rc == THC_OK) rc = check_dtype(dt);
     if (rc == THC_OK) rc = check_bits(bits);
@@ -266,8 +275,10 @@ static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, u
     a.max_spins = g_spin_limit;
     a.levels = thc::grid_levels(bits, sat);
     a.scale = scale;
+    const uint64_t slot_words = (uint64_t)thc::encode_all_slot_words(W) * chunks;
     a.error = words;
     a.slots = words + 4;
+    a.done = words + 4 + slot_words;
     if (W <= (uint32_t)thc::kMaxFusedWorkers) {
         thc::FusedWorkerPtrs ptrs{};
         for (uint32_t w = 0; w < W; ++w) {
@@ -275,13 +286,15 @@ static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, u
             ptrs.payload[w] = payloads[w];
         }
         if (thc::encode_all_fused_applicable(a, ptrs, chunk_log2)) {
-            const uint64_t slot_words = (uint64_t)thc::encode_all_slot_words(W) * chunks;
-            if (thc::launch_zero_words(words, 4 + slot_words, st) != hipSuccess) return THC_ERR_HIP;
+            // The kernel needs the words zero and leaves them zero (the last wave to have
+            // read a chunk's words clears them), so a workspace known to be clear skips this.
+            if (!cleared && thc::launch_zero_words(words, 4 + slot_words + chunks, st) != hipSuccess)
+                return THC_ERR_HIP;
             return finish(thc::launch_encode_all_fused(a, ptrs, dt == THC_BF16, bits, st));
         }
     }
     // Fallback: the unfused sequence, per-worker ranges kept in the workspace.
-    if (thc::launch_zero_words(words, 4, st) != hipSuccess) return THC_ERR_HIP;
+    if (!cleared && thc::launch_zero_words(words, 4, st) != hipSuccess) return THC_ERR_HIP;
     float* absmax_all = reinterpret_cast<float*>(words + 4);
     for (uint32_t w = 0; w < W; ++w) {
         rc = thc_chunk_absmax(grads[w], dt, n, chunk_log2, seed, absmax_all + (uint64_t)w * chunks, stream);
@@ -290,6 +303,8 @@ static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, u
     rc = thc_scale_reduce(absmax_all, W, chunks, scale, stream);
     for (uint32_t w = 0; rc == THC_OK && w < W; ++w)
         rc = encode_impl(grads[w], dt, n, chunk_log2, seed, w, bits, scale, payloads[w], nullptr, stream, sat);
+    // a workspace that came in clear goes out clear
+    if (cleared && thc::launch_zero_words(words + 4, (uint64_t)W * chunks, st) != hipSuccess) return THC_ERR_HIP;
     return rc;
 }
 
@@ -297,7 +312,14 @@ int thc_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t 
                    uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                    float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
     return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
-                           workspace_bytes, stream, false);
+                           workspace_bytes, stream, false, false);
+}
+
+int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                           uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                           float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
+    return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
+                           workspace_bytes, stream, false, true);
 }
 
 int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
@@ -355,7 +377,15 @@ int thc_sat_encode_all(const void* const* grads, thc_dtype dt, uint32_t W, uint6
                        uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                        float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
     return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
-                           workspace_bytes, stream, true);
+                           workspace_bytes, stream, true, false);
+}
+
+int thc_sat_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                               uint32_t chunk_log2, uint64_t seed, uint32_t bits,
+                               uint8_t* const* payloads, float* scale, void* workspace,
+                               uint64_t workspace_bytes, void* stream) {
+    return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
+                           workspace_bytes, stream, true, true);
 }
 
 static int check_sat_payloads(const uint8_t* const* payloads, uint32_t W) {

@@ -42,6 +42,8 @@ struct EncodeAllCtx {
     uint32_t w;             // worker of every item of this workgroup (the grid is a multiple of W)
     uint32_t dp;            // chunk stride between consecutive items of this workgroup
     uint32_t parity;        // which sign table the next front() reads
+    uint32_t prev;          // chunk of the workgroup's previous item, kNone before the first
+    static constexpr uint32_t kNone = 0xFFFFFFFFu;
 
     __device__ __forceinline__ void load(uint32_t p) {
         const uint64_t g0 = (uint64_t)p << kChunkLog2;
@@ -110,14 +112,43 @@ struct EncodeAllCtx {
             if (done || spins >= a.max_spins) {
                 if (!done && lane == 0)
                     __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // The workspace leaves the kernel as it entered it, all zero.  A peer's wave
+                // publishes for this chunk only after the barriers of this item's rotation,
+                // which every wave of its workgroup reaches only after reading the words of
+                // the workgroup's previous chunk; with all of this chunk's words seen, nobody
+                // will read the previous chunk's words again, and this wave clears its own.
+                if (done && prev != kNone && lane == 0)
+                    __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 sbits = wave_umax(mx);
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
+        prev = p;
         const float s = __uint_as_float(sbits);
         if (w == 0 && t == 0) a.scale[p] = s;
         quantize_store<BITS, false>(v, s, a.levels, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+    }
+
+    // After the workgroup's last item: its words have no later chunk to vouch for them, so
+    // the workgroups of the chunk count themselves off and the last one clears the words
+    // of all of them, and the counter.
+    __device__ __forceinline__ void finish() {
+        if (prev == kNone) return;
+        __syncthreads();   // every wave of this workgroup has read the chunk's words
+        if (wave != 0) return;
+        uint32_t arrived = 0u;
+        if (lane == 0)
+            arrived = __hip_atomic_fetch_add(&a.done[prev], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)arrived);
+        if (arrived == a.W - 1u) {
+            uint32_t* words = a.slots + (uint64_t)prev * nwords;
+            for (uint32_t i = lane; i < nwords; i += 64u)
+                __hip_atomic_store(&words[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0)
+                __hip_atomic_store(&a.done[prev], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 };
 
@@ -131,7 +162,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(con
     const uint32_t t = threadIdx.x;
     const uint32_t p0 = blockIdx.x / a.W;
     EncodeAllCtx<BF16> c{a, ptrs, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
-                         gridDim.x / a.W, 0u};
+                         gridDim.x / a.W, 0u, EncodeAllCtx<BF16>::kNone};
     if (p0 >= a.chunks) return;
     if (EncodeAllCtx<BF16>::kDirect) {
         c.load(p0);
@@ -143,6 +174,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(con
         c.front(v, (uint32_t)p);
         c.template back<BITS>(v, (uint32_t)p);
     }
+    c.finish();
 }
 
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* dst, uint64_t words) {

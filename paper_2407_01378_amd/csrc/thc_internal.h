@@ -67,7 +67,8 @@ struct EncodeAllArgs {
     uint32_t max_spins;  // bound on the polls of one wait
     uint32_t levels;     // largest grid index L
     float* scale;        // out: chunks shared scales
-    uint32_t* slots;     // zeroed: chunks x encode_all_slot_words(W) words
+    uint32_t* slots;     // zero on entry and on exit: chunks x encode_all_slot_words(W) words
+    uint32_t* done;      // zero on entry and on exit: one arrival counter per chunk
     uint32_t* error;     // zeroed: set to 1 if a wait timed out
 };
 // Words per chunk in `slots`: one for every wave of every worker's workgroup.

@@ -138,6 +138,67 @@ def test_expired_wait_sets_the_error_word_and_every_wave_exits():
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("l,bits,W,dtype,sat", [
+    (14, 4, 8, torch.bfloat16, False), (14, 2, 3, torch.float32, False), (14, 8, 17, torch.bfloat16, False),
+    (14, 4, 8, torch.bfloat16, True), (10, 4, 4, torch.float32, False),   # the last one: unfused fallback
+])
+def test_cleared_workspace_form_matches_and_leaves_the_workspace_clear(l, bits, W, dtype, sat):
+    """thc_encode_all_cleared skips the clearing launch: on a workspace cleared once it must
+    give the bytes thc_encode_all gives, call after call, also when the next call is
+    smaller, and every byte of the workspace must be zero again after each call."""
+    c = 1 << l
+    n1, n2 = 37 * c + 11, 6 * c
+    ws = torch.full((thc.thc_encode_all_workspace_bytes(W, n1, l),), 0xCD, dtype=torch.uint8, device=DEV)
+    thc.thc_workspace_clear(ws)
+    plain = thc.thc_sat_encode_all if sat else thc.thc_encode_all
+    kept = thc.thc_sat_encode_all_cleared if sat else thc.thc_encode_all_cleared
+    for k, n in enumerate((n1, n2, n1)):
+        print(f"cleared l={l} bits={bits} W={W} dtype={dtype} sat={sat} n={n}", flush=True)
+        xs = [_rand(n, dtype, 500 + 10 * k + w, scale=10.0 ** (-1 - (w % 3))) for w in range(W)]
+        P = thc.thc_num_chunks(n, l)
+        nb = thc.thc_payload_bytes(n, l, bits)
+        got = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(W)]
+        ref = [torch.full((nb,), 0x55, dtype=torch.uint8, device=DEV) for _ in range(W)]
+        sc_got, sc_ref = torch.empty(P, device=DEV), torch.empty(P, device=DEV)
+        kept(xs, l, 40 + k, bits, got, sc_got, ws)
+        torch.cuda.synchronize()
+        assert int(ws.count_nonzero()) == 0, "the workspace did not come back clear"
+        ws2 = torch.empty(thc.thc_encode_all_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
+        plain(xs, l, 40 + k, bits, ref, sc_ref, ws2)
+        torch.cuda.synchronize()
+        assert torch.equal(sc_got, sc_ref)
+        for x, y in zip(got, ref):
+            assert torch.equal(x, y)
+
+
+def test_cleared_form_after_an_expired_wait_needs_a_new_clear():
+    """A time-out (forced from the host) is reported in the first word; the workspace is
+    then no longer clear, and clearing it makes the next call good again."""
+    l, bits, W = 14, 4, 8
+    n = 600 * (1 << 14)
+    xs = [_rand(n, torch.bfloat16, 190 + w) for w in range(W)]
+    P = thc.thc_num_chunks(n, l)
+    pay = [torch.empty(thc.thc_payload_bytes(n, l, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
+    sc = torch.empty(P, device=DEV)
+    ws = torch.empty(thc.thc_encode_all_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
+    thc.thc_workspace_clear(ws)
+    try:
+        thc.thc_set_spin_limit(0)
+        thc.thc_encode_all_cleared(xs, l, 2, bits, pay, sc, ws)
+        torch.cuda.synchronize()
+    finally:
+        thc.thc_set_spin_limit(1 << 22)
+    assert thc.thc_encode_all_timed_out(ws)
+    thc.thc_workspace_clear(ws)
+    thc.thc_encode_all_cleared(xs, l, 2, bits, pay, sc, ws)
+    torch.cuda.synchronize()
+    assert not thc.thc_encode_all_timed_out(ws) and int(ws.count_nonzero()) == 0
+    ref = run_path(xs, l, 2, bits)
+    assert torch.equal(sc, ref["scale"])
+    for x, y in zip(pay, ref["payloads"]):
+        assert torch.equal(x, y)
+
+
 def test_fused_on_full_1p3b_bucket_sampled_chunks():
     wl = workload("gpt_1p3b")
     for k, n in enumerate((wl.buckets()[0][1], wl.buckets()[-1][1])):
