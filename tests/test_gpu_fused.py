@@ -206,6 +206,6 @@ def test_fused_on_full_1p3b_bucket_sampled_chunks():
         got = run_path_fused(xs, 14, 21 + k, 4, keep_sums=(k == 0))
         P = O.num_chunks(n, 14)
         rng = np.random.default_rng(k)
-        chunks = sorted({0, P - 1, P // 2} | set(rng.integers(0, P, size=20).tolist()))
+        chunks = sorted({0, P - 1, P // 2} | set(rng.integers(0, P, size=128).tolist()))
         check_against_oracle(xs, got, 14, 21 + k, 4, chunks=chunks)
         del xs, got

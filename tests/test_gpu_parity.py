@@ -183,14 +183,26 @@ def _sample_chunks(P, k, seed):
     return sorted(pick)
 
 
-def test_resnet50_sized_sampled_chunks():
+def _protocol_chunks(wl, n, seed, k=256):
+    """First and last (padded) chunk, the chunks on both sides of every segment boundary
+    below n, and k random ones: chunks are independent, so this samples the whole."""
+    P = O.num_chunks(n, 14)
+    pick = set(_sample_chunks(P, k, seed))
+    for e in np.cumsum([sg.size for sg in wl.segments]):
+        if 0 < e < n:
+            pick |= {int(e - 1) >> 14, int(e) >> 14}
+    return sorted(p for p in pick if p < P)
+
+
+@pytest.mark.parametrize("quarter", [0, 1, 2, 3])
+def test_resnet50_sized_in_full(quarter):
+    """Every one of the 1,560 chunks, a quarter per test case."""
     wl = workload("resnet50")
     xs = [generate(wl, w, DEV) for w in range(wl.W)]
     got = run_path(xs, 14, 0, 4)
     P = O.num_chunks(wl.n, 14)
-    # chunks at every 8th segment boundary, first, last (padded) and random ones
-    edges = np.cumsum([s.size for s in wl.segments])[::8] // (1 << 14)
-    chunks = sorted(set(_sample_chunks(P, 24, 1)) | set(int(e) for e in edges if e < P))
+    chunks = list(range(quarter * P // 4, (quarter + 1) * P // 4))
+    print(f"resnet50 chunks {chunks[0]}..{chunks[-1]} of {P}", flush=True)
     check_against_oracle(xs, got, 14, 0, 4, chunks=chunks)
 
 
@@ -198,20 +210,21 @@ def test_bert_base_sized_sampled_chunks_with_sparse_embedding():
     wl = workload("bert_base")
     xs = [generate(wl, w, DEV) for w in range(wl.W)]
     got = run_path(xs, 14, 0, 4)
-    P = O.num_chunks(wl.n, 14)
     emb = wl.segments[0].size // (1 << 14)
-    chunks = sorted(set(_sample_chunks(P, 16, 2)) | set(range(0, emb, emb // 12)) | {emb, emb + 1})
+    chunks = sorted(set(_protocol_chunks(wl, wl.n, 2)) | set(range(0, emb, emb // 12)) | {emb, emb + 1})
+    print(f"bert_base {len(chunks)} chunks", flush=True)
     check_against_oracle(xs, got, 14, 0, 4, chunks=chunks)
     assert (got["scale"][:emb] == 0).any()          # all-zero chunks exist and were exercised
 
 
 @pytest.mark.parametrize("bits", [2, 8])
-def test_gpt_345m_first_layers_sampled_chunks(bits):
+def test_gpt_345m_sampled_chunks(bits):
     wl = workload("gpt_345m")
-    n = 40 * (1 << 20) + 12345
-    xs = [generate(wl, w, DEV, max_elems=n) for w in range(wl.W)]
+    xs = [generate(wl, w, DEV) for w in range(wl.W)]
     got = run_path(xs, 14, 0, bits)
-    check_against_oracle(xs, got, 14, 0, bits, chunks=_sample_chunks(O.num_chunks(n, 14), 16, bits))
+    chunks = _protocol_chunks(wl, wl.n, bits)
+    print(f"gpt_345m bits={bits} {len(chunks)} chunks of {O.num_chunks(wl.n, 14)}", flush=True)
+    check_against_oracle(xs, got, 14, 0, bits, chunks=chunks)
 
 
 def test_gpt_1p3b_buckets_sampled_chunks():
@@ -223,5 +236,7 @@ def test_gpt_1p3b_buckets_sampled_chunks():
     for k, n in enumerate((full, last)):
         xs = [generate(wl, w, DEV, max_elems=n) for w in range(wl.W)]
         got = run_path(xs, 14, 7 + k, 4)
-        check_against_oracle(xs, got, 14, 7 + k, 4, chunks=_sample_chunks(O.num_chunks(n, 14), 20, k))
+        chunks = _protocol_chunks(wl, n, k)
+        print(f"gpt_1p3b bucket of {n}: {len(chunks)} chunks", flush=True)
+        check_against_oracle(xs, got, 14, 7 + k, 4, chunks=chunks)
         del xs, got
