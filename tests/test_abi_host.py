@@ -128,6 +128,25 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.thc_aggregate(ctypes.cast(arr1, ctypes.POINTER(ctypes.c_void_p)), 1, 100, 10, 4, p, nul) == -8
 
 
+def test_cleared_workspace_entry_points_validate_on_the_host(L):
+    p, nul = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    assert L.thc_workspace_clear(nul, 0, nul) == 0                 # nothing to clear
+    assert L.thc_workspace_clear(nul, 64, nul) == -1
+    assert L.thc_workspace_clear(ctypes.c_void_p(0x1004), 64, nul) == -8
+    assert L.thc_workspace_clear(p, 62, nul) == -8                  # not whole words
+    arr = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    pp = ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p))
+    for fn in (L.thc_encode_all_cleared, L.thc_sat_encode_all_cleared):
+        assert fn(pp, thc.THC_BF16, 2, 100, 14, 0, 3, pp, p, p, 1 << 20, nul) == -2      # bits
+        assert fn(pp, thc.THC_BF16, 2, 100, 15, 0, 4, pp, p, p, 1 << 20, nul) == -3      # chunk
+        assert fn(pp, 9, 2, 100, 14, 0, 4, pp, p, p, 1 << 20, nul) == -5                 # dtype
+        assert fn(pp, thc.THC_BF16, 2, 0, 14, 0, 4, pp, p, p, 0, nul) == 0               # n = 0
+        assert fn(pp, thc.THC_BF16, 2, 100, 14, 0, 4, pp, p, nul, 1 << 20, nul) == -1    # workspace
+        assert fn(pp, thc.THC_BF16, 2, 100, 14, 0, 4, pp, p, p, 8, nul) == -6            # too small
+    # one arrival counter per chunk on top of the range words
+    assert L.thc_encode_all_workspace_bytes(8, 1 << 14, 14) == 16 + 4 * (8 * 8 + 1)
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     import paper_2407_01378_amd.binding as B
     monkeypatch.setattr(B, "_lib", None)
