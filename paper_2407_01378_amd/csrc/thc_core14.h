@@ -463,7 +463,7 @@ __device__ __forceinline__ void store_signed_l4d(const SignTable& tab, const flo
         for (int e = 0; e < 4; ++e)
             x[e] = __uint_as_float(__float_as_uint(v[4 * h + e] * kInvSqrtC) ^ ((sb << (31 - e)) & 0x80000000u));
         if (i0 + 4u <= valid) {
-            *reinterpret_cast<float4*>(out + i0) = make_float4(x[0], x[1], x[2], x[3]);
+            store_streaming(out + i0, x[0], x[1], x[2], x[3]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)

@@ -92,6 +92,25 @@ __device__ __forceinline__ u32x4 round_block(uint64_t block, uint32_t worker, ui
     return philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), worker, kTagRound, k0, k1);
 }
 
+// 16-byte accesses that tell the memory system the data will not be used again soon
+// (a payload read for the last time, an output nobody in this library reads back): they
+// leave the caches to the data that is reused.
+typedef uint32_t u32x4_vec __attribute__((ext_vector_type(4)));
+typedef float f32x4_vec __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_last_use(const uint4* p) {
+    const u32x4_vec q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_vec*>(p));
+    return make_uint4(q.x, q.y, q.z, q.w);
+}
+__device__ __forceinline__ uint2 load_last_use(const uint2* p) {
+    typedef uint32_t u32x2_vec __attribute__((ext_vector_type(2)));
+    const u32x2_vec q = __builtin_nontemporal_load(reinterpret_cast<const u32x2_vec*>(p));
+    return make_uint2(q.x, q.y);
+}
+__device__ __forceinline__ void store_streaming(float* p, float a, float b, float c, float d) {
+    const f32x4_vec q = {a, b, c, d};
+    __builtin_nontemporal_store(q, reinterpret_cast<f32x4_vec*>(p));
+}
+
 __device__ __forceinline__ float flip_sign(float v, uint32_t bit) {
     return __uint_as_float(__float_as_uint(v) ^ (bit << 31));
 }

@@ -193,13 +193,13 @@ template <int BITS>
 __device__ __forceinline__ PayloadWords<BITS> load_payload_words(const uint8_t* p) {
     PayloadWords<BITS> r;
     if (BITS == 2) {
-        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        const uint2 q = load_last_use(reinterpret_cast<const uint2*>(p));
         r.w[0] = q.x;
         r.w[1] = q.y;
     } else {
 #pragma unroll
         for (int k = 0; k < BITS / 4; ++k) {
-            const uint4 q = reinterpret_cast<const uint4*>(p)[k];
+            const uint4 q = load_last_use(reinterpret_cast<const uint4*>(p) + k);
             r.w[4 * k] = q.x;
             r.w[4 * k + 1] = q.y;
             r.w[4 * k + 2] = q.z;
