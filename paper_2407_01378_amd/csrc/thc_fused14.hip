@@ -359,6 +359,24 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
 // from a = 0, which leaves a = z_0 after the first worker), so the running value never
 // needs more than BITS bits.  Optionally stores the packed aggregate (a + M) and counts
 // the coordinates with at least one clipped step.
+// Called from inside the rotation of the current chunk: loads the first worker group of
+// the workgroup's next chunk.
+template <int BITS, int GROUP>
+struct NextSatLoads {
+    PayloadWords<BITS> (&x)[GROUP];
+    const FusedPayloadPtrs& ptrs;
+    uint32_t W;
+    uint64_t byte0;
+    bool active;
+    template <int K>
+    __device__ __forceinline__ void at() {
+        if (K != 0 || !active) return;
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j)
+            if ((uint32_t)j < W) x[j] = load_payload_words<BITS>(ptrs.p[j] + byte0);
+    }
+};
+
 template <int BITS, bool COUNT>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_kernel(
     const SatAggDecodeArgs a, const FusedPayloadPtrs ptrs) {
@@ -370,7 +388,14 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_
     const float Lf = (float)(2 * M);
     const float Wf = (float)a.W;
     uint32_t clipped_total = 0u;
+    const uint64_t thread_byte = (uint64_t)t * (4u * BITS);
 
+    PayloadWords<BITS> first[kGroup];   // the first worker group of the chunk about to start
+    {
+        NextSatLoads<BITS, kGroup> now{first, ptrs, a.W, (((uint64_t)blockIdx.x << kChunkLog2) * BITS) / 8u + thread_byte,
+                                       blockIdx.x < a.chunks};
+        now.template at<0>();
+    }
     for (uint64_t p = blockIdx.x; p < a.chunks; p += gridDim.x) {
         const uint64_t g0 = p << kChunkLog2;
         const uint64_t left = a.n - g0;
@@ -385,12 +410,12 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_
             acc[r] = 0;
             clip[r] = 0u;
         }
-        const uint64_t byte0 = (g0 * BITS) / 8u + (uint64_t)t * (4u * BITS);
+        const uint64_t byte0 = (g0 * BITS) / 8u + thread_byte;
         for (uint32_t w0 = 0; w0 < a.W; w0 += kGroup) {
             PayloadWords<BITS> x[kGroup];
 #pragma unroll
             for (int j = 0; j < kGroup; ++j)
-                if (w0 + j < a.W) x[j] = load_payload_words<BITS>(ptrs.p[w0 + j] + byte0);
+                if (w0 + j < a.W) x[j] = w0 == 0 ? first[j] : load_payload_words<BITS>(ptrs.p[w0 + j] + byte0);
 #pragma unroll
             for (int j = 0; j < kGroup; ++j)
                 if (w0 + j < a.W) {
@@ -435,7 +460,11 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_
         float v[kRegs];
 #pragma unroll
         for (int r = 0; r < kRegs; ++r) v[r] = (float)acc[r] * qf;
-        rotate_l1_to_l3<false>(sh, v, lane, wave);
+        // the next chunk's first payloads arrive while this one rotates
+        const uint64_t pn = p + gridDim.x;
+        NextSatLoads<BITS, kGroup> next{first, ptrs, a.W, ((pn << kChunkLog2) * BITS) / 8u + thread_byte,
+                                        pn < a.chunks};
+        rotate_l1_to_l3<false>(sh, v, lane, wave, next);
         l3_to_l4d<false>(sh, v, lane, wave);
         store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
     }
