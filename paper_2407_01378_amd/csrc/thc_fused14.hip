@@ -177,9 +177,23 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(con
     c.finish();
 }
 
+// Fill with zeros (a kernel, not a memset node, so that callers can capture it in a
+// graph).  Words before the first and after the last 16-byte boundary are written one
+// by one by the first block; the aligned middle goes out as 16-byte stores.
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* dst, uint64_t words) {
-    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < words) dst[i] = 0u;
+    const uint64_t addr = reinterpret_cast<uint64_t>(dst);
+    uint64_t head = ((16u - (addr & 15u)) & 15u) / 4u;   // dst is 4-byte aligned
+    if (head > words) head = words;
+    const uint64_t vecs = (words - head) / 4u;
+    const uint64_t tail0 = head + 4u * vecs;
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < head) dst[threadIdx.x] = 0u;
+        if (tail0 + threadIdx.x < words) dst[tail0 + threadIdx.x] = 0u;
+    }
+    uint4* mid = reinterpret_cast<uint4*>(dst + head);
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        mid[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // ------------------------------------------------------------- aggregate_decode
@@ -596,8 +610,9 @@ bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& 
 
 hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream) {
     if (words == 0) return hipSuccess;
-    hipLaunchKernelGGL(k14::zero_words_kernel, dim3((uint32_t)((words + 255) / 256)), dim3(256), 0, stream,
-                       dst, words);
+    const uint64_t blocks = (words / 4u + 255u) / 256u;
+    hipLaunchKernelGGL(k14::zero_words_kernel, dim3((uint32_t)(blocks < 1u ? 1u : (blocks > 8192u ? 8192u : blocks))),
+                       dim3(256), 0, stream, dst, words);
     return hipGetLastError();
 }
 

@@ -72,6 +72,26 @@ def test_topkc_matches_oracle(n, C, J, W, dtype):
     check(xs, run_topkc(xs, C, J), C, J)
 
 
+@pytest.mark.parametrize("offset", [0, 1, 2, 3])
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 64, 1000, 65_537, 1_000_003])
+def test_scatter_fills_unaligned_outputs_exactly(offset, n):
+    """The zero fill under topkc_scatter_mean writes 16 bytes at a time in the aligned
+    middle of the output and word by word at its ends: nothing outside [0, n) may change
+    and nothing inside may be left over, wherever the output starts."""
+    C, W = 8, 2
+    J = min(3, (n + C - 1) // C)
+    buf = torch.full((n + 8,), 7.0, device=DEV)
+    out = buf[offset:offset + n]
+    vals = torch.full((J * C,), 4.0, dtype=torch.float16, device=DEV)
+    idx = torch.arange(J, dtype=torch.int32, device=DEV)
+    thc.topkc_scatter_mean(vals, idx, J, C, W, out)
+    torch.cuda.synchronize()
+    want = torch.zeros(n, device=DEV)
+    want[:min(n, J * C)] = 2.0
+    assert torch.equal(out, want)
+    assert (buf[:offset] == 7.0).all() and (buf[offset + n:] == 7.0).all()
+
+
 def test_topkc_many_ties_and_zero_chunks():
     """Most chunks are exactly zero (their fp16 norms tie at 0) and many non-zero chunks tie
     too: the J-th place falls among equal keys and must go to the lowest indices."""
