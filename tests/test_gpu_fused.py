@@ -140,7 +140,9 @@ def test_expired_wait_sets_the_error_word_and_every_wave_exits():
 
 @pytest.mark.parametrize("l,bits,W,dtype,sat", [
     (14, 4, 8, torch.bfloat16, False), (14, 2, 3, torch.float32, False), (14, 8, 17, torch.bfloat16, False),
-    (14, 4, 8, torch.bfloat16, True), (10, 4, 4, torch.float32, False),   # the last one: unfused fallback
+    (14, 4, 8, torch.bfloat16, True), (10, 4, 4, torch.float32, False),   # (10, ...): unfused fallback
+    (14, 4, 5, torch.bfloat16, False), (14, 4, 7, torch.float32, False), (14, 2, 64, torch.bfloat16, False),
+    (14, 4, 1, torch.bfloat16, False),
 ])
 def test_cleared_workspace_form_matches_and_leaves_the_workspace_clear(l, bits, W, dtype, sat):
     """thc_encode_all_cleared skips the clearing launch: on a workspace cleared once it must
