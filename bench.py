@@ -503,6 +503,16 @@ def main():
     dom_s = kernels[path.dominant]["us_per_launch"] * 1e-6
     achieved = dom_bytes / dom_s / 1e9
 
+    # The other kernel of the fused form, same accounting: W payloads in, fp32 estimate out.
+    second = None
+    if path.fused and not a.full_rotation and "aggregate_decode" in kernels:
+        sec_bytes = coords_per_launch * (W * bits / 8.0 + 4.0)
+        sec_gbs = sec_bytes / (kernels["aggregate_decode"]["us_per_launch"] * 1e-6) / 1e9
+        sec_name = "thc_sat_aggregate_decode" if a.sat else "thc_aggregate_decode"
+        second = {"bound": "hbm", "kernel": sec_name, "achieved": round(sec_gbs, 1), "peak": HBM_PEAK_GBS,
+                  "unit": "GB/s", "frac": round(sec_gbs / HBM_PEAK_GBS, 4),
+                  "traffic": read_traffic(wl.name, bits, "thc_aggregate_decode") if not a.sat else None}
+
     dom_ops = (path.size * (path.l + 2.0) if a.full_rotation
                else coords_per_launch * (W if path.fused else 1) * ENCODE_OPS_PER_COORD)
     alu_achieved = dom_ops / dom_s / 1e12
@@ -531,6 +541,7 @@ def main():
                          "peak": round(VALU_PEAK_TOPS, 2), "unit": "Top/s",
                          "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
                          "ops_per_worker_coord": ENCODE_OPS_PER_COORD},
+        "roofline_second": second,
         "pct_hbm_peak": round(100.0 * wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "copy_GBps": round(copy_gbs, 1),
         "pipeline_hbm": {"algorithmic_bytes_per_coord": alg_bytes_per_coord,
