@@ -104,3 +104,31 @@ def check_against_oracle(xs, got, l, seed, bits, chunks=None):
             worst = max(worst, err)
         assert (seg == ref["out"]).all(), f"decode differs from the fp32 canonical order, chunk {p0}"
     return worst
+
+
+def check_chunks_sliced(xs, got, l, seed, bits, chunks):
+    """check_against_oracle for arrays too large to copy to the host whole: only the
+    listed chunks' slices of every array leave the device."""
+    W = len(xs)
+    n = xs[0].numel()
+    c = 1 << l
+    bf16 = xs[0].dtype == torch.bfloat16
+    for p in sorted(set(chunks)):
+        g0 = p * c
+        ln = min(n, g0 + c) - g0
+        hx = [to_numpy_bits(x[g0:g0 + ln]) for x in xs]
+        ref = O.pipeline(hx, l, seed, bits, dtype=np.float32, bf16=bf16, g0=g0)
+        assert float(got["scale"][p]) == float(ref["scale"][0]), f"scale differs, chunk {p}"
+        if "absmax" in got:
+            assert (got["absmax"][:, p].cpu().numpy() == ref["absmax"][:, 0]).all(), f"absmax differs, chunk {p}"
+        b0, b1 = g0 * bits // 8, (g0 + c) * bits // 8
+        for w in range(W):
+            same = got["payloads"][w][b0:b1].cpu().numpy() == ref["payloads"][w]
+            assert same.all(), f"payload of worker {w} differs in chunk {p}: {np.flatnonzero(~same)[:8]}"
+        if got.get("sums") is not None:
+            assert (sums_to_numpy(got["sums"][g0:g0 + c]) == ref["sums"]).all(), f"sums differ, chunk {p}"
+        seg = got["out"][g0:g0 + ln].cpu().numpy()
+        d64 = O.decode(ref["sums"], ref["scale"].astype(np.float64), W, ln, l, seed, bits, g0=g0)
+        nrm = np.linalg.norm(d64)
+        assert nrm == 0 or np.linalg.norm(seg - d64) / nrm <= 1e-5, f"decode rel-L2, chunk {p}"
+        assert (seg == ref["out"]).all(), f"decode differs from the fp32 canonical order, chunk {p}"

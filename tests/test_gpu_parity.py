@@ -240,3 +240,37 @@ def test_gpt_1p3b_buckets_sampled_chunks():
         print(f"gpt_1p3b bucket of {n}: {len(chunks)} chunks", flush=True)
         check_against_oracle(xs, got, 14, 7 + k, 4, chunks=chunks)
         del xs, got
+
+
+def test_coordinates_beyond_2_to_32():
+    """4 Gi + 3 chunks + 100 coordinates per worker: global indices (Philox counters, byte
+    offsets, chunk numbers) cross 2^32.  Both forms, chunks sampled on both sides of the
+    boundary and at the ragged end."""
+    from gpu_util import check_chunks_sliced, run_path_fused
+    l, bits, W = 14, 4, 2
+    n = (1 << 32) + 3 * (1 << 14) + 100
+    print(f"large n={n}", flush=True)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4)
+    block = (torch.randn(1 << 24, generator=g, device=DEV) * 1e-3).to(torch.bfloat16)
+    xs = []
+    for w in range(W):
+        x = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+        full = n // block.numel()
+        x[:full * block.numel()].view(full, -1).copy_(block.roll(1000 * w + 1).unsqueeze(0).expand(full, -1))
+        x[full * block.numel():] = block[:n - full * block.numel()] * (w + 1)
+        xs.append(x)
+    P = O.num_chunks(n, l)
+    edge = (1 << 32) >> l
+    chunks = [0, 1, edge - 2, edge - 1, edge, edge + 1, P - 2, P - 1, P // 3]
+    got = run_path_fused(xs, l, 3, bits, keep_sums=False)
+    check_chunks_sliced(xs, got, l, 3, bits, chunks)
+    fused_out = got["out"]
+    fused_pay = got["payloads"]
+    print("large n: one-call-per-step form", flush=True)
+    got = run_path(xs, l, 3, bits)
+    check_chunks_sliced(xs, got, l, 3, bits, chunks)
+    # the two forms agree everywhere, not only on the sampled chunks
+    for a, b in zip(fused_pay, got["payloads"]):
+        assert torch.equal(a, b)
+    assert torch.equal(fused_out, got["out"])
