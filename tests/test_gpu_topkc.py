@@ -148,3 +148,44 @@ def test_topkc_on_headline_workload_slice():
     got = run_topkc(xs, C, J)
     check(xs, got, C, J)
     print(f"bits per coordinate: {K.bits_per_coordinate(J, C, n):.3f}", flush=True)
+
+
+def test_topkc_offsets_beyond_2_to_32():
+    """More than 2^32 coordinates, all zero except five chunks on both sides of the 2^32
+    boundary and at the ragged end: chunk numbers, gather and scatter offsets cross 32
+    bits.  The oracle runs on the five chunks laid side by side, which is the same problem
+    (zero chunks have norm 0 and cannot be selected ahead of them)."""
+    C, W, J = 64, 2, 5
+    n = (1 << 32) + 64 * 10 + 17
+    P = thc.topkc_num_chunks(n, C)
+    edge = (1 << 32) // C
+    picks = [7, edge - 1, edge + 3, P - 5, P - 1]
+    print(f"topkc large n={n} P={P} picks={picks}", flush=True)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(12)
+    xs = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for _ in range(W)]
+    compact = [np.zeros(J * C, dtype=np.uint16) for _ in range(W)]
+    for w in range(W):
+        for k, p in enumerate(picks):
+            ln = min(n, (p + 1) * C) - p * C
+            v = (torch.randn(ln, generator=g, device=DEV) * (0.05 * (k + 1))).to(torch.bfloat16)
+            xs[w][p * C:p * C + ln] = v
+            compact[w][k * C:k * C + ln] = to_numpy_bits(v)
+    got = run_topkc(xs, C, J)
+    ref = K.pipeline(compact, C, J, bf16=True)
+    assert ref["indices"].tolist() == list(range(J))
+    assert got["indices"].cpu().numpy().tolist() == picks
+    sel = torch.tensor(picks, device=DEV)
+    for w in range(W):
+        assert (_bits16(got["norms"][w][sel]) == ref["norms"][w].view(np.uint16)).all()
+        assert int(got["norms"][w].count_nonzero()) == J
+    assert (_bits16(got["s"][sel]) == ref["s"].view(np.uint16)).all()
+    assert int(got["s"].count_nonzero()) == J
+    assert (_bits16(got["values"]) == ref["values"].view(np.uint16)).all()
+    nonzero = 0
+    for k, p in enumerate(picks):
+        ln = min(n, (p + 1) * C) - p * C
+        seg = got["out"][p * C:p * C + ln].cpu().numpy()
+        assert (seg == ref["out"][k * C:k * C + ln]).all(), f"estimate differs in chunk {p}"
+        nonzero += int(np.count_nonzero(seg))
+    assert int(got["out"].count_nonzero()) == nonzero
