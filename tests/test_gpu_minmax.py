@@ -113,3 +113,37 @@ def test_minmax_all_equal_chunk_decodes_to_the_constant():
     for p in got["payloads"]:
         assert (p == 0).all()
     assert (got["out"] == 0.375).all()
+
+
+@pytest.mark.parametrize("rotate", [True, False])
+def test_minmax_coordinates_beyond_2_to_32(rotate):
+    """Min/max variant with global indices past 2^32, chunks sampled around the boundary
+    and at the ragged end."""
+    l, bits, W = 14, 4, 2
+    c = 1 << l
+    n = (1 << 32) + 2 * c + 55
+    g = torch.Generator(device=DEV)
+    g.manual_seed(9)
+    block = (torch.randn(1 << 24, generator=g, device=DEV) * 1e-3 + 2e-3).to(torch.bfloat16)
+    xs = []
+    for w in range(W):
+        x = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+        full = n // block.numel()
+        x[:full * block.numel()].view(full, -1).copy_(block.roll(31 * w + 2).unsqueeze(0).expand(full, -1))
+        x[full * block.numel():] = block[:n - full * block.numel()]
+        xs.append(x)
+    print(f"minmax large n={n} rotate={rotate}", flush=True)
+    got = run_minmax(xs, l, 4, bits, rotate, torch.float32)
+    P = thc.thc_num_chunks(n, l)
+    edge = (1 << 32) >> l
+    for p in (0, edge - 1, edge, edge + 1, P - 2, P - 1):
+        g0 = p * c
+        ln = min(n, g0 + c) - g0
+        ref = M.pipeline_minmax([to_numpy_bits(x[g0:g0 + ln]) for x in xs], l, 4, bits, rotate=rotate,
+                                dtype=np.float32, bf16=True, g0=g0)
+        assert (got["range"][p].cpu().numpy() == ref["range"][0]).all(), p
+        b0, b1 = g0 * bits // 8, (g0 + c) * bits // 8
+        for w in range(W):
+            assert (got["payloads"][w][b0:b1].cpu().numpy() == ref["payloads"][w]).all(), (p, w)
+        assert (sums_to_numpy(got["sums"][g0:g0 + c]) == ref["sums"]).all(), p
+        assert (got["out"][g0:g0 + ln].cpu().numpy() == ref["out"]).all(), p

@@ -160,3 +160,43 @@ def test_sat_on_headline_bucket_sampled_chunks():
         total_clipped += int(ref["clipped"].sum())
     assert 0 <= got["overflow"] <= n
     print(f"overflow rate on the bucket: {got['overflow'] / n:.4f}", flush=True)
+
+
+def test_sat_coordinates_beyond_2_to_32():
+    """Saturating variant with global indices past 2^32 (both encode forms, both
+    aggregate + decode forms), chunks sampled around the boundary and at the ragged end.
+    The overflow count, which covers every coordinate, is compared between the forms."""
+    l, bits, W = 14, 4, 2
+    c = 1 << l
+    n = (1 << 32) + 2 * c + 321
+    g = torch.Generator(device=DEV)
+    g.manual_seed(8)
+    block = (torch.randn(1 << 24, generator=g, device=DEV) * 1e-3).to(torch.bfloat16)
+    xs = []
+    for w in range(W):
+        x = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+        full = n // block.numel()
+        x[:full * block.numel()].view(full, -1).copy_(block.roll(77 * w + 5).unsqueeze(0).expand(full, -1))
+        x[full * block.numel():] = block[:n - full * block.numel()]
+        xs.append(x)
+    P = thc.thc_num_chunks(n, l)
+    edge = (1 << 32) >> l
+    results = []
+    for fused in (True, False):
+        print(f"sat large n={n} fused={fused}", flush=True)
+        got = run_sat(xs, l, 6, bits, fused, fused)
+        for p in (0, edge - 1, edge, edge + 1, P - 2, P - 1):
+            g0 = p * c
+            ln = min(n, g0 + c) - g0
+            ref = S.sat_pipeline([to_numpy_bits(x[g0:g0 + ln]) for x in xs], l, 6, bits, dtype=np.float32,
+                                 bf16=True, g0=g0)
+            assert float(got["scale"][p]) == float(ref["scale"][0])
+            b0, b1 = g0 * bits // 8, (g0 + c) * bits // 8
+            for w in range(W):
+                assert (got["payloads"][w][b0:b1].cpu().numpy() == ref["payloads"][w]).all(), (p, w)
+            assert (got["aggregate"][b0:b1].cpu().numpy() == ref["packed_aggregate"]).all(), p
+            assert (got["out"][g0:g0 + ln].cpu().numpy() == ref["out"]).all(), p
+        results.append(got)
+    a, b = results
+    assert a["overflow"] == b["overflow"]
+    assert torch.equal(a["aggregate"], b["aggregate"]) and torch.equal(a["out"], b["out"])
