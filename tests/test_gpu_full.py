@@ -100,3 +100,40 @@ def test_full_rotation_argument_checks():
         thc.rht_forward_full(torch.empty((1 << 15) + 4, device=DEV), 15, 0, y)   # n > 2^l
     with pytest.raises(thc.ThcError):
         thc.rht_forward_full(x[1:], 15, 0, y)      # x not 16-byte aligned
+
+
+def test_full_rotation_over_2_to_33_coordinates():
+    """One rotation over 2^33 coordinates (n just above 2^32): element indices need 33 bits.
+    The input is zero except for a few exactly representable entries, so every output value
+    has the closed form  y_i = N^(-1/2) * sum_j D_kj x_kj (-1)^popcount(i & kj)  (a few terms,
+    exact before the final scaling), checked at positions on both sides of 2^32; the
+    inverse must then give the input back."""
+    l = 33
+    n = (1 << 32) + 12_345
+    assert thc.thc_full_log2(n) == l
+    ks = [0, 5, (1 << 14) + 3, (1 << 31) + 7, (1 << 32) + 11, n - 1]
+    vs = [1.0, -2.0, 0.5, 4.0, 1.0, -1.0]
+    x = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    for k, v in zip(ks, vs):
+        x[k] = v
+    y = torch.empty(1 << l, device=DEV)
+    print(f"full rotation l={l} n={n}", flush=True)
+    thc.rht_forward_full(x, l, 9, y)
+    torch.cuda.synchronize()
+    signed = [(-v if O.sign_bits(k, 1, 9)[0] else v) for k, v in zip(ks, vs)]
+    rng = np.random.default_rng(0)
+    probe = [0, 1, (1 << 14) - 1, 1 << 14, (1 << 32) - 1, 1 << 32, (1 << 32) + 11, (1 << 33) - 1]
+    probe += [int(i) for i in rng.integers(0, 1 << 33, size=200)]
+    got = y[torch.tensor(probe, device=DEV)].cpu().numpy().astype(np.float64)
+    want = np.array([sum(s * (-1) ** bin(i & k).count("1") for s, k in zip(signed, ks)) for i in probe],
+                    dtype=np.float64) * 2.0 ** -16.5
+    assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
+    # energy: the rotation is orthonormal (sum over all 2^33 outputs, in float64 on the device)
+    step = 1 << 28
+    energy = sum(float((y[a:a + step].double() ** 2).sum()) for a in range(0, 1 << l, step))
+    assert abs(energy - sum(v * v for v in vs)) <= 1e-5 * sum(v * v for v in vs)
+    back = torch.full((n,), float("nan"), device=DEV)
+    thc.rht_inverse_full(y, n, l, 9, back)
+    torch.cuda.synchronize()
+    err2 = sum(float(((back[a:a + step] - x[a:a + step].float()).double() ** 2).sum()) for a in range(0, n, step))
+    assert err2 ** 0.5 <= 1e-5 * sum(v * v for v in vs) ** 0.5
