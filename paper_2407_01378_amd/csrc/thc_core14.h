@@ -437,7 +437,8 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
 }
 
 // Min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo) (0 for a constant chunk).
-template <int BITS>
+// ROTATED false: v holds y itself (the unrotated, zero-padded gradient), not 2^7 y.
+template <int BITS, bool ROTATED = true>
 __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], float lo, float hi, uint32_t L,
                                                      uint64_t g0, uint32_t worker, uint32_t key0,
                                                      uint32_t key1, uint8_t* payload, uint32_t t) {
@@ -445,7 +446,7 @@ __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], fl
     const float inv = width != 0.0f ? (float)L / width : 0.0f;
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];
-    quantize_pack<BITS, true, false, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);
+    quantize_pack<BITS, true, !ROTATED, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);
     store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 

@@ -69,6 +69,37 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
     }
 }
 
+// The "no rotation" arm of the min/max variant: y is the zero-padded gradient itself, so a
+// chunk needs no exchange at all.  Thread t loads its 32 consecutive coordinates, and
+// either the workgroup reduces them to (min, max) or the thread quantizes them onto the
+// given range and stores its 4 * BITS payload bytes.
+template <bool BF16, Mode MODE, int BITS>
+__global__ __launch_bounds__(kThreads) void unrotated_kernel(const ChunkArgs a) {
+    __shared__ Shared sh;
+    constexpr int kUnits = BF16 ? 4 : 8;
+    constexpr int kElem = BF16 ? 2 : 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint64_t p = blockIdx.x;
+    const uint64_t g0 = p << kChunkLog2;
+    const uint64_t left = a.n - g0;
+    const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    Raw<kUnits> raw;
+    load_raw<kUnits, kElem, true>(raw, static_cast<const uint8_t*>(a.in) + g0 * kElem, valid, t);
+    float v[kRegs];
+    units_to_l1<kUnits, false>(sh.sign[0], raw.u, v, t);
+    if constexpr (MODE == Mode::MinMax) {
+        const MinMax r = chunk_minmax(sh, v, lane, wave);
+        if (t == 0) {
+            static_cast<float*>(a.out)[2 * p] = r.lo;
+            static_cast<float*>(a.out)[2 * p + 1] = r.hi;
+        }
+    } else {
+        const float lo = a.range_in[2 * p], hi = a.range_in[2 * p + 1];
+        quantize_store_range<BITS, false>(v, lo, hi, a.levels, g0, a.worker, a.key0, a.key1,
+                                          static_cast<uint8_t*>(a.out), t);
+    }
+}
+
 // Inverse direction, one chunk per workgroup.
 //   SRC 0: rotated fp32 values (rht_inverse);  1: u8 sums;  2: u16 sums (thc_decode);
 //       3: packed saturated aggregate, offset binary (thc_sat_decode)
@@ -159,6 +190,19 @@ hipError_t launch_bits(const ChunkArgs& a, dim3 grid, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <bool BF16>
+hipError_t launch_unrotated(Mode mode, const ChunkArgs& a, dim3 grid, hipStream_t stream) {
+    if (mode == Mode::MinMax)
+        hipLaunchKernelGGL((unrotated_kernel<BF16, Mode::MinMax, 4>), grid, dim3(kThreads), 0, stream, a);
+    else if (a.bits == 2)
+        hipLaunchKernelGGL((unrotated_kernel<BF16, Mode::Encode, 2>), grid, dim3(kThreads), 0, stream, a);
+    else if (a.bits == 4)
+        hipLaunchKernelGGL((unrotated_kernel<BF16, Mode::Encode, 4>), grid, dim3(kThreads), 0, stream, a);
+    else
+        hipLaunchKernelGGL((unrotated_kernel<BF16, Mode::Encode, 8>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -167,7 +211,9 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool fast14_applicable(Mode mode, const ChunkArgs& a) {
     if (a.chunk_log2 != 14) return false;
     if ((a.padded >> 14) > 0x7FFFFFFFull) return false;
-    if (a.no_rotate || a.out_bf16 || mode == Mode::Plain) return false;
+    if (a.out_bf16 || mode == Mode::Plain) return false;
+    // without the rotation: the range and the encoder on a given range have a tuned form
+    if (a.no_rotate && !(mode == Mode::MinMax || (mode == Mode::Encode && a.range_in))) return false;
     return k14::aligned16(a.in) && k14::aligned16(a.out);
 }
 
@@ -175,6 +221,8 @@ hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
     using namespace k14;
     const dim3 grid((uint32_t)(a.padded >> 14));
     if (grid.x == 0) return hipSuccess;
+    if (a.no_rotate)
+        return a.in_bf16 ? launch_unrotated<true>(mode, a, grid, stream) : launch_unrotated<false>(mode, a, grid, stream);
     switch (mode) {
         case Mode::Forward:
             return a.in_bf16 ? launch_bits<true, Mode::Forward>(a, grid, stream)
