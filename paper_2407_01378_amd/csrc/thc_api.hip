@@ -285,7 +285,7 @@ static int encode_all_impl(const void* const* grads, thc_dtype dt, uint32_t W, u
             ptrs.grad[w] = grads[w];
             ptrs.payload[w] = payloads[w];
         }
-        if (thc::encode_all_fused_applicable(a, ptrs, chunk_log2)) {
+        if (thc::encode_all_fused_applicable(a, ptrs, chunk_log2, dt == THC_BF16, bits)) {
             // The kernel needs the words zero and leaves them zero (the last wave to have
             // read a chunk's words clears them), so a workspace known to be clear skips this.
             if (!cleared && thc::launch_zero_words(words, 4 + slot_words + chunks, st) != hipSuccess)

@@ -589,7 +589,10 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
-    if (G > a.W) G -= G % a.W;   // whole chunks per round of the grid
+    // every workgroup keeps one worker, so the grid is a whole number of chunks per round;
+    // fewer resident workgroups than workers would leave peers that never run
+    if (G < a.W) return hipErrorInvalidConfiguration;
+    G -= G % a.W;
     hipLaunchKernelGGL((encode_all_kernel<BF16, BITS>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
     return hipGetLastError();
 }
@@ -599,9 +602,23 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
 
 uint32_t encode_all_slot_words(uint32_t W) { return k14::kWaves * W; }
 
-bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2) {
+// Workgroups of the one-pass encoder that the device keeps resident at once.
+static uint32_t encode_all_resident(bool bf16, uint32_t bits) {
+    using namespace k14;
+    if (bf16) return bits == 2 ? resident_grid<encode_all_kernel<true, 2>>()
+                   : bits == 4 ? resident_grid<encode_all_kernel<true, 4>>()
+                               : resident_grid<encode_all_kernel<true, 8>>();
+    return bits == 2 ? resident_grid<encode_all_kernel<false, 2>>()
+         : bits == 4 ? resident_grid<encode_all_kernel<false, 4>>()
+                     : resident_grid<encode_all_kernel<false, 8>>();
+}
+
+bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2,
+                                 bool bf16, uint32_t bits) {
     if (chunk_log2 != 14 || a.W > (uint32_t)kMaxFusedWorkers) return false;
     if (a.chunks * a.W >= 0x7FFFFFFFull) return false;
+    // the W workgroups of a chunk wait for one another: all of them must be resident
+    if (encode_all_resident(bf16, bits) < a.W) return false;
     for (uint32_t w = 0; w < a.W; ++w)
         if ((reinterpret_cast<uintptr_t>(ptrs.grad[w]) & 15u) || (reinterpret_cast<uintptr_t>(ptrs.payload[w]) & 15u))
             return false;
@@ -631,9 +648,12 @@ hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs
 
 bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
     if (chunk_log2 != 14 || W > (uint32_t)kMaxFusedPayloads) return false;
-    // packed accumulators: 8-bit lanes for 2- and 4-bit payloads, 16-bit lanes for 8-bit
+    // packed accumulators: 8-bit lanes for 2- and 4-bit payloads, 16-bit lanes for 8-bit.
+    // The kernel stores the sums at the width of its lanes, so the shape qualifies only
+    // when that is also the width the caller's buffer has (one worker of 8-bit payloads
+    // has one-byte sums and takes the unfused path).
     const uint32_t top = W * ((1u << bits) - 1u);
-    return bits == 8 ? top <= 65535u : top <= 255u;
+    return bits == 8 ? (top > 255u && top <= 65535u) : top <= 255u;
 }
 
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,

@@ -74,7 +74,7 @@ struct EncodeAllArgs {
 // Words per chunk in `slots`: one for every wave of every worker's workgroup.
 uint32_t encode_all_slot_words(uint32_t W);
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs,
-                                 uint32_t chunk_log2);
+                                 uint32_t chunk_log2, bool bf16, uint32_t bits);
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
                                    uint32_t bits, hipStream_t stream);
 hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream);

@@ -27,6 +27,7 @@ def _rand(n, dtype, seed, scale=1e-3):
     (14, 4, 8, torch.float32, 9), (14, 8, 3, torch.float32, 4), (14, 2, 1, torch.float32, 3),
     (14, 4, 17, torch.bfloat16, 6), (14, 4, 18, torch.bfloat16, 3), (14, 4, 64, torch.bfloat16, 2),
     (14, 2, 40, torch.float32, 2), (14, 8, 33, torch.bfloat16, 2),
+    (14, 8, 1, torch.bfloat16, 3), (14, 8, 1, torch.float32, 2), (14, 8, 2, torch.bfloat16, 2),
     (10, 4, 4, torch.float32, 40), (12, 8, 5, torch.bfloat16, 9), (3, 2, 3, torch.float32, 1000),
 ])
 def test_fused_path_matches_oracle_and_unfused(l, bits, W, dtype, chunks):
@@ -81,6 +82,9 @@ def test_is_fused_predicate():
     assert thc.thc_aggregate_decode_is_fused(17, 14, 4)
     assert not thc.thc_aggregate_decode_is_fused(18, 14, 4)
     assert thc.thc_aggregate_decode_is_fused(8, 14, 8)
+    # one worker of 8-bit payloads has one-byte sums; the fused kernel stores 16-bit lanes
+    assert thc.thc_sum_bytes(1, 8) == 1 and not thc.thc_aggregate_decode_is_fused(1, 14, 8)
+    assert thc.thc_sum_bytes(2, 8) == 2 and thc.thc_aggregate_decode_is_fused(2, 14, 8)
     assert not thc.thc_aggregate_decode_is_fused(8, 10, 4)
     assert thc.thc_aggregate_decode_is_fused(64, 14, 2)
     assert not thc.thc_aggregate_decode_is_fused(65, 14, 2)
