@@ -183,6 +183,25 @@ int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, u
                            uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                            float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
 
+/* thc_encode_all for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Not a
+ * step of the paper: the same computation as thc_encode_all, with the workspace taken from
+ * a fixed array of THC_STATIC_SCRATCH_BYTES bytes that the library holds in device memory
+ * on every GPU it runs on, for as long as the process lives.  The call allocates and frees
+ * nothing (no hipMalloc / hipFree, no allocating library routine) and never synchronises.
+ *   grads, payloads, scale   as for thc_encode_all
+ *   timed_out   NULL, or one 4-byte aligned device word that receives 0 after a good run
+ *               and 1 if a bounded wait between workgroups expired (payloads then invalid)
+ * THC_ERR_SIZE if thc_encode_all_workspace_bytes(W, n, chunk_log2) exceeds
+ * THC_STATIC_SCRATCH_BYTES (at W = 8 that is 8065 chunks of 2^14 coordinates).  All calls on
+ * one GPU share that GPU's array, which keeps the previous call's contents; the call
+ * clears the words it uses with a fill kernel first.  Calls that overlap in time on one
+ * GPU (two streams, two host threads) race on the array: issue them on one stream. */
+#define THC_STATIC_SCRATCH_BYTES (2u << 20)
+int thc_encode_all_static(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                          uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                          float* scale, uint32_t* timed_out, void* stream);
+
 /* Upper bound on the polls of one inter-workgroup wait inside thc_encode_all (default
  * 2^22, about seconds).  A tuning and test knob: with a tiny limit the waits expire, the
  * error word is set and every wave still exits. */

@@ -50,6 +50,9 @@ _SIGNATURES = {
                                       ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
                                       ctypes.c_void_p]),
+    "thc_encode_all_static": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                             ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_workspace_clear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]),
     "thc_encode_all_cleared": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
                                       ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, _u8pp,
@@ -295,6 +298,24 @@ def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, st
 def thc_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
     return _encode_all("thc_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
                        workspace, stream)
+
+
+THC_STATIC_SCRATCH_BYTES = 2 << 20
+
+
+def thc_encode_all_static(grads, chunk_log2, seed, bits, payloads, scale, timed_out=None, stream=None):
+    W = len(grads)
+    n = grads[0].numel()
+    for g in grads:
+        _flat(g)
+        if g.numel() != n or g.dtype != grads[0].dtype:
+            raise ValueError("all workers must have gradients of one size and dtype")
+    keep_g, pg = _ptr_array(grads)
+    keep_p, pp = _ptr_array(payloads)
+    _check(lib().thc_encode_all_static(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits, pp,
+                                       _ptr(scale), _ptr(timed_out), _stream(stream)),
+           "thc_encode_all_static")
+    return payloads
 
 
 def thc_workspace_clear(workspace, stream=None):

@@ -2,6 +2,8 @@
 // dispatch to the kernel launchers.  See include/thc.h for the contract.
 #include <math.h>
 
+#include <mutex>
+
 #include "thc_internal.h"
 
 namespace {
@@ -320,6 +322,53 @@ int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, u
                            float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
     return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
                            workspace_bytes, stream, false, true);
+}
+
+// ---- thc_encode_all for callers that cannot allocate ---------------------------------
+// The workspace is a file-scope device array: every GPU the library runs on holds its own
+// copy at its own address until the process ends.  In host code the array's name is only
+// a stand-in for that address; the address is asked for once per device, with that device
+// current, and only the pointer obtained that way is handed to kernels.
+static __device__ __align__(256) uint32_t scratch[THC_STATIC_SCRATCH_BYTES / 4];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t* g_scratch_ptr[kMaxDevices];   // per device, filled on the first call there
+
+int static_scratch(uint32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return THC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return THC_ERR_HIP;
+        g_scratch_ptr[dev] = static_cast<uint32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return THC_OK;
+}
+}  // namespace
+
+int thc_encode_all_static(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n,
+                          uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
+                          float* scale, uint32_t* timed_out, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!aligned(timed_out, 4)) return THC_ERR_ALIGN;
+    if (thc_encode_all_workspace_bytes(W, n, chunk_log2) > (uint64_t)THC_STATIC_SCRATCH_BYTES) return THC_ERR_SIZE;
+    uint32_t* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != THC_OK) return rc;
+    // the array keeps the previous call's contents: this form clears the words it uses first
+    rc = encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, ws,
+                         (uint64_t)THC_STATIC_SCRATCH_BYTES, stream, false, false);
+    if (rc != THC_OK || timed_out == nullptr) return rc;
+    return finish(thc::launch_copy_word(ws, timed_out, static_cast<hipStream_t>(stream)));
 }
 
 int thc_aggregate_decode_is_fused(uint32_t W, uint32_t chunk_log2, uint32_t bits) {

@@ -196,6 +196,8 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* dst, uint64_t
         mid[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
+__global__ void copy_word_kernel(const uint32_t* src, uint32_t* dst) { *dst = *src; }
+
 // ------------------------------------------------------------- aggregate_decode
 // One chunk per work item, persistent grid.  Thread t owns coordinates 32 t .. 32 t + 31
 // (layout L1): 4 * BITS payload bytes (BITS dwords) per worker.
@@ -630,6 +632,11 @@ hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream) 
     const uint64_t blocks = (words / 4u + 255u) / 256u;
     hipLaunchKernelGGL(k14::zero_words_kernel, dim3((uint32_t)(blocks < 1u ? 1u : (blocks > 8192u ? 8192u : blocks))),
                        dim3(256), 0, stream, dst, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stream) {
+    hipLaunchKernelGGL(k14::copy_word_kernel, dim3(1), dim3(1), 0, stream, src, dst);
     return hipGetLastError();
 }
 

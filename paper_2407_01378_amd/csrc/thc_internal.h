@@ -78,6 +78,8 @@ bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& 
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
                                    uint32_t bits, hipStream_t stream);
 hipError_t launch_zero_words(uint32_t* dst, uint64_t words, hipStream_t stream);
+// *dst = *src, one 32-bit word, on the stream (a kernel, so that it can be captured).
+hipError_t launch_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stream);
 
 constexpr int kMaxFusedPayloads = 64;
 struct FusedPayloadPtrs {
