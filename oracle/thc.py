@@ -31,9 +31,11 @@ implemented, independently, by the GPU library):
   R4  Levels: L + 1 = 2^b grid points, index 0 at -s_p and index L at +s_p.
   R5  Rounding: idx = floor(v + u), v = y * inv + L/2 the position in grid units
       (inv = L / (2 s_p)), u uniform in (0,1) built from RBITS random bits, centred:
-      u = (r + 0.5) / 2^RBITS.  In the fp32 mode v + u is ONE fused operation
-      fma(y, inv, L/2 + u) (L/2 + u is exact), the form a GPU evaluates in one
-      instruction; an all-zero chunk has index 0 everywhere.
+      u = (r + 0.5) / 2^RBITS.  The fp32 mode evaluates v + u in the order that keeps
+      it within 1e-6 * max(1, |t|) of the float64 definition for every grid size
+      (see grid_position_plus_noise): fma(y, inv, L/2 + u) for grids of up to 32
+      points (L/2 + u is exact), fma(y + s_p, inv, u) for larger ones; an all-zero
+      chunk has index 0 everywhere.
   R6  Decode returns the estimate of the workers' MEAN gradient.
   R7  All-zero chunk (s_p = 0): every index is 0 and it decodes to exactly 0.
   R8  Padding: zeros up to a multiple of the chunk only.
@@ -232,12 +234,33 @@ def fma32(a, b, c):
     return r
 
 
-def grid_position_plus_noise(y, inv, half_plus_u, dtype):
-    """t = y * inv + (L/2 + u): one fused operation in the fp32 mode, plain arithmetic in
-    the float64 definition."""
-    if dtype == np.float32:
-        return fma32(y, inv, half_plus_u)
-    return y * inv + half_plus_u
+#: Largest grid index for which the fp32 mode forms the position with one fused operation
+#: from y itself; larger grids (8-bit payloads) take the offset y + s first.
+SINGLE_FMA_MAX_LEVELS = 31
+
+
+def grid_position_plus_noise(y, s, inv, L, u, dtype):
+    """t = (position of y on the grid of [-s, s], in grid units) + u.
+
+    float64, the definition:      t = y * inv + L/2 + u.
+    float32, the canonical order, chosen by grid size so that t stays within the band
+    1e-6 * max(1, |t|) of the definition (the band inside which an index may differ):
+
+      L <= 31 (2- and 4-bit grids):   t = fma(y, inv, L/2 + u)   one rounding; L/2 + u is exact.
+          inv = fl(L / (2 s)) carries a relative error of at most 2^-24, which the product
+          turns into an ABSOLUTE error of |y * inv| * 2^-24 <= (L/2) 2^-24 in t, plus the final
+          rounding |t| 2^-24:  (L/2 + |t|) 2^-24 <= (15.5 + |t|) 6e-8 < 1e-6 max(1, |t|).
+      L >= 32 (8-bit grids):          t = fma(fl(y + s), inv, u)  the offset is rounded first.
+          With L = 255 the bound above is 7.6e-6 at the low end of the grid (|t| near 1),
+          outside the band.  Here every error is relative to the offset value itself:
+          |t| (2^-24 + 2^-24 + 2^-24) <= 1.8e-7 |t|.
+
+    tests/test_oracle_quantizer.py measures both claims on 10^7 samples per grid size."""
+    if dtype != np.float32:
+        return y * inv + dtype(L / 2.0) + u
+    if L <= SINGLE_FMA_MAX_LEVELS:
+        return fma32(y, inv, np.float32(L / 2.0) + u)      # L/2 + u: exact short binary fraction
+    return fma32((y + s).astype(np.float32), inv, u)
 
 
 def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
@@ -247,8 +270,9 @@ def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
     each coordinate rounded to one of its two neighbours; readings R4, R5, R7).
 
         inv = L / (s_p + s_p)
-        t   = y * inv + (L/2 + u),  u = (r + 0.5) / 2^RBITS     (position in grid units + noise)
-        idx = min(floor(t), L);     s_p = 0 -> idx = 0
+        t   = y * inv + L/2 + u,  u = (r + 0.5) / 2^RBITS     (position in grid units + noise;
+                                  fp32 evaluation order: grid_position_plus_noise)
+        idx = min(floor(t), L);   s_p = 0 -> idx = 0
 
     `r` (tests only) replaces the generator's RBITS-bit integers, so that every
     value of r can be enumerated by brute force.
@@ -265,8 +289,7 @@ def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
         r = rounding_fields(g0, y.size, worker, seed, rbits)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -rbits)
-    half_plus_u = dtype(L / 2.0) + u                      # exact: L/2 and u are short binary fractions
-    t = grid_position_plus_noise(y, inv, half_plus_u, dtype)
+    t = grid_position_plus_noise(y, s, inv, L, u, dtype)
     idx = np.minimum(np.floor(t), dtype(L)).astype(np.uint16)
     idx[np.broadcast_to(~nz, idx.shape)] = 0
     idx = idx.reshape(-1)

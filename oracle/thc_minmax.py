@@ -66,7 +66,8 @@ def quantize_minmax(y, rng, chunk_log2, worker, seed, bits, dtype=np.float64, g0
         r = T.rounding_fields(g0, y.size, worker, seed)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -T.RBITS)
-    t = T.grid_position_plus_noise(y - lo, inv, u, dtype)
+    d = y - lo                                   # rounded on its own in the fp32 mode
+    t = T.fma32(d, inv, u) if dtype == np.float32 else d * inv + u
     return np.minimum(np.floor(t), dtype(L)).astype(np.uint16).reshape(-1)
 
 

@@ -50,8 +50,8 @@ def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=
     """Reading S1: stochastic rounding onto the 2M+1-point grid of [-s_p, s_p].
 
         inv = 2M / (s_p + s_p)
-        t   = y * inv + (M + u),  u = (r + 0.5) / 2^RBITS   (one fused operation in fp32,
-                                                             same random stream as the exact-sum path)
+        t   = y * inv + M + u,  u = (r + 0.5) / 2^RBITS   (fp32 evaluation order and random
+                                                           stream of the exact-sum path)
         idx = min(floor(t), 2M);  s_p = 0 -> idx = M  (the grid's centre: z = 0)
     """
     c = 1 << chunk_log2
@@ -66,8 +66,10 @@ def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=
         r = T.rounding_fields(g0, y.size, worker, seed)
     r = np.asarray(r).reshape(y.shape)
     u = (r.astype(dtype) + dtype(0.5)) * dtype(2.0 ** -T.RBITS)
-    t = T.grid_position_plus_noise(y, inv, dtype(L / 2.0) + u, dtype)
-    return np.minimum(np.floor(t), dtype(L)).astype(np.uint16).reshape(-1)
+    t = T.grid_position_plus_noise(y, s, inv, L, u, dtype)
+    idx = np.minimum(np.floor(t), dtype(L)).astype(np.uint16)
+    idx[np.broadcast_to(~nz, idx.shape)] = L // 2          # all-zero chunk: the centre, z = 0
+    return idx.reshape(-1)
 
 
 def sat_aggregate(payloads, bits, count=None):

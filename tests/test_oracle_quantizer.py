@@ -311,3 +311,69 @@ def test_fma32_breaks_float64_ties_by_the_discarded_bits():
     assert fma32(a, b, c) == np.float32(1 + 2.0 ** -23)                          # fused: just below -> down
     assert fma32(-a, b, -c) == np.float32(-(1 + 2.0 ** -23))                     # mirrored: e > 0
     assert fma32(a, b, c) == _rn32(Fraction(float(a)) * Fraction(float(b)) + Fraction(float(c)))
+
+
+# ------------------------------------------- fp32 evaluation order against the definition
+def _quantizer_samples(bits, count, seed):
+    """(y, s, r) triples: scales over 2^-120 .. 2^105, y uniform on the range for one half
+    of the samples and crowded into the two lowest and two highest grid cells for the other half
+    (where a relative error in the multiplier shows most), y = +-s included."""
+    rng = np.random.default_rng(1000 * seed + bits)
+    L = (1 << bits) - 1
+    e = rng.integers(-120, 106, size=count)
+    s = (rng.uniform(1.0, 2.0, size=count) * np.exp2(e.astype(np.float64))).astype(np.float32)
+    frac = rng.uniform(-1.0, 1.0, size=count)
+    edge = rng.uniform(0.0, 4.0 / L, size=count // 2)            # within 2 cells of an end
+    frac[: 3 * count // 8] = -1.0 + edge[: 3 * count // 8]       # mostly the low end: there the
+    frac[3 * count // 8: count // 2] = 1.0 - edge[3 * count // 8:]   # band is narrowest
+    frac[-2000:-1000], frac[-1000:] = 1.0, -1.0
+    y = np.clip((s.astype(np.float64) * frac).astype(np.float32), -s, s)
+    r = rng.integers(0, 1 << RBITS, size=count)
+    return y, s, r
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_fp32_evaluation_orders_against_the_float64_definition(bits):
+    """The canonical fp32 order may move an index only where the definition's pre-rounding
+    value t lies within 1e-6 * max(1, |t|) of an integer (the band inside which an index is
+    allowed to differ).  Measured on 4 x 10^6 triples per grid size (1.2 x 10^7 in all), for
+    three evaluation orders written out here in NumPy float32:
+      three   ((y + s) * inv) + u, three roundings (add, multiply, add)
+      single  fma(y, inv, L/2 + u)
+      offset  fma(y + s, inv, u)
+    The canonical order (single for L <= 31, offset above) must stay inside the band, and
+    `three` must agree with it outside the band; `single` on the 256-point grid does NOT
+    stay inside (why the canonical order switches there) - the sample has to show that too,
+    otherwise it would not be able to tell the orders apart."""
+    from oracle.thc import SINGLE_FMA_MAX_LEVELS, fma32
+    L = (1 << bits) - 1
+    count = 4_000_000
+    y, s, r = _quantizer_samples(bits, count, 7)
+    f32 = np.float32
+    u = (r.astype(f32) + f32(0.5)) * f32(2.0 ** -RBITS)
+    inv = f32(L) / (s + s)
+    assert inv.dtype == f32
+    floor_idx = lambda t: np.minimum(np.floor(t), f32(L)).astype(np.int64)
+    three = floor_idx(((y + s) * inv) + u)
+    single = floor_idx(fma32(y, inv, f32(L / 2.0) + u))
+    offset = floor_idx(fma32(y + s, inv, u))
+    canonical = quantize(y, s, 0, 0, 0, bits, dtype=f32, r=r).astype(np.int64)      # chunks of one
+    assert np.array_equal(canonical, single if L <= SINGLE_FMA_MAX_LEVELS else offset)
+    y64, s64 = y.astype(np.float64), s.astype(np.float64)
+    t64 = y64 * (L / (s64 + s64)) + L / 2.0 + (r + 0.5) / (1 << RBITS)
+    definition = np.minimum(np.floor(t64), L).astype(np.int64)
+    assert np.array_equal(definition, quantize(y64, s64, 0, 0, 0, bits, dtype=np.float64, r=r))
+    outside = np.abs(t64 - np.rint(t64)) > 1e-6 * np.maximum(1.0, np.abs(t64))
+    report = {}
+    for name, idx in (("three", three), ("single", single), ("offset", offset)):
+        moved = idx != definition
+        assert (np.abs(idx - definition) <= 1).all()
+        report[name] = (int(moved.sum()), int((moved & outside).sum()))
+    print(f"bits {bits}: indices moved (in all, outside the band) of {count}: {report}")
+    assert report["three"][1] == 0 and report["offset"][1] == 0
+    assert ((canonical != definition) & outside).sum() == 0
+    assert ((three != canonical) & outside).sum() == 0
+    if L <= SINGLE_FMA_MAX_LEVELS:
+        assert report["single"][1] == 0
+    else:
+        assert report["single"][1] > 0
