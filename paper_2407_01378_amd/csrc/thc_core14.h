@@ -377,9 +377,10 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 //   CLAMP    false only for the symmetric grid with s the largest |y| of the chunk: then
 //            0 < t < L + 1 for every coordinate (|y * inv| <= L/2 (1 + 2^-24) and
 //            2^-9 <= c - L/2 <= 255.5 / 256), so the minimum with L never binds
-//   FOLD     y = v * 2^-7 is not formed; mul already carries the factor 2^-7.  Exact as long
-//            as the power of two moves nothing into the subnormal range: the callers fold
-//            only for 2^-100 <= s <= 2^100.
+//   FOLD     y = v * 2^-7 is not formed; mul already carries the factor 2^-7 and sub is given
+//            in v's units (v - 2^7 lo = 2^7 (y - lo), rounded alike).  Exact as long
+//            as the power of two moves nothing into the subnormal range or past the largest
+//            float: the callers fold only for 2^-100 <= s <= 2^100.
 template <int BITS, bool CLAMP, bool FOLD, bool RANGED>
 __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float sub, float mul, float base,
                                               uint32_t L, uint64_t g, uint32_t worker, uint32_t key0,
@@ -418,21 +419,26 @@ __device__ __forceinline__ void store_packed(const uint32_t (&pk)[BITS], uint8_t
 }
 
 // Symmetric grid.  An all-zero chunk (s = 0) gets index 0 everywhere on the 2^BITS-point
-// grid (L odd) and the centre index L/2 on the signed grid (L even).
+// grid (L odd) and the centre index L/2 on the signed grid (L even).  Evaluation order by
+// grid size (kSingleFmaMaxLevels): 2- and 4-bit grids t = fma(y, inv, L/2 + u); 8-bit
+// grids t = fma(y + s, inv, u), which is the ranged form with sub = -s.  The clamp stays
+// dead there too when s is the chunk's largest magnitude: 0 <= y + s <= 2 s, and
+// 2 s * inv <= L (1 + 2^-24), so t < L + 255.5/256 + L 2^-24 < L + 1.
 template <int BITS, bool CLAMP>
 __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s, uint32_t L, uint64_t g0,
                                                uint32_t worker, uint32_t key0, uint32_t key1,
                                                uint8_t* payload, uint32_t t) {
+    constexpr bool kOffset = ((1u << BITS) - 2u) > kSingleFmaMaxLevels;   // both grids of this width
     const float two = s + s;
     const float inv = two != 0.0f ? (float)L / two : 0.0f;
-    const float half = (two != 0.0f || (L & 1u) == 0u) ? 0.5f * (float)L : 0.0f;
-    const float base = half + 0x1p-9f;   // exact
+    const float centre = (two != 0.0f ? !kOffset : (L & 1u) == 0u) ? 0.5f * (float)L : 0.0f;
+    const float base = centre + 0x1p-9f;   // exact
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
     if (s >= 0x1p-100f && s <= 0x1p100f)   // the same for every thread of the workgroup
-        quantize_pack<BITS, CLAMP, true, false>(v, 0.0f, inv * kInvSqrtC, base, L, g, worker, key0, key1, pk);
+        quantize_pack<BITS, CLAMP, true, kOffset>(v, -128.0f * s, inv * kInvSqrtC, base, L, g, worker, key0, key1, pk);
     else
-        quantize_pack<BITS, CLAMP, false, false>(v, 0.0f, inv, base, L, g, worker, key0, key1, pk);
+        quantize_pack<BITS, CLAMP, false, kOffset>(v, -s, inv, base, L, g, worker, key0, key1, pk);
     store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 

@@ -19,6 +19,12 @@ constexpr uint32_t kTagSign = 0x5349474Eu;   // fourth counter word of the sign 
 constexpr uint32_t kTagRound = 0x524F554Eu;  // fourth counter word of the rounding stream
 constexpr int kRoundingBits = 8;             // random bits per coordinate
 constexpr int kCoordsPerRoundBlock = 128 / kRoundingBits;  // 16
+// fp32 evaluation order of the quantizer, by the grid's largest index L.  Up to here the
+// position plus noise is t = fma(y, inv, L/2 + u); above (8-bit payloads) the offset is
+// rounded first, t = fma(y + s, inv, u): inv = L / (2 s) carries a relative rounding error
+// of 2^-24, which the first form turns into an absolute error of up to (L/2) 2^-24 in t -
+// 7.6e-6 for L = 255, more than the 1e-6 max(1, |t|) an index is allowed to depend on.
+constexpr uint32_t kSingleFmaMaxLevels = 31;
 
 struct u32x4 {
     uint32_t w[4];

@@ -171,7 +171,9 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
     const float two = s + s;
     const float Lf = (float)levels;
     const float inv = two != 0.0f ? Lf / two : 0.0f;
-    const float half = two != 0.0f ? 0.5f * Lf : 0.0f;   // an all-zero vector gets index 0
+    const bool single = levels <= kSingleFmaMaxLevels;   // evaluation order by grid size
+    const float half = (single && two != 0.0f) ? 0.5f * Lf : 0.0f;   // an all-zero vector gets index 0
+    const float off = single ? 0.0f : s;
     const u32x4 rb = round_block(blk, worker, key0, key1);
     uint32_t pk[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -183,7 +185,8 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
             const int j = 4 * k + e;
             const uint32_t r = (rb.w[k] >> (8 * e)) & 0xFFu;
             const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
-            const float tt = __builtin_fmaf(yv[e], inv, half + u);   // y * inv + (L/2 + u), one rounding
+            // small grids: fma(y, inv, L/2 + u); large grids: fma(y + s, inv, u)
+            const float tt = __builtin_fmaf(yv[e] + off, inv, half + u);
             const uint32_t idx = (uint32_t)fminf(floorf(tt), Lf);
             const int bit = j * BITS;
             pk[bit >> 5] |= idx << (bit & 31);

@@ -30,6 +30,37 @@ def run_path_fused(xs, l, seed, bits, keep_sums=True):
     return dict(scale=scale, payloads=payloads, sums=sums if keep_sums else None, out=out)
 
 
+def run_path_timed(xs, l, seed, bits, reuse=None):
+    """The form bench.py times: a workspace cleared ONCE (thc_workspace_clear), then
+    thc_encode_all_cleared + thc_aggregate_decode with sums = NULL.  `reuse` is a workspace
+    left by an earlier call of this function (it must have come back clear)."""
+    W = len(xs)
+    n = xs[0].numel()
+    dev = xs[0].device
+    P = thc.thc_num_chunks(n, l)
+    scale = torch.full((P,), -1.0, dtype=torch.float32, device=dev)
+    nb = thc.thc_payload_bytes(n, l, bits)
+    payloads = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=dev) for _ in range(W)]
+    need = thc.thc_encode_all_workspace_bytes(W, n, l)
+    if reuse is None:
+        ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev)
+        thc.thc_workspace_clear(ws)
+    else:
+        ws = reuse
+        assert ws.numel() >= need
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=dev)
+    sums = None                       # the fused decoder never stores them; the fallback needs them
+    if not thc.thc_aggregate_decode_is_fused(W, l, bits):
+        sb = thc.thc_sum_bytes(W, bits)
+        sums = torch.full((P << l,), 77, dtype=torch.uint8 if sb == 1 else torch.int16, device=dev)
+    thc.thc_encode_all_cleared(xs, l, seed, bits, payloads, scale, ws)
+    thc.thc_aggregate_decode(payloads, scale, n, l, seed, bits, sums, out)
+    torch.cuda.synchronize()
+    assert not thc.thc_encode_all_timed_out(ws), "a wait inside thc_encode_all_cleared expired"
+    assert int(ws.count_nonzero()) == 0, "the workspace did not come back clear"
+    return dict(scale=scale, payloads=payloads, sums=sums, out=out, workspace=ws)
+
+
 def run_path(xs, l, seed, bits, own_scale=False):
     """absmax -> scale_reduce -> encode x W -> aggregate -> decode on the GPU.
     xs: list of W device tensors (fp32 or bf16).  Returns device tensors."""

@@ -109,6 +109,33 @@ def test_sat_path_matches_oracle_fused_and_unfused(l, bits, W, dtype, chunks):
         assert torch.equal(lean["out"], plain["out"]) and lean["overflow"] == plain["overflow"]
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_sat_all_zero_chunks_get_the_centre_index(bits, dtype):
+    """A chunk that is zero for every worker has scale 0; on the signed grid its index is
+    the centre M (z = 0), through thc_sat_encode and through thc_sat_encode_all alike, and it
+    decodes to exactly 0.  Chunks zero for one worker only go through the ordinary rule."""
+    l, c, W = 14, 1 << 14, 5
+    n = 4 * c + 9
+    M = thc.thc_sat_max(bits)
+    xs = [_rand(n, dtype, 300 + w) for w in range(W)]
+    for x in xs:
+        x[:c] = 0
+        x[2 * c:3 * c] = 0
+    xs[1][c:2 * c] = 0
+    for fused in (False, True):
+        print(f"sat zero chunks bits={bits} dtype={dtype} fused={fused}", flush=True)
+        got = run_sat(xs, l, 9, bits, fused_encode=fused, fused_decode=fused)
+        check_sat(xs, got, l, 9, bits)
+        assert got["scale"][0].item() == 0 and got["scale"][2].item() == 0
+        per = 8 // bits
+        centre = sum(M << (bits * j) for j in range(per))           # a byte full of index M
+        for p in got["payloads"]:
+            assert (p[: c * bits // 8] == centre).all()
+            assert (p[2 * c * bits // 8: 3 * c * bits // 8] == centre).all()
+        assert (got["out"][:c] == 0).all() and (got["out"][2 * c:3 * c] == 0).all()
+
+
 def test_sat_without_clipping_equals_exact_sum_decode():
     """Small, cancelling values: no Sat step clips, so the saturated aggregate is the
     exact integer sum and the decoded mean equals the exact-sum decode of the same

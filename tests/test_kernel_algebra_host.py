@@ -1,10 +1,12 @@
 """Two facts about fp32 arithmetic that the tuned kernels rely on, checked here with the
 oracle's exact float32 fused multiply-add (tests only; the kernels share no code with it):
 
-1. With |y| <= s the rounding rule's t = fma(y, inv, L/2 + u) satisfies 0 < t < L + 1, so
-   the clamp min(floor(t), L) is dead whenever s is the chunk's own largest magnitude.
+1. With |y| <= s the rounding rule's t = fma(y, inv, L/2 + u) (grids of up to 32 points)
+   or t = fma(y + s, inv, u) (larger grids) satisfies 0 <= t < L + 1, so the clamp
+   min(floor(t), L) is dead whenever s is at least the chunk's own largest magnitude.
 2. For 2^-100 <= s <= 2^100 the normalisation y = v * 2^-7 can be folded into the
-   multiplier: fma(v * 2^-7, inv, c) == fma(v, 2^-7 inv, c) bit for bit.
+   multiplier: fma(v * 2^-7, inv, c) == fma(v, 2^-7 inv, c) bit for bit, and likewise
+   fma(v * 2^-7 + s, inv, u) == fma(v + 128 s, 2^-7 inv, u).
 """
 import numpy as np
 import pytest
@@ -30,12 +32,14 @@ def test_clamp_is_dead_when_scale_is_the_largest_magnitude(bits):
     c_max = half + F(255.5 / 256.0)
     c_min = half + F(0.5 / 256.0)
     # t is monotone in y: the extremes are y = +s with the largest noise, y = -s with the smallest
+    offset = L > 31
+    u_max, u_min = F(255.5 / 256.0), F(0.5 / 256.0)
     for y in (s, np.nextafter(s, F(0)), s * F(0.999)):
-        t = fma32(y, inv, c_max)
+        t = fma32(y + s, inv, u_max) if offset else fma32(y, inv, c_max)
         assert t.dtype == F
         assert (np.floor(t) <= L).all()
     for y in (-s, -np.nextafter(s, F(0))):
-        t = fma32(y, inv, c_min)
+        t = fma32(y + s, inv, u_min) if offset else fma32(y, inv, c_min)
         assert (t > 0).all()
 
 
@@ -57,6 +61,11 @@ def test_folded_normalisation_is_bit_exact_inside_its_range(bits):
     c = F(0.5) * L + ((rng.integers(0, 256, size=count).astype(F) + F(0.5)) * F(2.0 ** -8))
     plain = fma32(v * F(0.0078125), inv, c)
     folded = fma32(v, inv * F(0.0078125), c)
+    assert np.array_equal(plain.view(np.uint32), folded.view(np.uint32))
+    # the offset form of the large grids: v * 2^-7 + s against (v + 128 s) * 2^-7
+    u = c - F(0.5) * L
+    plain = fma32(v * F(0.0078125) + s, inv, u)
+    folded = fma32(v - F(-128.0) * s, inv * F(0.0078125), u)
     assert np.array_equal(plain.view(np.uint32), folded.view(np.uint32))
     # tiny v (y underflows to subnormal or zero) changes nothing either
     v_tiny = (rng.uniform(-1, 1, size=count) * 2.0 ** -140).astype(F)
