@@ -223,9 +223,10 @@ __device__ __forceinline__ void x3e_store(Shared& sh, const float (&v)[kRegs], u
     for (int r = 0; r < kRegs; ++r) sh.xb[lay14::x3e_store(wave, lane, r)] = v[r];
 }
 __device__ __forceinline__ void x3e_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    const float4* units = reinterpret_cast<const float4*>(sh.xb);   // unit-indexed: provably 16-byte aligned
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        const float4 f = *reinterpret_cast<const float4*>(sh.xb + lay14::x3e_load(wave, lane, q));
+        const float4 f = units[lay14::x3e_load_unit(wave, lane, q)];
         v[4 * q] = f.x;
         v[4 * q + 1] = f.y;
         v[4 * q + 2] = f.z;
@@ -237,9 +238,10 @@ __device__ __forceinline__ void x3d_store(Shared& sh, const float (&v)[kRegs], u
     for (int r = 0; r < kRegs; ++r) sh.xb[lay14::x3d_store(wave, lane, r)] = v[r];
 }
 __device__ __forceinline__ void x3d_load(const Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {
+    const float4* units = reinterpret_cast<const float4*>(sh.xb);   // unit-indexed: provably 16-byte aligned
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
-        const float4 f = *reinterpret_cast<const float4*>(sh.xb + lay14::x3d_load(wave, lane, h));
+        const float4 f = units[lay14::x3d_load_unit(wave, lane, h)];
         v[4 * h] = f.x;
         v[4 * h + 1] = f.y;
         v[4 * h + 2] = f.z;
@@ -381,12 +383,36 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 //            in v's units (v - 2^7 lo = 2^7 (y - lo), rounded alike).  Exact as long
 //            as the power of two moves nothing into the subnormal range or past the largest
 //            float: the callers fold only for 2^-100 <= s <= 2^100.
+// Packing: float -> integer conversion writes its result straight into one byte of a
+// 32-bit register (sub-dword destination select), so 32 conversions leave 8 registers of 4
+// index bytes each and no shift-or per coordinate; register m holds, in byte i, the index
+// of coordinate (32 / BITS) * (m / kSub) ... chosen so that the payload word is
+//     8 bits:  register d itself                         (bytes = coordinates 4d .. 4d+3)
+//     4 bits:  A_d | B_d << 4                            (A: even, B: odd coordinates of 8d .. 8d+7)
+//     2 bits:  R_d0 | R_d1 << 2 | R_d2 << 4 | R_d3 << 6  (R_dm byte i = coordinate 16d + 4i + m)
+template <int BYTE, bool FIRST>
+__device__ __forceinline__ void cvt_into_byte(uint32_t& acc, float tt) {
+    static_assert(BYTE >= 0 && BYTE < 4, "byte index");
+    if constexpr (FIRST) {   // writes the byte, zeroes the rest of the register
+        if constexpr (BYTE == 0) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD" : "=v"(acc) : "v"(tt));
+        if constexpr (BYTE == 1) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PAD src0_sel:DWORD" : "=v"(acc) : "v"(tt));
+        if constexpr (BYTE == 2) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_2 dst_unused:UNUSED_PAD src0_sel:DWORD" : "=v"(acc) : "v"(tt));
+        if constexpr (BYTE == 3) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_3 dst_unused:UNUSED_PAD src0_sel:DWORD" : "=v"(acc) : "v"(tt));
+    } else {                 // writes the byte, keeps the rest
+        if constexpr (BYTE == 0) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD" : "+v"(acc) : "v"(tt));
+        if constexpr (BYTE == 1) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD" : "+v"(acc) : "v"(tt));
+        if constexpr (BYTE == 2) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD" : "+v"(acc) : "v"(tt));
+        if constexpr (BYTE == 3) asm("v_cvt_u32_f32_sdwa %0, %1 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD" : "+v"(acc) : "v"(tt));
+    }
+}
+
 template <int BITS, bool CLAMP, bool FOLD, bool RANGED>
 __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float sub, float mul, float base,
                                               uint32_t L, uint64_t g, uint32_t worker, uint32_t key0,
                                               uint32_t key1, uint32_t (&pk)[BITS]) {
-#pragma unroll
-    for (int i = 0; i < BITS; ++i) pk[i] = 0u;
+    constexpr int kSub = 8 / BITS;        // coordinates per payload byte: 1, 2, 4
+    uint32_t by[8];                       // index bytes; by[m] serves payload word m / kSub
+    const float Lf = (float)L;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const u32x4 rb = round_block((g >> 4) + half, worker, key0, key1);
@@ -397,12 +423,27 @@ __device__ __forceinline__ void quantize_pack(const float (&v)[kRegs], float sub
             if (RANGED) y = y - sub;
             const uint32_t rnd = (rb.w[e >> 2] >> (8 * (e & 3))) & 0xFFu;
             const float c = __builtin_fmaf((float)rnd, 0x1p-8f, base);
-            const float tt = __builtin_fmaf(y, mul, c);
-            uint32_t q = (uint32_t)tt;                    // tt >= 0: truncation = floor
-            if (CLAMP) q = q < L ? q : L;
-            const int bit = r * BITS;
-            pk[bit >> 5] |= q << (bit & 31);
+            float tt = __builtin_fmaf(y, mul, c);            // tt >= 0: truncation = floor
+            if (CLAMP) tt = fminf(tt, Lf);                   // floor(min(t, L)) = min(floor(t), L)
+            // coordinate r sits in payload word d = r / (32 / BITS), at slot j = r % (32 / BITS);
+            // its index goes to byte j / kSub of register kSub * d + j % kSub
+            constexpr int kPerWord = 32 / BITS;
+            const int d = r / kPerWord, j = r % kPerWord;
+            const int m = kSub * d + j % kSub, byte = j / kSub;
+            switch (byte) {
+                case 0: cvt_into_byte<0, true>(by[m], tt); break;
+                case 1: cvt_into_byte<1, false>(by[m], tt); break;
+                case 2: cvt_into_byte<2, false>(by[m], tt); break;
+                default: cvt_into_byte<3, false>(by[m], tt); break;
+            }
         }
+    }
+#pragma unroll
+    for (int d = 0; d < BITS; ++d) {
+        if constexpr (BITS == 8) pk[d] = by[d];
+        if constexpr (BITS == 4) pk[d] = by[2 * d] | (by[2 * d + 1] << 4);
+        if constexpr (BITS == 2)
+            pk[d] = by[4 * d] | (by[4 * d + 1] << 2) | (by[4 * d + 2] << 4) | (by[4 * d + 3] << 6);
     }
 }
 

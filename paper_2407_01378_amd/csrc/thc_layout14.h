@@ -15,9 +15,12 @@
 // flight (LDS holds one 64 KB chunk per workgroup), so that one chunk's LDS exchanges and
 // barriers overlap the other's vector arithmetic.
 //
-// Every map is a bijection of the index bits onto dword addresses such that the 128-bit
-// side of an exchange has 8 consecutive lanes on 8 distinct 16-byte bank groups and the
-// 32-bit side has 32 consecutive lanes on 32 distinct banks.  XOR terms involve at most
+// Every map is a bijection of the index bits onto dword addresses such that, as measured on
+// gfx950: 32-bit accesses put the 32 lanes of each half wave on 32 distinct banks (dword
+// address mod 32); 128-bit stores put 8 consecutive lanes on 8 distinct 16-byte columns of
+// a 128-byte row; 128-bit loads (which run at twice the bandwidth of 32-bit ones) put the
+// lanes of each half wave on all 16 columns of a 256-byte row, lane bits 0 and 1 among the
+// column bits.  XOR terms involve at most
 // three register bits, so a thread needs at most 8 base addresses per exchange and every
 // access is base + immediate offset.
 #pragma once
@@ -36,13 +39,15 @@ namespace lay14 {
 // ---- E0: raw input units (16 bytes each) from load order to L1 order -------------------
 // Load order: thread t (0..511), round j holds unit 512 j + t.  L1 order: thread T needs
 // units per*T .. per*T + per-1 (per = 4 for bf16: 8 coordinates a unit; 8 for fp32: 4 a unit).
-// Unit u is kept at unit address u ^ swz(u): bf16 swz = (u >> 3) & 3, fp32 swz = (u >> 3) & 7.
+// Unit u is kept at unit address u ^ swz(u): bf16 swz = (u >> 4) & 3, fp32 swz = (u >> 4) & 7
+// (a half wave of readers then covers all 16 columns of a 256-byte row: columns
+// 4 (T & 3) + (k ^ (T >> 2 & 3)) for bf16, 8 (T & 1) + (k ^ (T >> 1 & 7)) for fp32).
 THC_HD uint32_t e0_store_unit(uint32_t t, uint32_t j, uint32_t per) {
-    const uint32_t swz = per == 4 ? ((t >> 3) & 3u) : ((t >> 3) & 7u);
+    const uint32_t swz = per == 4 ? ((t >> 4) & 3u) : ((t >> 4) & 7u);
     return j * 512u + (t ^ swz);
 }
 THC_HD uint32_t e0_load_unit(uint32_t T, uint32_t k, uint32_t per) {
-    const uint32_t swz = per == 4 ? ((T >> 1) & 3u) : (T & 7u);
+    const uint32_t swz = per == 4 ? ((T >> 2) & 3u) : ((T >> 1) & 7u);
     return per * T + (k ^ swz);
 }
 
@@ -70,18 +75,25 @@ THC_HD uint32_t x2_load(uint32_t wave, uint32_t lane, uint32_t rho) {  // rho = 
 }
 
 // ---- X3e: L3 -> L4e (= L1), whole buffer ---------------------------------------------------
-// a0 a1 = i0 i1 | a2 a3 = i5 i6 | a4 = i2^i7 | a5 a6 = i3 i4 | a7 a8 = i7 i8 | a9..a13 = i9..i13
+// a0 a1 = i0 i1 | a2 a3 = i5 i6 | a4 = i2^i7 | a5 = i8 | a6 = i4 | a7 = i7 | a8 = i3 | a9..a13 = i9..i13
+// The 128-bit reads of a wave are served half a wave (32 lanes, 512 bytes) at a time over a
+// 256-byte row of banks: the four address bits a2..a5 that select the 16-byte column must
+// take 16 values across those lanes (here i5, i6, i7, i8 = lane bits 0..3), or the read
+// takes twice as long.
 // writer (L3): 32-bit stores of register rho
 THC_HD uint32_t x3e_store(uint32_t wave, uint32_t lane, uint32_t rho) {
     const uint32_t i5i6 = lane & 3u, i0i1 = (lane >> 2) & 3u, i2 = (lane >> 4) & 1u, i3 = (lane >> 5) & 1u;
     const uint32_t i4 = wave & 1u, i7 = (wave >> 1) & 1u, i8 = (wave >> 2) & 1u;
-    return (i0i1 | (i5i6 << 2) | ((i2 ^ i7) << 4) | (i3 << 5) | (i4 << 6) | (i7 << 7) | (i8 << 8)) + (rho << 9);
+    return (i0i1 | (i5i6 << 2) | ((i2 ^ i7) << 4) | (i8 << 5) | (i4 << 6) | (i7 << 7) | (i3 << 8)) + (rho << 9);
 }
-// reader (L4e): wave = i11..i13, lane = i5..i10, loads registers 4q..4q+3 (q = i2..i4) as 128 bits
-THC_HD uint32_t x3e_load(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..7
+// reader (L4e): wave = i11..i13, lane = i5..i10, loads registers 4q..4q+3 (q = i2..i4) as 128 bits;
+// returns the index of the 16-byte unit
+THC_HD uint32_t x3e_load_unit(uint32_t wave, uint32_t lane, uint32_t q) {  // q = 0..7
     const uint32_t i5i6 = lane & 3u, i7 = (lane >> 2) & 1u, i8 = (lane >> 3) & 1u, i9i10 = lane >> 4;
-    return (i5i6 << 2) | (((q & 1u) ^ i7) << 4) | ((q >> 1) << 5) | (i7 << 7) | (i8 << 8) | (i9i10 << 9) | (wave << 11);
+    const uint32_t i2 = q & 1u, i3 = (q >> 1) & 1u, i4 = q >> 2;
+    return i5i6 | ((i2 ^ i7) << 2) | (i8 << 3) | (i4 << 4) | (i7 << 5) | (i3 << 6) | (i9i10 << 7) | (wave << 9);
 }
+THC_HD uint32_t x3e_load(uint32_t wave, uint32_t lane, uint32_t q) { return x3e_load_unit(wave, lane, q) << 2; }
 
 // ---- X3d: L3 -> L4d, whole buffer ----------------------------------------------------------
 // a0 a1 = i0 i1 | a2 = i2 | a3 = i3^i5 | a4 = i4^i6 | a5..a8 = i5..i8 | a9..a13 = i9..i13
@@ -91,14 +103,16 @@ THC_HD uint32_t x3d_store(uint32_t wave, uint32_t lane, uint32_t rho) {
     const uint32_t i4 = wave & 1u, i7i8 = wave >> 1;
     return (i0i1 | (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7i8 << 7)) + (rho << 9);
 }
-// reader (L4d): wave = i8..i10, lane = i2..i7, loads registers (i0,i1) of group h = (i11..i13) as 128 bits
-THC_HD uint32_t x3d_load(uint32_t wave, uint32_t lane, uint32_t h) {  // h = 0..7
+// reader (L4d): wave = i8..i10, lane = i2..i7, loads registers (i0,i1) of group h = (i11..i13) as 128 bits;
+// returns the index of the 16-byte unit (column bits a2..a5 = i2, i3^i5, i4^i6, i5: lane bits 0..3)
+THC_HD uint32_t x3d_load_unit(uint32_t wave, uint32_t lane, uint32_t h) {  // h = 0..7
     const uint32_t i2 = lane & 1u, i3 = (lane >> 1) & 1u, i4 = (lane >> 2) & 1u, i5 = (lane >> 3) & 1u,
                    i6 = (lane >> 4) & 1u, i7 = (lane >> 5) & 1u;
     const uint32_t i8 = wave & 1u, i9i10 = wave >> 1;
-    return (i2 << 2) | ((i3 ^ i5) << 3) | ((i4 ^ i6) << 4) | (i5 << 5) | (i6 << 6) | (i7 << 7) | (i8 << 8) |
-           (i9i10 << 9) | (h << 11);
+    return i2 | ((i3 ^ i5) << 1) | ((i4 ^ i6) << 2) | (i5 << 3) | (i6 << 4) | (i7 << 5) | (i8 << 6) |
+           (i9i10 << 7) | (h << 9);
 }
+THC_HD uint32_t x3d_load(uint32_t wave, uint32_t lane, uint32_t h) { return x3d_load_unit(wave, lane, h) << 2; }
 
 }  // namespace lay14
 }  // namespace thc

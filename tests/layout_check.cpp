@@ -1,7 +1,18 @@
 // Host check of the LDS address maps of the chunk-2^14 kernels: for every exchange, each
-// coordinate is written and read at the same address, the map is a bijection, the 128-bit
-// side puts 8 consecutive lanes on 8 distinct 16-byte bank groups and the 32-bit side puts
-// 32 consecutive lanes on 32 distinct banks.  Compiled and run by tests/test_layout_host.py.
+// coordinate is written and read at the same address, the map is a bijection, and every
+// access pattern is free of bank conflicts under the model fitted to timings of
+// ds_read / ds_write instructions on gfx950 (bit permutations of the lane index as
+// address, 16 waves per compute unit in flight):
+//   32-bit loads and stores   the 32 lanes of a half wave on 32 distinct banks, bank =
+//                             dword address mod 32 (2.2 / 4.1 clocks per instruction, twice
+//                             that with lanes l and l + 32 swapped into one half);
+//   128-bit stores            8 consecutive lanes on the 8 distinct 16-byte columns of a
+//                             128-byte row (13.4 clocks; 16 to 32 otherwise);
+//   128-bit loads             run at twice the bandwidth (4.5 clocks for 1 KB): the 32
+//                             lanes of a half wave must cover all 16 columns of a 256-byte
+//                             row, and the 4 lanes of a quad must sit on 4 different columns
+//                             (8 clocks if either fails, 16 if both do).
+// Compiled and run by tests/test_layout_host.py.
 #include <cstdio>
 #include <set>
 #include <vector>
@@ -28,7 +39,7 @@ static Pos L3(uint32_t i) {
 static Pos L4d(uint32_t i) { return {bits(i, 8, 3), bits(i, 2, 6), bits(i, 0, 2) | (bits(i, 11, 3) << 2)}; }
 
 template <typename F>
-static void conflict_128(const char* what, F addr_of_lane) {   // F(lane) -> dword address of a 16-byte access
+static void conflict_128(const char* what, F addr_of_lane) {   // stores; F(lane) -> dword address of a 16-byte access
     for (int g = 0; g < 64; g += 8) {
         std::set<uint32_t> s;
         for (int l = g; l < g + 8; ++l) {
@@ -36,6 +47,22 @@ static void conflict_128(const char* what, F addr_of_lane) {   // F(lane) -> dwo
             s.insert((addr_of_lane(l) >> 2) & 7u);
         }
         CHECK(s.size() == 8, "%s: 128-bit bank-group conflict in lanes %d..%d", what, g, g + 7);
+    }
+}
+template <typename F>
+static void conflict_128_load(const char* what, F addr_of_lane) {   // F(lane) -> dword address of a 16-byte access
+    for (int g = 0; g < 64; g += 32) {
+        std::set<uint32_t> s;
+        for (int l = g; l < g + 32; ++l) {
+            CHECK(addr_of_lane(l) % 4 == 0, "%s: unaligned 128-bit access", what);
+            s.insert((addr_of_lane(l) >> 2) & 15u);
+        }
+        CHECK(s.size() == 16, "%s: half wave %d covers %d of 16 columns", what, g / 32, (int)s.size());
+    }
+    for (int g = 0; g < 64; g += 4) {
+        std::set<uint32_t> s;
+        for (int l = g; l < g + 4; ++l) s.insert((addr_of_lane(l) >> 2) & 15u);
+        CHECK(s.size() == 4, "%s: quad %d shares a column", what, g / 4);
     }
 }
 template <typename F>
@@ -81,8 +108,8 @@ int main() {
         for (uint32_t wv = 0; wv < 8; ++wv) {
             for (uint32_t q = 0; q < 8; ++q) {
                 conflict_128("X2 store", [&](int l) { return x2_store(wv, l, q); });
-                conflict_128("X3e load", [&](int l) { return x3e_load(wv, l, q); });
-                conflict_128("X3d load", [&](int l) { return x3d_load(wv, l, q); });
+                conflict_128_load("X3e load", [&](int l) { return x3e_load(wv, l, q); });
+                conflict_128_load("X3d load", [&](int l) { return x3d_load(wv, l, q); });
             }
             for (uint32_t r = 0; r < 32; ++r) {
                 conflict_32("X2 load", [&](int l) { return x2_load(wv, l, r); });
@@ -108,7 +135,7 @@ int main() {
             for (uint32_t j = 0; j < nunits / 512; ++j)
                 conflict_128("E0 store", [&](int l) { return e0_store_unit(wv * 64 + l, j, per) << 2; });
             for (uint32_t k = 0; k < per; ++k)
-                conflict_128("E0 load", [&](int l) { return e0_load_unit(wv * 64 + l, k, per) << 2; });
+                conflict_128_load("E0 load", [&](int l) { return e0_load_unit(wv * 64 + l, k, per) << 2; });
         }
     }
     printf("layout check: %d problems\n", bad);
