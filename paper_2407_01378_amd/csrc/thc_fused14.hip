@@ -29,7 +29,10 @@ constexpr int kWavesPerSimd = 4;
 constexpr int kFirstPollSleep = 32;
 constexpr int kPollSleep = 8;
 // ------------------------------------------------------------------ encode_all
-template <bool BF16>
+// ODD: bf16 input with an odd number of coordinates.  Its last coordinate shares a dword
+// with nothing, which the range check of a buffer load (done per dword) would cut off, so
+// that shape keeps the element-wise loader; every other shape loads through a descriptor.
+template <bool BF16, bool ODD>
 struct EncodeAllCtx {
     static constexpr int kUnits = BF16 ? 4 : 8;
     static constexpr int kElem = BF16 ? 2 : 4;
@@ -48,12 +51,32 @@ struct EncodeAllCtx {
     uint32_t prev;          // chunk of the workgroup's previous item, kNone before the first
     static constexpr uint32_t kNone = 0xFFFFFFFFu;
 
-    __device__ __forceinline__ void load(uint32_t p) {
-        const uint64_t g0 = (uint64_t)p << kChunkLog2;
-        const uint64_t left = a.n - g0;
-        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-        load_raw<kUnits, kElem, kDirect>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem,
-                                         valid, t);
+    // The chunk's raw 16-byte units.  Through a buffer descriptor whose range is the part of
+    // the chunk that exists, reads beyond it return zero: there is no ragged path, and the
+    // load may be issued for a chunk past the end (range 0), which keeps the prefetch of the
+    // next item unconditional.
+    __device__ __forceinline__ void load(uint64_t p) {
+        const uint64_t g0 = p << kChunkLog2;
+        uint64_t left = p < a.chunks ? a.n - g0 : 0u;
+        if (left > (uint64_t)kChunk) left = kChunk;
+        uint64_t addr = reinterpret_cast<uint64_t>(ptrs.grad[w]) + (p < a.chunks ? g0 * kElem : 0u);
+        if constexpr (ODD) {
+            if (left != 0u) load_raw<kUnits, kElem, kDirect>(raw, reinterpret_cast<const void*>(addr), (uint32_t)left, t);
+        } else {
+            // the descriptor is the same for every lane: it belongs in scalar registers
+            addr = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(addr >> 32)) << 32) |
+                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+            const uint32_t bytes = (uint32_t)left * kElem;   // a multiple of 4: the count is even
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                reinterpret_cast<void*>(addr), 0, bytes, 0x00020000);
+            typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int j = 0; j < kUnits; ++j) {
+                const uint32_t unit = kDirect ? kUnits * t + j : j * kThreads + t;
+                const u4v q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit * 16u, 0, 0);
+                raw.u[j] = make_uint4(q.x, q.y, q.z, q.w);
+            }
+        }
     }
     __device__ __forceinline__ void fill_signs(uint32_t p, uint32_t which) {
         fill_sign_table<!BF16, BF16>(sh.sign[which], (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
@@ -67,10 +90,13 @@ struct EncodeAllCtx {
         const bool more = (uint64_t)p + dp < a.chunks;
         if (kDirect) {
             units_to_l1<kUnits, true>(sh.sign[parity], raw.u, v, t);
-            if (more) {
-                load(p + dp);
-                fill_signs(p + dp, parity ^ 1u);
-            }
+            // the conversion is complete before the registers of `raw` are loaded again: without
+            // this the compiler moves it below the loads and copies `raw` out of their way
+#pragma unroll
+            for (int i = 0; i < kRegs; ++i) asm volatile("" : "+v"(v[i]));
+            asm volatile("" ::: "memory");
+            load((uint64_t)p + dp);
+            if (more) fill_signs(p + dp, parity ^ 1u);
             parity ^= 1u;
         } else {
             load(p);
@@ -99,7 +125,8 @@ struct EncodeAllCtx {
     template <int BITS>
     __device__ __forceinline__ void back(const float (&v)[kRegs], uint32_t p) {
         const uint32_t* slot = a.slots + (uint64_t)p * nwords;
-        uint32_t sbits = 0u;
+        uint32_t mx = 0u;
+        bool done = false;
         // The peers of a chunk publish up to about 2 us apart and a word takes about as long
         // to travel, so the first read waits a little: reads that come back incomplete are not
         // free (they load the path the words travel on), and measured on the headline bucket a
@@ -107,7 +134,8 @@ struct EncodeAllCtx {
         // 3 % faster than reading at once and every 64 clocks.
         __builtin_amdgcn_s_sleep(kFirstPollSleep);
         for (uint32_t spins = 0;; ++spins) {
-            uint32_t all_valid = 0x80000000u, mx = 0u;
+            uint32_t all_valid = 0x80000000u;
+            mx = 0u;
             for (uint32_t base = 0; base < nwords; base += 64u) {
                 const uint32_t i = base + lane;
                 const uint32_t val =
@@ -117,23 +145,30 @@ struct EncodeAllCtx {
                 const uint32_t mag = val & 0x7FFFFFFFu;
                 mx = mag > mx ? mag : mx;
             }
-            const bool done = __all(all_valid != 0u);
-            if (done || spins >= a.max_spins) {
-                if (!done && lane == 0)
-                    __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                // The workspace leaves the kernel as it entered it, all zero.  A peer's wave
-                // publishes for this chunk only after the barriers of this item's rotation,
-                // which every wave of its workgroup reaches only after reading the words of
-                // the workgroup's previous chunk; with all of this chunk's words seen, nobody
-                // will read the previous chunk's words again, and this wave clears its own.
-                if (done && prev != kNone && lane == 0)
-                    __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                sbits = wave_umax(mx);
-                break;
-            }
+            done = __all(all_valid != 0u);
+            if (done || spins >= a.max_spins) break;
             __builtin_amdgcn_s_sleep(kPollSleep);
         }
+        // Every earlier vector-memory operation of the wave has completed (the read of the range
+        // words just did), among them the loads of the next item's input.  Passing those
+        // registers through an empty asm tells the compiler so: the next item then starts
+        // without a wait on them, which would also wait for the stores issued below.
+        if (kDirect) {
+#pragma unroll
+            for (int j = 0; j < kUnits; ++j)
+                asm volatile("" : "+v"(raw.u[j].x), "+v"(raw.u[j].y), "+v"(raw.u[j].z), "+v"(raw.u[j].w));
+        }
+        if (!done && lane == 0)
+            __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // The workspace leaves the kernel as it entered it, all zero.  A peer's wave
+        // publishes for this chunk only after the barriers of this item's rotation,
+        // which every wave of its workgroup reaches only after reading the words of
+        // the workgroup's previous chunk; with all of this chunk's words seen, nobody
+        // will read the previous chunk's words again, and this wave clears its own.
+        if (done && prev != kNone && lane == 0)
+            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t sbits = wave_umax(mx);
         prev = p;
         const float s = __uint_as_float(sbits);
         if (w == 0 && t == 0) a.scale[p] = s;
@@ -164,19 +199,25 @@ struct EncodeAllCtx {
 // Items are (chunk, worker) pairs; workgroup g of a grid of G (a multiple of W) takes worker
 // g mod W of chunks g / W, g / W + G / W, ...  The peers of an item are therefore items of
 // the same round of other workgroups, and with every workgroup resident no wait is circular.
-template <bool BF16, int BITS>
+template <bool BF16, int BITS, bool ODD>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
                                                                  const FusedWorkerPtrs ptrs) {
     __shared__ Shared sh;
+    using Ctx = EncodeAllCtx<BF16, ODD>;
     const uint32_t t = threadIdx.x;
     const uint32_t p0 = blockIdx.x / a.W;
-    EncodeAllCtx<BF16> c{a, ptrs, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
-                         gridDim.x / a.W, 0u, EncodeAllCtx<BF16>::kNone};
+    Ctx c{a, ptrs, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
+          gridDim.x / a.W, 0u, Ctx::kNone};
     if (p0 >= a.chunks) return;
-    if (EncodeAllCtx<BF16>::kDirect) {
+    if (Ctx::kDirect) {
         c.load(p0);
         c.fill_signs(p0, 0u);
         __syncthreads();
+        // the first chunk's input has arrived before the loop is entered, as every later
+        // chunk's has by the time its item starts (see the end of the wait in back())
+#pragma unroll
+        for (int j = 0; j < Ctx::kUnits; ++j)
+            asm volatile("" : "+v"(c.raw.u[j].x), "+v"(c.raw.u[j].y), "+v"(c.raw.u[j].z), "+v"(c.raw.u[j].w));
     }
     for (uint64_t p = p0; p < a.chunks; p += c.dp) {
         float v[kRegs];
@@ -594,9 +635,9 @@ uint32_t resident_grid() {
     return cached;
 }
 
-template <bool BF16, int BITS>
+template <bool BF16, int BITS, bool ODD>
 hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid<encode_all_kernel<BF16, BITS>>();
+    uint32_t G = resident_grid<encode_all_kernel<BF16, BITS, ODD>>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
@@ -604,7 +645,7 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
     // fewer resident workgroups than workers would leave peers that never run
     if (G < a.W) return hipErrorInvalidConfiguration;
     G -= G % a.W;
-    hipLaunchKernelGGL((encode_all_kernel<BF16, BITS>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    hipLaunchKernelGGL((encode_all_kernel<BF16, BITS, ODD>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
     return hipGetLastError();
 }
 
@@ -616,12 +657,12 @@ uint32_t encode_all_slot_words(uint32_t W) { return k14::kWaves * W; }
 // Workgroups of the one-pass encoder that the device keeps resident at once.
 static uint32_t encode_all_resident(bool bf16, uint32_t bits) {
     using namespace k14;
-    if (bf16) return bits == 2 ? resident_grid<encode_all_kernel<true, 2>>()
-                   : bits == 4 ? resident_grid<encode_all_kernel<true, 4>>()
-                               : resident_grid<encode_all_kernel<true, 8>>();
-    return bits == 2 ? resident_grid<encode_all_kernel<false, 2>>()
-         : bits == 4 ? resident_grid<encode_all_kernel<false, 4>>()
-                     : resident_grid<encode_all_kernel<false, 8>>();
+    if (bf16) return bits == 2 ? resident_grid<encode_all_kernel<true, 2, false>>()
+                   : bits == 4 ? resident_grid<encode_all_kernel<true, 4, false>>()
+                               : resident_grid<encode_all_kernel<true, 8, false>>();
+    return bits == 2 ? resident_grid<encode_all_kernel<false, 2, false>>()
+         : bits == 4 ? resident_grid<encode_all_kernel<false, 4, false>>()
+                     : resident_grid<encode_all_kernel<false, 8, false>>();
 }
 
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2,
@@ -652,14 +693,19 @@ hipError_t launch_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stre
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
                                    uint32_t bits, hipStream_t stream) {
     using namespace k14;
-    if (bf16) {
-        if (bits == 2) return launch_encode_all_t<true, 2>(a, ptrs, stream);
-        if (bits == 4) return launch_encode_all_t<true, 4>(a, ptrs, stream);
-        return launch_encode_all_t<true, 8>(a, ptrs, stream);
+    if (bf16 && (a.n & 1u)) {   // odd count of bf16: element-wise loader for the last coordinate
+        if (bits == 2) return launch_encode_all_t<true, 2, true>(a, ptrs, stream);
+        if (bits == 4) return launch_encode_all_t<true, 4, true>(a, ptrs, stream);
+        return launch_encode_all_t<true, 8, true>(a, ptrs, stream);
     }
-    if (bits == 2) return launch_encode_all_t<false, 2>(a, ptrs, stream);
-    if (bits == 4) return launch_encode_all_t<false, 4>(a, ptrs, stream);
-    return launch_encode_all_t<false, 8>(a, ptrs, stream);
+    if (bf16) {
+        if (bits == 2) return launch_encode_all_t<true, 2, false>(a, ptrs, stream);
+        if (bits == 4) return launch_encode_all_t<true, 4, false>(a, ptrs, stream);
+        return launch_encode_all_t<true, 8, false>(a, ptrs, stream);
+    }
+    if (bits == 2) return launch_encode_all_t<false, 2, false>(a, ptrs, stream);
+    if (bits == 4) return launch_encode_all_t<false, 4, false>(a, ptrs, stream);
+    return launch_encode_all_t<false, 8, false>(a, ptrs, stream);
 }
 
 bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
