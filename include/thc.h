@@ -13,7 +13,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work on it and never synchronise.
  *   - The caller owns every buffer.  Unless an entry point says otherwise the
- *     library allocates nothing and keeps no state between calls.
+ *     library allocates nothing.  Process-wide state, all of it: the poll limit set by
+ *     thc_set_spin_limit (one unsynchronised word read by every one-pass encode
+ *     launch), the device's compute-unit count and per-kernel occupancy (queried once,
+ *     then cached), and for thc_encode_all_static the per-device address of its fixed
+ *     device array.  Nothing else survives a call.
  *   - Inputs and outputs of one call must not overlap.
  *   - n is the number of gradient coordinates of ONE worker, c = 2^chunk_log2 the
  *     chunk length (1 <= chunk_log2 <= 14), chunks = ceil(n / c).  Coordinates
@@ -89,32 +93,39 @@ uint32_t thc_sum_bytes(uint32_t W, uint32_t bits);
 int rht_forward(const void* x, thc_dtype dt, uint64_t n, uint32_t chunk_log2, uint64_t seed,
                 float* y, void* stream);
 
-/* Partial rotation, inverse: x = D (1/sqrt(c)) H_c y; undoes rht_forward.
+/* Partial rotation, inverse: x = D (1/sqrt(c)) H_c y; undoes rht_forward.  The paper
+ * describes the sender only; the receiver's rotation back is implied by it (THC
+ * background paragraph: the aggregate is decoded into the gradient estimate).
  *   y   chunks * c fp32 values;   x   n fp32 values */
 int rht_inverse(const float* y, uint64_t n, uint32_t chunk_log2, uint64_t seed,
                 float* x, void* stream);
 
-/* Per-chunk range of one worker after the partial rotation ("we compute the
- * value range of each chunk"), in the symmetric form used here:
+/* Per-chunk range of one worker after the partial rotation (the "Partial rotation"
+ * paragraph takes the value range chunk by chunk), in the symmetric form used here:
  * absmax[p] = max_j |y_j| over chunk p of rht_forward(grad).
  *   absmax   chunks fp32 values */
 int thc_chunk_absmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2,
                      uint64_t seed, float* absmax, void* stream);
 
-/* Shared grid: scale[p] = max over workers of absmax_all[w][p].  Stands in for
+/* Shared grid: scale[p] = max over workers of absmax_all[w][p].  The paper is silent on
+ * how workers agree on a chunk's range ("Partial rotation" paragraph); this is the
+ * reading taken: one range per chunk, the largest over the workers.  Stands in for
  * the small max-all-reduce that lets every worker quantize onto the same grid,
  * so that integer payloads can be summed.
  *   absmax_all   W * chunks fp32, worker-major;   scale   chunks fp32 */
 int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float* scale,
                      void* stream);
 
-/* Encode one worker: rotate, then stochastically round every rotated value onto
+/* Encode one worker (THC background paragraph of the quantization subsection: q-bit
+ * stochastic quantization after the rotation): rotate, then stochastically round every rotated value onto
  * the 2^bits-point grid of [-s_p, +s_p] (index 0 at -s_p, index L = 2^bits - 1 at
  * +s_p), and bit-pack:
  *     inv = L / (s_p + s_p),  u = (r + 0.5) / 256,
- *     idx = min(floor(fma(y, inv, L/2 + u)), L);   s_p == 0: idx = 0
- * (the position y * inv + L/2 in grid units plus the noise u, evaluated as ONE fused
- * multiply-add: L/2 + u is exact in fp32; inv is one correctly rounded division).
+ *     idx = min(floor(t), L),  t = y * inv + L/2 + u;   s_p == 0: idx = 0
+ * (the position in grid units plus the noise u; inv is one correctly rounded division;
+ * t is evaluated as fma(y, inv, L/2 + u) for bits = 2 and 4, where L/2 + u is exact in
+ * fp32, and as fma(y + s_p, inv, u) for bits = 8, which keeps t within 1e-6 max(1, |t|) of
+ * its exact value on the 256-point grid).
  *   shared_scale  chunks fp32 (the output of thc_scale_reduce), or NULL to use
  *                 this worker's own absmax
  *   payload       thc_payload_bytes bytes; coordinate g occupies bits
@@ -132,7 +143,8 @@ int thc_encode(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk_log2, 
 int thc_aggregate(const uint8_t* const* payloads, uint32_t W, uint64_t n, uint32_t chunk_log2,
                   uint32_t bits, void* sums, void* stream);
 
-/* Decode the aggregate into the estimate of the workers' MEAN gradient:
+/* Decode the aggregate into the estimate of the workers' MEAN gradient (the receiver side
+ * the THC background paragraph implies; the paper evaluates the estimate of the average):
  *     step = (s_p + s_p) / L,  yhat = float(sum) * (step / W) - s_p,
  *     out  = D (1/sqrt(c)) H_c yhat   (first n coordinates)
  *   sums    as written by thc_aggregate;   scale   chunks fp32;   out   n fp32 */
@@ -204,7 +216,10 @@ int thc_encode_all_static(const void* const* grads, thc_dtype dt, uint32_t W, ui
 
 /* Upper bound on the polls of one inter-workgroup wait inside thc_encode_all (default
  * 2^22, about seconds).  A tuning and test knob: with a tiny limit the waits expire, the
- * error word is set and every wave still exits. */
+ * error word is set and every wave still exits.  PROCESS-GLOBAL and not thread-safe: the
+ * value is read when a call is enqueued, by every thread's calls; changing it while another
+ * thread encodes makes that thread's waits expire early, which only the error word of its
+ * workspace reports. */
 void thc_set_spin_limit(uint32_t polls);
 
 /* 1 if thc_aggregate_decode can run fused for this shape, in which case `sums` may be
@@ -276,10 +291,10 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
                              uint8_t* aggregate, unsigned long long* overflow_count, float* out,
                              void* stream);
 
-/* ---- min/max range (the paper's literal wording: "the value range between the minimum
- * and maximum gradient values is equally split", "the value range max_p - min_p of each
- * chunk p"), with the rotation optional (the "No Rotation" column of the THC throughput
- * table) and an optional bf16 output -----------------------------------------------------
+/* ---- min/max range (the range as the THC background paragraph and the "Partial rotation"
+ * paragraph word it: from the chunk's smallest to its largest value, split evenly), with
+ * the rotation optional (the "No Rotation" column of the THC throughput table) and an
+ * optional bf16 output ------------------------------------------------------------------
  * range arrays hold (lo, hi) pairs, 2 floats per chunk, 8-byte aligned.  The grid of a chunk
  * has 2^bits points, index 0 at lo and index L at hi, shared by all workers:
  *     inv = L / (hi - lo)  (0 when hi == lo),  idx = min(floor(fma(y - lo, inv, u)), L)
@@ -307,8 +322,8 @@ int thc_decode_minmax(const void* sums, const float* range, uint32_t W, uint64_t
 
 /* ---- full rotation (l' = l): the baseline the paper's "Partial rotation" paragraph and
  * its THC throughput table compare against ---------------------------------------------
- * The whole gradient, zero-padded to 2^log2_size coordinates ("Gradients are padded to
- * size 2^l", notation table), is ONE chunk: y = 2^(-l/2) H_(2^l) D x with the same stage
+ * The whole gradient, zero-padded to 2^log2_size coordinates (the notation table pads
+ * gradients to a power of two), is ONE chunk: y = 2^(-l/2) H_(2^l) D x with the same stage
  * order, sign diagonal and rounding as the chunked path (identical to it with
  * chunk_log2 = log2_size, which the chunked entry points do not accept above 14).
  * Stages above 2^14 run as passes over y in global memory, in place, so rotated data is

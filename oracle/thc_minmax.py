@@ -1,8 +1,7 @@
 """CPU oracle of the paper-literal range variant: the grid spans the chunk's minimum to
-its maximum ("the value range between the minimum and maximum gradient values is equally
-split", "compute the value range max_p - min_p of each chunk p"), optionally without any
-rotation (the "No Rotation" column of the THC throughput table), with an optional bf16
-output.
+its maximum, split evenly (the range as the THC background paragraph and the "Partial
+rotation" paragraph word it), optionally without any rotation (the "No Rotation" column
+of the THC throughput table), with an optional bf16 output.
 
 TEST INFRASTRUCTURE ONLY, like the rest of this package.
 

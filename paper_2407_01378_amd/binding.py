@@ -275,7 +275,9 @@ def thc_encode_all_workspace_bytes(W, n, chunk_log2):
     return lib().thc_encode_all_workspace_bytes(W, n, chunk_log2)
 
 
-def _encode_all(name, grads, chunk_log2, seed, bits, payloads, scale, workspace, stream):
+def _encode_all(name, grads, chunk_log2, seed, bits, payloads, scale, workspace, stream, check=False):
+    """check=True synchronises the device after the call and raises ThcError(-7) if a bounded
+    wait between workgroups expired (the workspace's first word); marshalling otherwise."""
     W = len(grads)
     n = grads[0].numel()
     for g in grads:
@@ -288,16 +290,20 @@ def _encode_all(name, grads, chunk_log2, seed, bits, payloads, scale, workspace,
                                 _ptr(scale), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)),
            name)
+    if check:
+        torch.cuda.synchronize(workspace.device)
+        if thc_encode_all_timed_out(workspace):
+            raise ThcError(-7, name + " (a bounded wait between workgroups expired)")
     return payloads
 
 
-def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
-    return _encode_all("thc_encode_all", grads, chunk_log2, seed, bits, payloads, scale, workspace, stream)
+def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None, check=False):
+    return _encode_all("thc_encode_all", grads, chunk_log2, seed, bits, payloads, scale, workspace, stream, check)
 
 
-def thc_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+def thc_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None, check=False):
     return _encode_all("thc_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
-                       workspace, stream)
+                       workspace, stream, check)
 
 
 THC_STATIC_SCRATCH_BYTES = 2 << 20
@@ -361,14 +367,14 @@ def thc_sat_encode(grad, chunk_log2, seed, worker, bits, shared_scale, payload, 
     return payload
 
 
-def thc_sat_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+def thc_sat_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None, check=False):
     return _encode_all("thc_sat_encode_all", grads, chunk_log2, seed, bits, payloads, scale, workspace,
-                       stream)
+                       stream, check)
 
 
-def thc_sat_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None):
+def thc_sat_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None, check=False):
     return _encode_all("thc_sat_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
-                       workspace, stream)
+                       workspace, stream, check)
 
 
 def thc_sat_aggregate(payloads, n, chunk_log2, bits, aggregate, overflow_count=None, stream=None):
