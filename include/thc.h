@@ -195,6 +195,44 @@ int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, u
                            uint32_t chunk_log2, uint64_t seed, uint32_t bits, uint8_t* const* payloads,
                            float* scale, void* workspace, uint64_t workspace_bytes, void* stream);
 
+/* ---- several buckets per launch ---------------------------------------------------------
+ * A gradient that is processed bucket by bucket (the headline configuration cuts 1.3e9
+ * coordinates into 25 * 2^20-coordinate buckets, as data-parallel training frameworks do)
+ * can hand any number of ready buckets to ONE call: the kernels run over all their chunks
+ * in one persistent launch, so the start-up and the partly filled last round of a launch
+ * are paid once instead of once per bucket.  Results are byte for byte those of
+ * thc_encode_all / thc_aggregate_decode called bucket by bucket.
+ * Restrictions (negative status otherwise): chunk_log2 == 14 (THC_ERR_CHUNK); W <= 64 and,
+ * for the decode side, the shapes for which thc_aggregate_decode_is_fused is 1
+ * (THC_ERR_WORKERS); gradients, payloads and outputs 16-byte aligned (THC_ERR_ALIGN); at
+ * most 4096 buckets (THC_ERR_SIZE).  A bucket with n == 0 is skipped. */
+typedef struct {
+    const void* const* grads;  /* HOST array of W device pointers, n values each; encode only */
+    uint8_t* const* payloads;  /* HOST array of W device pointers, thc_payload_bytes(n, 14, bits) each */
+    float* scale;              /* device, chunks fp32: written by the encode call, read by the decode call */
+    float* out;                /* device, n fp32: decode only */
+    uint64_t n;                /* coordinates of one worker in this bucket */
+    uint64_t seed;             /* the bucket's seed, as passed to the per-bucket calls */
+} thc_bucket;
+
+/* Bytes of device scratch the two batched calls need for these buckets (the decode call
+ * uses only the first 16 + count * (40 + 16 W) bytes, rounded up to 16).  0 on bad arguments.
+ *   buckets   HOST array; only n is read */
+uint64_t thc_batch_workspace_bytes(const thc_bucket* buckets, uint32_t count, uint32_t W,
+                                   uint32_t chunk_log2);
+
+/* thc_encode_all over every bucket.  The workspace may be in any state (the call clears
+ * what it uses); its first 32-bit word reports an expired wait as for thc_encode_all.  The
+ * per-bucket records travel to the device as arguments of small kernels: no host-to-device
+ * copy, no allocation.  Same rules about concurrent calls as thc_encode_all. */
+int thc_encode_all_batch(const thc_bucket* buckets, uint32_t count, thc_dtype dt, uint32_t W,
+                         uint32_t chunk_log2, uint32_t bits, void* workspace, uint64_t workspace_bytes,
+                         void* stream);
+
+/* thc_aggregate_decode (sums == NULL) over every bucket; writes out[0 .. n) of each. */
+int thc_aggregate_decode_batch(const thc_bucket* buckets, uint32_t count, uint32_t W, uint32_t chunk_log2,
+                               uint32_t bits, void* workspace, uint64_t workspace_bytes, void* stream);
+
 /* thc_encode_all for callers that cannot allocate device memory or pass a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Not a
  * step of the paper: the same computation as thc_encode_all, with the workspace taken from

@@ -19,7 +19,23 @@ THC_OK = 0
 _lib = None
 
 _u8pp = ctypes.POINTER(ctypes.c_void_p)
+
+
+class ThcBucket(ctypes.Structure):
+    """thc_bucket of include/thc.h."""
+    _fields_ = [("grads", _u8pp), ("payloads", _u8pp), ("scale", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("n", ctypes.c_uint64), ("seed", ctypes.c_uint64)]
+
+
+_bucketp = ctypes.POINTER(ThcBucket)
 _SIGNATURES = {
+    "thc_batch_workspace_bytes": (ctypes.c_uint64, [_bucketp, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]),
+    "thc_encode_all_batch": (ctypes.c_int, [_bucketp, ctypes.c_uint32, ctypes.c_int, ctypes.c_uint32,
+                                            ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                            ctypes.c_void_p]),
+    "thc_aggregate_decode_batch": (ctypes.c_int, [_bucketp, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                                  ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                                  ctypes.c_void_p]),
     "thc_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "thc_version": (ctypes.c_int, []),
     "thc_rounding_bits": (ctypes.c_uint32, []),
@@ -304,6 +320,50 @@ def thc_encode_all(grads, chunk_log2, seed, bits, payloads, scale, workspace, st
 def thc_encode_all_cleared(grads, chunk_log2, seed, bits, payloads, scale, workspace, stream=None, check=False):
     return _encode_all("thc_encode_all_cleared", grads, chunk_log2, seed, bits, payloads, scale,
                        workspace, stream, check)
+
+
+# ------------------------------------------------------------ several buckets per launch
+def _bucket_array(buckets):
+    """buckets: list of dicts with keys n, seed and any of grads (list of W tensors), payloads
+    (list of W tensors), scale, out.  Returns (keep-alive objects, ctypes array)."""
+    arr = (ThcBucket * max(len(buckets), 1))()
+    keep = []
+    for i, b in enumerate(buckets):
+        if b.get("grads") is not None:
+            kg, pg = _ptr_array(b["grads"])
+            keep.append(kg)
+            arr[i].grads = pg
+        if b.get("payloads") is not None:
+            kp, pp = _ptr_array(b["payloads"])
+            keep.append(kp)
+            arr[i].payloads = pp
+        arr[i].scale = None if b.get("scale") is None else b["scale"].data_ptr()
+        arr[i].out = None if b.get("out") is None else b["out"].data_ptr()
+        arr[i].n = int(b["n"])
+        arr[i].seed = int(b.get("seed", 0))
+    return keep, arr
+
+
+def thc_batch_workspace_bytes(ns, W, chunk_log2):
+    keep, arr = _bucket_array([dict(n=n) for n in ns])
+    return lib().thc_batch_workspace_bytes(arr, len(ns), W, chunk_log2)
+
+
+def thc_encode_all_batch(buckets, chunk_log2, bits, workspace, stream=None):
+    W = len(buckets[0]["grads"]) if buckets else 1
+    keep, arr = _bucket_array(buckets)
+    dt = _dtype_code(buckets[0]["grads"][0]) if buckets else THC_F32
+    _check(lib().thc_encode_all_batch(arr, len(buckets), dt, W, chunk_log2, bits, _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)),
+           "thc_encode_all_batch")
+
+
+def thc_aggregate_decode_batch(buckets, chunk_log2, bits, workspace, stream=None):
+    W = len(buckets[0]["payloads"]) if buckets else 1
+    keep, arr = _bucket_array(buckets)
+    _check(lib().thc_aggregate_decode_batch(arr, len(buckets), W, chunk_log2, bits, _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "thc_aggregate_decode_batch")
 
 
 THC_STATIC_SCRATCH_BYTES = 2 << 20

@@ -1,6 +1,7 @@
 // C ABI of the library: argument checking on the host (before any HIP call), then
 // dispatch to the kernel launchers.  See include/thc.h for the contract.
 #include <math.h>
+#include <string.h>
 
 #include <mutex>
 
@@ -322,6 +323,164 @@ int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, u
                            float* scale, void* workspace, uint64_t workspace_bytes, void* stream) {
     return encode_all_impl(grads, dt, W, n, chunk_log2, seed, bits, payloads, scale, workspace,
                            workspace_bytes, stream, false, true);
+}
+
+// ---- several buckets in one launch -------------------------------------------------------
+namespace {
+
+constexpr uint32_t kMaxBatch = 4096;
+
+struct BatchPlan {
+    uint64_t total_chunks = 0;
+    uint64_t record_words = 0;    // 32-bit words of all records, padded to 16 bytes
+    bool any_odd = false;
+};
+
+// Checks that do not depend on the direction, and the sizes that follow from the buckets.
+int plan_batch(const thc_bucket* buckets, uint32_t count, uint32_t W, uint32_t chunk_log2, uint32_t bits,
+               BatchPlan* plan) {
+    if (chunk_log2 != 14) return THC_ERR_CHUNK;
+    int rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0 || W > (uint32_t)thc::kMaxFusedWorkers) return THC_ERR_WORKERS;
+    if (count > kMaxBatch) return THC_ERR_SIZE;
+    if (count != 0 && !buckets) return THC_ERR_NULL;
+    for (uint32_t b = 0; b < count; ++b) {
+        if (buckets[b].n > kMaxCoords) return THC_ERR_SIZE;
+        plan->total_chunks += padded_coords(buckets[b].n, chunk_log2) >> chunk_log2;
+        plan->any_odd = plan->any_odd || (buckets[b].n & 1u);
+    }
+    if (plan->total_chunks * W >= 0x7FFFFFFFull) return THC_ERR_SIZE;
+    plan->record_words = ((uint64_t)count * thc::batch_record_bytes(W) + 15u) / 16u * 4u;
+    return THC_OK;
+}
+
+// Writes the records of the non-empty buckets to `dst` (device) on the stream; returns their number.
+int write_records(const thc_bucket* buckets, uint32_t count, uint32_t W, uint32_t chunk_log2, bool decode,
+                  uint32_t* dst, hipStream_t st, uint32_t* written) {
+    // staged on the stack, one batch of kernel arguments at a time: no host allocation either
+    uint32_t stage[thc::kBlobWords];
+    const uint32_t rec_words = thc::batch_record_bytes(W) / 4u;
+    uint32_t used = 0, live = 0;
+    uint64_t chunk0 = 0;
+    uint32_t* out = dst;
+    for (uint32_t b = 0; b < count; ++b) {
+        const thc_bucket& k = buckets[b];
+        if (k.n == 0) continue;
+        if (used + rec_words > (uint32_t)thc::kBlobWords) {
+            if (thc::launch_write_words(out, stage, used, st) != hipSuccess) return THC_ERR_HIP;
+            out += used;
+            used = 0;
+        }
+        thc::BatchRecord r{};
+        r.n = k.n;
+        r.chunk0 = chunk0;
+        r.key0 = (uint32_t)k.seed;
+        r.key1 = (uint32_t)(k.seed >> 32);
+        r.scale = k.scale;
+        r.out = decode ? k.out : nullptr;
+        memcpy(stage + used, &r, sizeof r);
+        uint64_t* ptr = reinterpret_cast<uint64_t*>(stage + used + sizeof(r) / 4u);
+        for (uint32_t w = 0; w < W; ++w) {
+            ptr[w] = decode ? 0u : reinterpret_cast<uint64_t>(k.grads[w]);
+            ptr[W + w] = reinterpret_cast<uint64_t>(k.payloads[w]);
+        }
+        used += rec_words;
+        chunk0 += padded_coords(k.n, chunk_log2) >> chunk_log2;
+        ++live;
+    }
+    if (used != 0 && thc::launch_write_words(out, stage, used, st) != hipSuccess) return THC_ERR_HIP;
+    *written = live;
+    return THC_OK;
+}
+
+}  // namespace
+
+uint64_t thc_batch_workspace_bytes(const thc_bucket* buckets, uint32_t count, uint32_t W, uint32_t chunk_log2) {
+    BatchPlan plan;
+    if (plan_batch(buckets, count, W, chunk_log2, 4, &plan) != THC_OK) return 0;
+    // error word (16 bytes) + records + range words and arrival counters as in thc_encode_all
+    return 16 + 4 * plan.record_words + 4 * ((uint64_t)thc::encode_all_slot_words(W) + 1u) * plan.total_chunks;
+}
+
+int thc_encode_all_batch(const thc_bucket* buckets, uint32_t count, thc_dtype dt, uint32_t W,
+                         uint32_t chunk_log2, uint32_t bits, void* workspace, uint64_t workspace_bytes,
+                         void* stream) {
+    int rc = check_dtype(dt);
+    BatchPlan plan;
+    if (rc == THC_OK) rc = plan_batch(buckets, count, W, chunk_log2, bits, &plan);
+    if (rc != THC_OK) return rc;
+    if (plan.total_chunks == 0) return THC_OK;
+    if (!workspace) return THC_ERR_NULL;
+    if (!aligned(workspace, 16)) return THC_ERR_ALIGN;
+    for (uint32_t b = 0; b < count; ++b) {
+        const thc_bucket& k = buckets[b];
+        if (k.n == 0) continue;
+        if (!k.grads || !k.payloads || !k.scale) return THC_ERR_NULL;
+        if (!aligned(k.scale, 4)) return THC_ERR_ALIGN;
+        for (uint32_t w = 0; w < W; ++w) {
+            if (!k.grads[w] || !k.payloads[w]) return THC_ERR_NULL;
+            if (!aligned(k.grads[w], 16) || !aligned(k.payloads[w], 16)) return THC_ERR_ALIGN;
+        }
+    }
+    if (workspace_bytes < thc_batch_workspace_bytes(buckets, count, W, chunk_log2)) return THC_ERR_SIZE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t* words = static_cast<uint32_t*>(workspace);
+    uint32_t* records = words + 4;
+    uint32_t* slots = records + plan.record_words;
+    const uint64_t slot_words = (uint64_t)thc::encode_all_slot_words(W) * plan.total_chunks;
+
+    thc::EncodeAllArgs a{};
+    a.chunks = plan.total_chunks;
+    a.W = W;
+    a.max_spins = g_spin_limit;
+    a.levels = thc::grid_levels(bits, false);
+    a.error = words;
+    a.slots = slots;
+    a.done = slots + slot_words;
+    thc::BatchArgs batch{};
+    batch.records = reinterpret_cast<const uint8_t*>(records);
+    batch.record_bytes = thc::batch_record_bytes(W);
+    rc = write_records(buckets, count, W, chunk_log2, false, records, st, &batch.count);
+    if (rc != THC_OK) return rc;
+    if (thc::launch_zero_words(words, 4, st) != hipSuccess) return THC_ERR_HIP;
+    if (thc::launch_zero_words(slots, slot_words + plan.total_chunks, st) != hipSuccess) return THC_ERR_HIP;
+    const hipError_t e = thc::launch_encode_all_batch(a, batch, dt == THC_BF16, plan.any_odd, bits, st);
+    if (e == hipErrorInvalidConfiguration) return THC_ERR_WORKERS;   // fewer resident workgroups than workers
+    return finish(e);
+}
+
+int thc_aggregate_decode_batch(const thc_bucket* buckets, uint32_t count, uint32_t W, uint32_t chunk_log2,
+                               uint32_t bits, void* workspace, uint64_t workspace_bytes, void* stream) {
+    BatchPlan plan;
+    int rc = plan_batch(buckets, count, W, chunk_log2, bits, &plan);
+    if (rc != THC_OK) return rc;
+    if (!thc::aggregate_decode_fused_applicable(W, chunk_log2, bits)) return THC_ERR_WORKERS;
+    if (plan.total_chunks == 0) return THC_OK;
+    if (!workspace) return THC_ERR_NULL;
+    if (!aligned(workspace, 16)) return THC_ERR_ALIGN;
+    for (uint32_t b = 0; b < count; ++b) {
+        const thc_bucket& k = buckets[b];
+        if (k.n == 0) continue;
+        if (!k.payloads || !k.scale || !k.out) return THC_ERR_NULL;
+        if (!aligned(k.scale, 4) || !aligned(k.out, 16)) return THC_ERR_ALIGN;
+        for (uint32_t w = 0; w < W; ++w) {
+            if (!k.payloads[w]) return THC_ERR_NULL;
+            if (!aligned(k.payloads[w], 16)) return THC_ERR_ALIGN;
+        }
+    }
+    if (workspace_bytes < 16 + 4 * plan.record_words) return THC_ERR_SIZE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t* records = static_cast<uint32_t*>(workspace) + 4;
+    thc::AggDecodeArgs a{};
+    a.chunks = plan.total_chunks;
+    a.W = W;
+    thc::BatchArgs batch{};
+    batch.records = reinterpret_cast<const uint8_t*>(records);
+    batch.record_bytes = thc::batch_record_bytes(W);
+    rc = write_records(buckets, count, W, chunk_log2, true, records, st, &batch.count);
+    if (rc != THC_OK) return rc;
+    return finish(thc::launch_aggregate_decode_batch(a, batch, bits, st));
 }
 
 // ---- thc_encode_all for callers that cannot allocate ---------------------------------

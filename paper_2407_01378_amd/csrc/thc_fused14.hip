@@ -29,10 +29,35 @@ constexpr int kWavesPerSimd = 4;
 constexpr int kFirstPollSleep = 32;
 constexpr int kPollSleep = 8;
 // ------------------------------------------------------------------ encode_all
+// The records of a batched launch were written by earlier kernels and are never written by
+// this one: reading them through the constant address space lets the compiler use scalar
+// loads (one request per wave, served by the scalar cache) where a global pointer, which
+// might alias the kernel's stores, would get a vector load and its full memory latency.
+#define THC_CONSTANT __attribute__((address_space(4)))
+typedef const BatchRecord THC_CONSTANT* ConstRecordPtr;
+typedef const uint64_t THC_CONSTANT* ConstU64Ptr;
+__device__ __forceinline__ ConstRecordPtr batch_record(const BatchArgs& batch, uint32_t k) {
+    return (ConstRecordPtr)(batch.records + (uint64_t)k * batch.record_bytes);
+}
+
+// What an item needs to know about the bucket its chunk belongs to; the same for every
+// lane, so it lives in scalar registers.  A single-bucket call has one view for good; a
+// batched call looks the view up in the records as its chunks move from bucket to bucket.
+struct BucketView {
+    uint64_t n;          // coordinates of the bucket
+    uint64_t chunk0;     // number of its first chunk in the launch's chunk numbering
+    uint32_t key0, key1;
+    const void* grad;    // of this workgroup's worker
+    uint8_t* payload;
+    float* scale;
+};
+
 // ODD: bf16 input with an odd number of coordinates.  Its last coordinate shares a dword
 // with nothing, which the range check of a buffer load (done per dword) would cut off, so
 // that shape keeps the element-wise loader; every other shape loads through a descriptor.
-template <bool BF16, bool ODD>
+// BATCH: the launch covers several buckets (a.chunks is their total, chunks are numbered
+// through all of them); everything per bucket comes from the records in device memory.
+template <bool BF16, bool ODD, bool BATCH>
 struct EncodeAllCtx {
     static constexpr int kUnits = BF16 ? 4 : 8;
     static constexpr int kElem = BF16 ? 2 : 4;
@@ -42,6 +67,7 @@ struct EncodeAllCtx {
     static constexpr bool kDirect = BF16;
     const EncodeAllArgs& a;
     const FusedWorkerPtrs& ptrs;
+    const BatchArgs& batch;
     Shared& sh;
     Raw<kUnits> raw;        // input of the next item to enter the pipeline, in flight
     uint32_t t, lane, wave, nwords;
@@ -49,17 +75,33 @@ struct EncodeAllCtx {
     uint32_t dp;            // chunk stride between consecutive items of this workgroup
     uint32_t parity;        // which sign table the next front() reads
     uint32_t prev;          // chunk of the workgroup's previous item, kNone before the first
+    uint32_t bidx;          // BATCH: bucket of the most recent look-up (chunks only move forward)
+    uint64_t boundary;      // BATCH: first chunk of the bucket after that one
+    BucketView cur, nxt;    // of the item being processed / of the item whose input is in flight
     static constexpr uint32_t kNone = 0xFFFFFFFFu;
+
+    __device__ __forceinline__ BucketView view_of(uint64_t p) {
+        if constexpr (BATCH) {
+            while (bidx + 1u < batch.count && p >= batch_record(batch, bidx + 1u)->chunk0) ++bidx;
+            ConstRecordPtr r = batch_record(batch, bidx);
+            boundary = bidx + 1u < batch.count ? batch_record(batch, bidx + 1u)->chunk0 : ~0ull;
+            ConstU64Ptr ptr = (ConstU64Ptr)(r + 1);   // W gradients, then W payloads
+            return BucketView{r->n, r->chunk0, r->key0, r->key1, reinterpret_cast<const void*>(ptr[w]),
+                              reinterpret_cast<uint8_t*>(ptr[a.W + w]), r->scale};
+        } else {
+            return BucketView{a.n, 0u, a.key0, a.key1, ptrs.grad[w], ptrs.payload[w], a.scale};
+        }
+    }
 
     // The chunk's raw 16-byte units.  Through a buffer descriptor whose range is the part of
     // the chunk that exists, reads beyond it return zero: there is no ragged path, and the
     // load may be issued for a chunk past the end (range 0), which keeps the prefetch of the
     // next item unconditional.
-    __device__ __forceinline__ void load(uint64_t p) {
-        const uint64_t g0 = p << kChunkLog2;
-        uint64_t left = p < a.chunks ? a.n - g0 : 0u;
+    __device__ __forceinline__ void load(uint64_t p, const BucketView& bv) {
+        const uint64_t g0 = (p - bv.chunk0) << kChunkLog2;
+        uint64_t left = p < a.chunks ? bv.n - g0 : 0u;
         if (left > (uint64_t)kChunk) left = kChunk;
-        uint64_t addr = reinterpret_cast<uint64_t>(ptrs.grad[w]) + (p < a.chunks ? g0 * kElem : 0u);
+        uint64_t addr = reinterpret_cast<uint64_t>(bv.grad) + (p < a.chunks ? g0 * kElem : 0u);
         if constexpr (ODD) {
             if (left != 0u) load_raw<kUnits, kElem, kDirect>(raw, reinterpret_cast<const void*>(addr), (uint32_t)left, t);
         } else {
@@ -78,16 +120,16 @@ struct EncodeAllCtx {
             }
         }
     }
-    __device__ __forceinline__ void fill_signs(uint32_t p, uint32_t which) {
-        fill_sign_table<!BF16, BF16>(sh.sign[which], (uint64_t)p << kChunkLog2, a.key0, a.key1, t);
+    __device__ __forceinline__ void fill_signs(uint64_t p, const BucketView& bv, uint32_t which) {
+        fill_sign_table<!BF16, BF16>(sh.sign[which], (p - bv.chunk0) << kChunkLog2, bv.key0, bv.key1, t);
     }
 
     // Front half of an item: bring the input into registers (layout L1), rotate, publish
     // this wave's share of the chunk's range, and bring the chunk into the quantizer's
     // layout.  The direct form also fills the sign table of the workgroup's next item,
     // which is read only after the barriers of this item's exchanges.
-    __device__ __forceinline__ void front(float (&v)[kRegs], uint32_t p) {
-        const bool more = (uint64_t)p + dp < a.chunks;
+    __device__ __forceinline__ void front(float (&v)[kRegs], uint64_t p) {
+        const bool more = p + dp < a.chunks;
         if (kDirect) {
             units_to_l1<kUnits, true>(sh.sign[parity], raw.u, v, t);
             // the conversion is complete before the registers of `raw` are loaded again: without
@@ -95,16 +137,18 @@ struct EncodeAllCtx {
 #pragma unroll
             for (int i = 0; i < kRegs; ++i) asm volatile("" : "+v"(v[i]));
             asm volatile("" ::: "memory");
-            load((uint64_t)p + dp);
-            if (more) fill_signs(p + dp, parity ^ 1u);
+            if (BATCH && more && p + dp >= boundary) nxt = view_of(p + dp);   // rarely: a new bucket
+            load(p + dp, nxt);
+            if (more) fill_signs(p + dp, nxt, parity ^ 1u);
             parity ^= 1u;
         } else {
-            load(p);
+            load(p, cur);
             __syncthreads();   // the previous item's last reads of the buffer and table are done
-            fill_signs(p, 0u);
+            fill_signs(p, cur, 0u);
             raw_to_lds<kUnits>(sh, raw, t);
             __syncthreads();
             lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
+            if (BATCH && more && p + dp >= boundary) nxt = view_of(p + dp);
         }
         rotate_l1_to_l3<true>(sh, v, lane, wave);
         const float m = wave_absmax(v) * kInvSqrtC;
@@ -113,7 +157,7 @@ struct EncodeAllCtx {
         // through device-scope stores and loads, which are served at the memory side, so
         // no cache write-back or invalidate is needed.  The slots start zeroed.
         if (lane == 0)
-            __hip_atomic_store(&a.slots[(uint64_t)p * nwords + kWaves * w + wave],
+            __hip_atomic_store(&a.slots[p * nwords + kWaves * w + wave],
                                __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         l3_to_l4e<true>(sh, v, lane, wave);
@@ -123,8 +167,8 @@ struct EncodeAllCtx {
     // the largest value as the shared scale, quantize and store.  The wait is bounded:
     // on time-out the error word is set and the wave carries on.
     template <int BITS>
-    __device__ __forceinline__ void back(const float (&v)[kRegs], uint32_t p) {
-        const uint32_t* slot = a.slots + (uint64_t)p * nwords;
+    __device__ __forceinline__ void back(const float (&v)[kRegs], uint64_t p) {
+        const uint32_t* slot = a.slots + p * nwords;
         uint32_t mx = 0u;
         bool done = false;
         // The peers of a chunk publish up to about 2 us apart and a word takes about as long
@@ -169,10 +213,11 @@ struct EncodeAllCtx {
             __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const uint32_t sbits = wave_umax(mx);
-        prev = p;
+        prev = (uint32_t)p;
         const float s = __uint_as_float(sbits);
-        if (w == 0 && t == 0) a.scale[p] = s;
-        quantize_store<BITS, false>(v, s, a.levels, (uint64_t)p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        const uint64_t pl = p - cur.chunk0;   // the chunk's number inside its bucket
+        if (w == 0 && t == 0) cur.scale[pl] = s;
+        quantize_store<BITS, false>(v, s, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1, cur.payload, t);
     }
 
     // After the workgroup's last item: its words have no later chunk to vouch for them, so
@@ -199,19 +244,21 @@ struct EncodeAllCtx {
 // Items are (chunk, worker) pairs; workgroup g of a grid of G (a multiple of W) takes worker
 // g mod W of chunks g / W, g / W + G / W, ...  The peers of an item are therefore items of
 // the same round of other workgroups, and with every workgroup resident no wait is circular.
-template <bool BF16, int BITS, bool ODD>
+template <bool BF16, int BITS, bool ODD, bool BATCH>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
-                                                                 const FusedWorkerPtrs ptrs) {
+                                                                 const FusedWorkerPtrs ptrs,
+                                                                 const BatchArgs batch) {
     __shared__ Shared sh;
-    using Ctx = EncodeAllCtx<BF16, ODD>;
+    using Ctx = EncodeAllCtx<BF16, ODD, BATCH>;
     const uint32_t t = threadIdx.x;
     const uint32_t p0 = blockIdx.x / a.W;
-    Ctx c{a, ptrs, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
-          gridDim.x / a.W, 0u, Ctx::kNone};
+    Ctx c{a, ptrs, batch, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
+          gridDim.x / a.W, 0u, Ctx::kNone, 0u, 0u, {}, {}};
     if (p0 >= a.chunks) return;
+    c.cur = c.nxt = c.view_of(p0);
     if (Ctx::kDirect) {
-        c.load(p0);
-        c.fill_signs(p0, 0u);
+        c.load(p0, c.cur);
+        c.fill_signs(p0, c.cur, 0u);
         __syncthreads();
         // the first chunk's input has arrived before the loop is entered, as every later
         // chunk's has by the time its item starts (see the end of the wait in back())
@@ -221,10 +268,21 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(con
     }
     for (uint64_t p = p0; p < a.chunks; p += c.dp) {
         float v[kRegs];
-        c.front(v, (uint32_t)p);
-        c.template back<BITS>(v, (uint32_t)p);
+        c.front(v, p);
+        c.template back<BITS>(v, p);
+        if (BATCH) c.cur = c.nxt;
     }
     c.finish();
+}
+
+// Copies `count` 32-bit words that arrive as kernel arguments to device memory: how the
+// batched calls put their per-bucket records where the kernels can read them, without a
+// host-to-device copy (which would need a staging allocation or pinned memory).
+struct WordBlob {
+    uint32_t w[kBlobWords];
+};
+__global__ __launch_bounds__(256) void write_words_kernel(uint32_t* dst, const WordBlob blob, uint32_t count) {
+    for (uint32_t i = threadIdx.x; i < count; i += 256u) dst[i] = blob.w[i];
 }
 
 // Fill with zeros (a kernel, not a memset node, so that callers can capture it in a
@@ -277,13 +335,14 @@ __device__ __forceinline__ PayloadWords<BITS> load_payload_words(const uint8_t* 
 
 // Sum of the workers' payload words of one thread (its 32 coordinates) in sub-word lanes,
 // built up group by group: a group is the payload of kGroup workers in flight at once.
-template <int BITS>
+template <int BITS, bool BATCH = false>
 struct PayloadSum {
     static constexpr int kWords = BITS;                        // payload dwords per worker per thread
     static constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;    // sub-word accumulators per dword
     static constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
     static constexpr int kGroup = BITS == 8 ? 2 : 4;           // at most 16 registers in flight
-    const FusedPayloadPtrs& ptrs;
+    const FusedPayloadPtrs& ptrs;   // single bucket: the payload pointers, in the kernel arguments
+    ConstU64Ptr pp;                 // batched: those of the bucket being summed, in its record
     uint32_t W;
     uint32_t acc[kWords][kLanes];
     PayloadWords<BITS> x[kGroup];
@@ -297,7 +356,11 @@ struct PayloadSum {
     __device__ __forceinline__ void issue(uint64_t byte0, uint32_t group) {
 #pragma unroll
         for (int j = 0; j < kGroup; ++j)
-            if (group * kGroup + j < W) x[j] = load_payload_words<BITS>(ptrs.p[group * kGroup + j] + byte0);
+            if (group * kGroup + j < W) {
+                const uint8_t* src = BATCH ? reinterpret_cast<const uint8_t*>(pp[group * kGroup + j])
+                                           : ptrs.p[group * kGroup + j];
+                x[j] = load_payload_words<BITS>(src + byte0);
+            }
     }
     __device__ __forceinline__ void add(uint32_t group) {
 #pragma unroll
@@ -314,9 +377,9 @@ struct PayloadSum {
 
 // Called from inside the rotation of the current chunk: loads and sums the first three
 // worker groups of the workgroup's NEXT chunk, one exchange of latency apart.
-template <int BITS>
+template <int BITS, bool BATCH>
 struct NextChunkLoads {
-    PayloadSum<BITS>& sum;
+    PayloadSum<BITS, BATCH>& sum;
     uint64_t byte0;
     bool active;
     template <int K>
@@ -327,35 +390,63 @@ struct NextChunkLoads {
     }
 };
 
-template <int BITS>
+// The bucket a decode item belongs to (uniform).  A single-bucket call has one for good; a
+// batched call looks it up in the records as its chunks move from bucket to bucket.
+struct DecodeView {
+    uint64_t n, chunk0;
+    uint32_t key0, key1;
+    const float* scale;
+    float* out;
+    ConstU64Ptr pp;      // the bucket's W payload pointers
+};
+
+template <int BITS, bool BATCH>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kernel(const AggDecodeArgs a,
-                                                                       const FusedPayloadPtrs ptrs) {
+                                                                       const FusedPayloadPtrs ptrs,
+                                                                       const BatchArgs batch) {
     __shared__ Shared sh;
-    using Sum = PayloadSum<BITS>;
+    using Sum = PayloadSum<BITS, BATCH>;
     constexpr int kWords = Sum::kWords, kLanes = Sum::kLanes;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const float Lf = (float)((1u << BITS) - 1u);
     const float Wf = (float)a.W;
     const uint64_t thread_byte = (uint64_t)t * (4u * BITS);
 
-    Sum sum{ptrs, a.W};
+    uint32_t bidx = 0u;
+    uint64_t boundary = 0u;   // first chunk of the bucket after bidx
+    auto view_of = [&](uint64_t p) -> DecodeView {
+        if constexpr (BATCH) {
+            while (bidx + 1u < batch.count && p >= batch_record(batch, bidx + 1u)->chunk0) ++bidx;
+            ConstRecordPtr r = batch_record(batch, bidx);
+            boundary = bidx + 1u < batch.count ? batch_record(batch, bidx + 1u)->chunk0 : ~0ull;
+            ConstU64Ptr pp = (ConstU64Ptr)(r + 1) + a.W;   // the payload pointers follow the gradient pointers
+            return DecodeView{r->n, r->chunk0, r->key0, r->key1, r->scale, r->out, pp};
+        } else {
+            return DecodeView{a.n, 0u, a.key0, a.key1, a.scale, a.out, nullptr};
+        }
+    };
+
+    if (blockIdx.x >= a.chunks) return;
+    DecodeView cur = view_of(blockIdx.x);
+    Sum sum{ptrs, cur.pp, a.W};
     sum.clear();
-    if (blockIdx.x < a.chunks) {   // the first chunk's payload, without overlap
-        const uint64_t byte0 = (((uint64_t)blockIdx.x << kChunkLog2) * BITS) / 8u + thread_byte;
+    {   // the first chunk's payload, without overlap
+        const uint64_t byte0 = (((blockIdx.x - cur.chunk0) << kChunkLog2) * BITS) / 8u + thread_byte;
         for (uint32_t g = 0; g < sum.groups(); ++g) {
             sum.issue(byte0, g);
             sum.add(g);
         }
     }
     for (uint64_t p = blockIdx.x; p < a.chunks; p += gridDim.x) {
-        const uint64_t g0 = p << kChunkLog2;
-        const uint64_t left = a.n - g0;
+        const uint64_t pl = p - cur.chunk0;      // the chunk's number inside its bucket
+        const uint64_t g0 = pl << kChunkLog2;
+        const uint64_t left = cur.n - g0;
         const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
         __syncthreads();   // the previous item's last reads of the buffer and sign table are done
-        fill_sign_table<true, false>(sh.sign[0], g0, a.key0, a.key1, t);
+        fill_sign_table<true, false>(sh.sign[0], g0, cur.key0, cur.key1, t);
 
         // sums -> rotated-domain estimate of the mean, layout L1
-        const float s = a.scale[p];
+        const float s = cur.scale[pl];
         const float step = (s + s) / Lf;
         const float qf = step / Wf;
         float v[kRegs];
@@ -379,7 +470,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
 #pragma unroll
         for (int r = 0; r < kRegs; ++r) v[r] = (float)S[r] * qf - s;
 
-        if (a.sums) {   // the caller also wants the integer aggregate
+        if (!BATCH && a.sums) {   // the caller also wants the integer aggregate
             if (BITS == 8) {
                 uint16_t* dst = static_cast<uint16_t*>(a.sums) + g0 + 32u * t;
 #pragma unroll
@@ -404,7 +495,11 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
 
         // the next chunk's payload arrives while this one rotates
         const uint64_t pn = p + gridDim.x;
-        NextChunkLoads<BITS> next{sum, ((pn << kChunkLog2) * BITS) / 8u + thread_byte, pn < a.chunks};
+        const bool more = pn < a.chunks;
+        DecodeView nxt = cur;
+        if (BATCH && more && pn >= boundary) nxt = view_of(pn);   // rarely: a new bucket
+        sum.pp = nxt.pp;
+        NextChunkLoads<BITS, BATCH> next{sum, (((pn - nxt.chunk0) << kChunkLog2) * BITS) / 8u + thread_byte, more};
         sum.clear();
         rotate_l1_to_l3<false>(sh, v, lane, wave, next);
         if (next.active) {
@@ -415,7 +510,8 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
             }
         }
         l3_to_l4d<false>(sh, v, lane, wave);
-        store_signed_l4d(sh.sign[0], v, a.out + g0, valid, t);
+        store_signed_l4d(sh.sign[0], v, cur.out + g0, valid, t);
+        cur = nxt;
     }
 }
 
@@ -635,9 +731,10 @@ uint32_t resident_grid() {
     return cached;
 }
 
-template <bool BF16, int BITS, bool ODD>
-hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid<encode_all_kernel<BF16, BITS, ODD>>();
+template <bool BF16, int BITS, bool ODD, bool BATCH>
+hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, const BatchArgs& batch,
+                               hipStream_t stream) {
+    uint32_t G = resident_grid<encode_all_kernel<BF16, BITS, ODD, BATCH>>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
@@ -645,7 +742,45 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
     // fewer resident workgroups than workers would leave peers that never run
     if (G < a.W) return hipErrorInvalidConfiguration;
     G -= G % a.W;
-    hipLaunchKernelGGL((encode_all_kernel<BF16, BITS, ODD>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    hipLaunchKernelGGL((encode_all_kernel<BF16, BITS, ODD, BATCH>), dim3(G), dim3(kThreads), 0, stream, a, ptrs,
+                       batch);
+    return hipGetLastError();
+}
+
+template <bool BATCH>
+hipError_t launch_encode_all_pick(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, const BatchArgs& batch,
+                                  bool bf16, bool odd, uint32_t bits, hipStream_t stream) {
+    if (bf16 && odd) {   // an odd count of bf16 somewhere: element-wise loader for the last coordinate
+        if (bits == 2) return launch_encode_all_t<true, 2, true, BATCH>(a, ptrs, batch, stream);
+        if (bits == 4) return launch_encode_all_t<true, 4, true, BATCH>(a, ptrs, batch, stream);
+        return launch_encode_all_t<true, 8, true, BATCH>(a, ptrs, batch, stream);
+    }
+    if (bf16) {
+        if (bits == 2) return launch_encode_all_t<true, 2, false, BATCH>(a, ptrs, batch, stream);
+        if (bits == 4) return launch_encode_all_t<true, 4, false, BATCH>(a, ptrs, batch, stream);
+        return launch_encode_all_t<true, 8, false, BATCH>(a, ptrs, batch, stream);
+    }
+    if (bits == 2) return launch_encode_all_t<false, 2, false, BATCH>(a, ptrs, batch, stream);
+    if (bits == 4) return launch_encode_all_t<false, 4, false, BATCH>(a, ptrs, batch, stream);
+    return launch_encode_all_t<false, 8, false, BATCH>(a, ptrs, batch, stream);
+}
+
+template <bool BATCH>
+hipError_t launch_aggregate_decode_pick(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, const BatchArgs& batch,
+                                        uint32_t bits, hipStream_t stream) {
+    if (a.chunks == 0) return hipSuccess;
+    uint32_t G = 0;
+    if (bits == 2) G = resident_grid<aggregate_decode_kernel<2, BATCH>>();
+    else if (bits == 4) G = resident_grid<aggregate_decode_kernel<4, BATCH>>();
+    else G = resident_grid<aggregate_decode_kernel<8, BATCH>>();
+    if (G == 0) return hipErrorInvalidValue;
+    if (G > a.chunks) G = (uint32_t)a.chunks;
+    if (bits == 2)
+        hipLaunchKernelGGL((aggregate_decode_kernel<2, BATCH>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, batch);
+    else if (bits == 4)
+        hipLaunchKernelGGL((aggregate_decode_kernel<4, BATCH>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, batch);
+    else
+        hipLaunchKernelGGL((aggregate_decode_kernel<8, BATCH>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, batch);
     return hipGetLastError();
 }
 
@@ -657,12 +792,12 @@ uint32_t encode_all_slot_words(uint32_t W) { return k14::kWaves * W; }
 // Workgroups of the one-pass encoder that the device keeps resident at once.
 static uint32_t encode_all_resident(bool bf16, uint32_t bits) {
     using namespace k14;
-    if (bf16) return bits == 2 ? resident_grid<encode_all_kernel<true, 2, false>>()
-                   : bits == 4 ? resident_grid<encode_all_kernel<true, 4, false>>()
-                               : resident_grid<encode_all_kernel<true, 8, false>>();
-    return bits == 2 ? resident_grid<encode_all_kernel<false, 2, false>>()
-         : bits == 4 ? resident_grid<encode_all_kernel<false, 4, false>>()
-                     : resident_grid<encode_all_kernel<false, 8, false>>();
+    if (bf16) return bits == 2 ? resident_grid<encode_all_kernel<true, 2, false, false>>()
+                   : bits == 4 ? resident_grid<encode_all_kernel<true, 4, false, false>>()
+                               : resident_grid<encode_all_kernel<true, 8, false, false>>();
+    return bits == 2 ? resident_grid<encode_all_kernel<false, 2, false, false>>()
+         : bits == 4 ? resident_grid<encode_all_kernel<false, 4, false, false>>()
+                     : resident_grid<encode_all_kernel<false, 8, false, false>>();
 }
 
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t chunk_log2,
@@ -692,20 +827,25 @@ hipError_t launch_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stre
 
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
                                    uint32_t bits, hipStream_t stream) {
-    using namespace k14;
-    if (bf16 && (a.n & 1u)) {   // odd count of bf16: element-wise loader for the last coordinate
-        if (bits == 2) return launch_encode_all_t<true, 2, true>(a, ptrs, stream);
-        if (bits == 4) return launch_encode_all_t<true, 4, true>(a, ptrs, stream);
-        return launch_encode_all_t<true, 8, true>(a, ptrs, stream);
+    return k14::launch_encode_all_pick<false>(a, ptrs, BatchArgs{}, bf16, (a.n & 1u) != 0u, bits, stream);
+}
+
+hipError_t launch_encode_all_batch(const EncodeAllArgs& a, const BatchArgs& batch, bool bf16, bool any_odd,
+                                   uint32_t bits, hipStream_t stream) {
+    return k14::launch_encode_all_pick<true>(a, FusedWorkerPtrs{}, batch, bf16, any_odd, bits, stream);
+}
+
+hipError_t launch_write_words(uint32_t* dst, const uint32_t* host_words, uint32_t count, hipStream_t stream) {
+    // the words travel as kernel arguments, kBlobWords at a time
+    for (uint32_t done = 0; done < count; done += (uint32_t)kBlobWords) {
+        k14::WordBlob blob;
+        const uint32_t now = count - done < (uint32_t)kBlobWords ? count - done : (uint32_t)kBlobWords;
+        for (uint32_t i = 0; i < now; ++i) blob.w[i] = host_words[done + i];
+        hipLaunchKernelGGL(k14::write_words_kernel, dim3(1), dim3(256), 0, stream, dst + done, blob, now);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    if (bf16) {
-        if (bits == 2) return launch_encode_all_t<true, 2, false>(a, ptrs, stream);
-        if (bits == 4) return launch_encode_all_t<true, 4, false>(a, ptrs, stream);
-        return launch_encode_all_t<true, 8, false>(a, ptrs, stream);
-    }
-    if (bits == 2) return launch_encode_all_t<false, 2, false>(a, ptrs, stream);
-    if (bits == 4) return launch_encode_all_t<false, 4, false>(a, ptrs, stream);
-    return launch_encode_all_t<false, 8, false>(a, ptrs, stream);
+    return hipSuccess;
 }
 
 bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
@@ -720,21 +860,12 @@ bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t
 
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                          uint32_t bits, hipStream_t stream) {
-    using namespace k14;
-    if (a.chunks == 0) return hipSuccess;
-    uint32_t G = 0;
-    if (bits == 2) G = resident_grid<aggregate_decode_kernel<2>>();
-    else if (bits == 4) G = resident_grid<aggregate_decode_kernel<4>>();
-    else G = resident_grid<aggregate_decode_kernel<8>>();
-    if (G == 0) return hipErrorInvalidValue;
-    if (G > a.chunks) G = (uint32_t)a.chunks;
-    if (bits == 2)
-        hipLaunchKernelGGL(aggregate_decode_kernel<2>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
-    else if (bits == 4)
-        hipLaunchKernelGGL(aggregate_decode_kernel<4>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
-    else
-        hipLaunchKernelGGL(aggregate_decode_kernel<8>, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
-    return hipGetLastError();
+    return k14::launch_aggregate_decode_pick<false>(a, ptrs, BatchArgs{}, bits, stream);
+}
+
+hipError_t launch_aggregate_decode_batch(const AggDecodeArgs& a, const BatchArgs& batch, uint32_t bits,
+                                         hipStream_t stream) {
+    return k14::launch_aggregate_decode_pick<true>(a, FusedPayloadPtrs{}, batch, bits, stream);
 }
 
 bool sat_aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2) {

@@ -71,6 +71,31 @@ struct EncodeAllArgs {
     uint32_t* done;      // zero on entry and on exit: one arrival counter per chunk
     uint32_t* error;     // zeroed: set to 1 if a wait timed out
 };
+// ---- batched forms: several buckets in one launch ---------------------------------------
+// One record per bucket in device memory, followed by the bucket's W gradient pointers and
+// its W payload pointers; the records are sorted by chunk0.
+struct BatchRecord {
+    uint64_t n;         // coordinates of the bucket (> 0)
+    uint64_t chunk0;    // chunks of all earlier buckets of the launch
+    uint32_t key0, key1;
+    float* scale;
+    float* out;         // decode only
+};
+inline uint32_t batch_record_bytes(uint32_t W) { return (uint32_t)sizeof(BatchRecord) + 16u * W; }
+struct BatchArgs {
+    const uint8_t* records;
+    uint32_t record_bytes;
+    uint32_t count;
+};
+constexpr int kBlobWords = 832;   // 32-bit words one launch of the record writer carries as arguments
+// dst[0 .. count) = host_words[0 .. count), by small kernels that take the words as arguments.
+hipError_t launch_write_words(uint32_t* dst, const uint32_t* host_words, uint32_t count, hipStream_t stream);
+// a.n is unused, a.chunks the total over the buckets, a.scale unused.
+hipError_t launch_encode_all_batch(const struct EncodeAllArgs& a, const BatchArgs& batch, bool bf16, bool any_odd,
+                                   uint32_t bits, hipStream_t stream);
+hipError_t launch_aggregate_decode_batch(const struct AggDecodeArgs& a, const BatchArgs& batch, uint32_t bits,
+                                         hipStream_t stream);
+
 // Words per chunk in `slots`: one for every wave of every worker's workgroup.
 uint32_t encode_all_slot_words(uint32_t W);
 bool encode_all_fused_applicable(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs,
