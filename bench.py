@@ -237,22 +237,103 @@ def time_region(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+def time_steps(torch, fn, steps):
+    """Exactly `steps` repetitions of fn(), bracketed by synchronisation on both sides, with
+    one HIP event between consecutive repetitions (no synchronisation in between).
+    Returns (median, mean, min, max) of the per-step times in milliseconds."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(steps):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    med = t[steps // 2] if steps % 2 else 0.5 * (t[steps // 2 - 1] + t[steps // 2])
+    return med, ev[0].elapsed_time(ev[steps]) / steps, t[0], t[-1]
+
+
+_POOL_INPUT = None
+
+
+def _oracle_pool_init(shm_name, W, m, np_dtype):
+    """Pool initializer of the all-cores leg: map the parent's copy of the sample."""
+    global _POOL_INPUT
+    from multiprocessing import shared_memory
+
+    import numpy as np
+    shm = shared_memory.SharedMemory(name=shm_name)
+    _POOL_INPUT = (shm, np.ndarray((W, m), dtype=np.dtype(np_dtype), buffer=shm.buf))
+
+
+def _oracle_slice(args):
+    """Pool worker of the all-cores leg: the oracle on one slice (whole chunks) of every
+    worker's sample."""
+    import numpy as np
+
+    from oracle import thc as O
+    g0, piece, chunk_log2, bits, bf16 = args
+    x = _POOL_INPUT[1]
+    O.pipeline([x[w, g0:g0 + piece] for w in range(x.shape[0])], chunk_log2, 0, bits,
+               dtype=np.float32, bf16=bf16, g0=g0)
+    return piece
+
+
 def cpu_baseline(wl, bits, xs, log2_sample):
-    """The NumPy oracle (float32 canonical-order mode), as it stands, on the first
-    2^log2_sample coordinates of every worker; single process."""
+    """The NumPy oracle (float32 canonical-order mode), as it stands, on the first coordinates
+    of every worker: once in this process (NumPy runs these operations on one thread), once
+    with a process pool over slices of whole chunks on the host cores this job may use."""
+    import multiprocessing as mp
+
     import numpy as np
 
     from oracle import thc as O
     from synth import to_numpy_bits
+    s_in = 2 if wl.dtype == "bf16" else 4
+    bf16 = wl.dtype == "bf16"
     m = min(wl.n, 1 << log2_sample)
     hx = [to_numpy_bits(x[:m]) for x in xs]
     t0 = time.perf_counter()
-    O.pipeline(hx, wl.chunk_log2, 0, bits, dtype=np.float32, bf16=(wl.dtype == "bf16"))
+    O.pipeline(hx, wl.chunk_log2, 0, bits, dtype=np.float32, bf16=bf16)
     dt = time.perf_counter() - t0
-    s_in = 2 if wl.dtype == "bf16" else 4
-    return dict(value=round(wl.W * m * s_in / dt / 1e9, 5), unit="GB/s", cores=1, kind="oracle",
-                sample=f"first 2^{log2_sample} coordinates of each of the {wl.W} workers "
-                       f"({dt:.1f} s of NumPy, one thread)")
+    res = dict(value=round(wl.W * m * s_in / dt / 1e9, 5), unit="GB/s", cores=1, kind="oracle",
+               sample=f"first 2^{log2_sample} coordinates of each of the {wl.W} workers "
+                      f"({dt:.1f} s of NumPy, one thread)")
+    # all cores: the job's share of the host is 16 threads whatever the machine reports
+    cores = max(1, min(os.cpu_count() or 1, 16))
+    piece = 1 << 21                              # 128 chunks of 2^14 per task
+    m_all = min(wl.n, max(m, piece * cores * 2)) // piece * piece
+    if cores > 1 and m_all >= 2 * piece:
+        from multiprocessing import shared_memory
+        first = to_numpy_bits(xs[0][:m_all])
+        shm = shared_memory.SharedMemory(create=True, size=wl.W * m_all * first.itemsize)
+        try:
+            host = np.ndarray((wl.W, m_all), dtype=first.dtype, buffer=shm.buf)
+            host[0] = first
+            for w in range(1, wl.W):
+                host[w] = to_numpy_bits(xs[w][:m_all])
+            tasks = [(g, piece, wl.chunk_log2, bits, bf16) for g in range(0, m_all, piece)]
+            ctx = mp.get_context("spawn")            # the parent holds a GPU context: no fork
+            # an executor, not multiprocessing.Pool: a worker that dies ends the run with
+            # an error instead of being replaced for ever
+            from concurrent.futures import ProcessPoolExecutor
+            with ProcessPoolExecutor(cores, mp_context=ctx, initializer=_oracle_pool_init,
+                                     initargs=(shm.name, wl.W, m_all, first.dtype.str)) as pool:
+                list(pool.map(_oracle_slice,
+                              [(0, 1 << wl.chunk_log2, wl.chunk_log2, bits, bf16)] * cores))   # start-up, untimed
+                t0 = time.perf_counter()
+                done = sum(pool.map(_oracle_slice, tasks))
+                dt_all = time.perf_counter() - t0
+            del host
+        finally:
+            shm.close()
+            shm.unlink()
+        res["all_cores"] = dict(value=round(wl.W * done * s_in / dt_all / 1e9, 5), unit="GB/s", cores=cores,
+                                host_cpu_count=os.cpu_count(),
+                                kind="oracle, process pool over slices of 2^21 coordinates",
+                                sample=f"first {done} coordinates of each of the {wl.W} workers "
+                                       f"({dt_all:.1f} s wall)")
+    return res
 
 
 def copy_bandwidth(torch, dev):
@@ -471,7 +552,7 @@ def main():
 
     for _ in range(a.warmup):
         path.step()
-    ms = time_region(torch, path.step, a.steps)
+    ms, ms_mean, ms_min, ms_max = time_steps(torch, path.step, a.steps)
     assert not path.timed_out(), "a bounded wait inside thc_encode_all expired"
 
     # per-kernel launch durations, live, on the same stream
@@ -523,6 +604,9 @@ def main():
     # sums for the exact path, b bits for the saturating one
     agg_bytes = bits / 8.0 if a.sat else sb
     alg_bytes_per_coord = W * (s_in + bits / 8.0) + W * bits / 8.0 + 2 * agg_bytes + 4
+    moved_bytes_per_coord = alg_bytes_per_coord - (2 * agg_bytes if (path.fused and path.no_sums) else 0)
+    if a.full_rotation:
+        moved_bytes_per_coord = alg_bytes_per_coord
     value = W * wl.n * s_in / (ms * 1e-3) / 1e9
     res = {
         "metric": "gradient GB/s for encode+aggregate+decode (W workers) and % of HBM peak, 1 GPU",
@@ -532,8 +616,14 @@ def main():
         "config": {"workload": wl.name, "W": W, "n": wl.n, "input": wl.dtype, "bits": bits,
                    "chunk_log2": wl.chunk_log2, "buckets": nb, "bucket_elems": wl.bucket or wl.n,
                    "form": "fused" if path.fused else "unfused",
+                   "launches": "one thc_encode_all_cleared + one thc_aggregate_decode per bucket"
+                               if path.fused else "one call per step of the method",
                    "aggregation": "saturating" if a.sat else "exact",
-                   "rotation": f"full, 2^{path.l}" if a.full_rotation else "partial"},
+                   "rotation": f"full, 2^{path.l}" if a.full_rotation else "partial",
+                   "philox_seed": 0 if a.full_rotation else "bucket index (0 .. buckets - 1)",
+                   "data_seed": "1000 * configuration + worker"},
+        "step_time_ms": {"statistic": "median of per-step HIP-event pairs", "median": round(ms, 4),
+                         "mean": round(ms_mean, 4), "min": round(ms_min, 4), "max": round(ms_max, 4)},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(wl.name, bits, dom_name)},
@@ -547,7 +637,11 @@ def main():
         "pipeline_hbm": {"algorithmic_bytes_per_coord": alg_bytes_per_coord,
                          "achieved_GBps": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                         "frac_of_copy": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / copy_gbs, 4)},
+                         "frac_of_copy": round(wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / copy_gbs, 4),
+                         # what the timed calls really move: the fused decoder never stores the sums
+                         "moved_bytes_per_coord": moved_bytes_per_coord,
+                         "moved_GBps": round(wl.n * moved_bytes_per_coord / (ms * 1e-3) / 1e9, 1),
+                         "moved_frac_of_peak": round(wl.n * moved_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "kernels": kernels,
     }
     if a.full_rotation:
@@ -560,6 +654,29 @@ def main():
         res["vnmse"] = float(((path.out - mean) ** 2).sum() / (mean ** 2).sum())
     if path.fused and not a.sat:
         res["vnmse_first_bucket"] = vnmse(torch, path, path.items[0])
+    if path.fused and not a.sat and not a.full_rotation and nb > 1 and wl.chunk_log2 == 14 and path.no_sums:
+        # the same step through the batched entry points: every bucket in one call of each
+        # kind (outputs are byte-identical; reported beside the per-bucket form, which stays
+        # the headline because it is the form a bucket-at-a-time caller uses)
+        bk = [dict(grads=it["grads"], payloads=it["payloads"], scale=it["scale"], out=it["out"],
+                   n=it["ln"], seed=it["seed"]) for it in path.items]
+        wsb = torch.empty(thc.thc_batch_workspace_bytes([it["ln"] for it in path.items], W, wl.chunk_log2),
+                          dtype=torch.uint8, device=dev)
+        ref_out = path.items[-1]["out"].clone()
+
+        def batched():
+            thc.thc_encode_all_batch(bk, wl.chunk_log2, bits, wsb)
+            thc.thc_aggregate_decode_batch(bk, wl.chunk_log2, bits, wsb)
+        batched()
+        torch.cuda.synchronize()
+        assert not thc.thc_encode_all_timed_out(wsb) and torch.equal(ref_out, path.items[-1]["out"])
+        b_med, b_mean, b_min, b_max = time_steps(torch, batched, max(3, a.steps // 2))
+        enc_b = time_region(torch, lambda: thc.thc_encode_all_batch(bk, wl.chunk_log2, bits, wsb), 3)
+        dec_b = time_region(torch, lambda: thc.thc_aggregate_decode_batch(bk, wl.chunk_log2, bits, wsb), 3)
+        res["batched"] = {"form": "thc_encode_all_batch + thc_aggregate_decode_batch, all buckets per call",
+                          "ms_per_step": round(b_med, 4), "value": round(W * wl.n * s_in / (b_med * 1e-3) / 1e9, 2),
+                          "pct_hbm_peak": round(100.0 * wl.n * alg_bytes_per_coord / (b_med * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+                          "encode_ms_per_step": round(enc_b, 4), "decode_ms_per_step": round(dec_b, 4)}
     if a.sat:
         # quality of the variant on the first bucket, next to the exact-sum path's
         it = path.items[0]
