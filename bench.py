@@ -76,6 +76,9 @@ def parse():
     ap.add_argument("--topkc-bits", type=float, default=2.0, help="target bits per coordinate")
     ap.add_argument("--workers", type=int, default=None,
                     help="simulate this many workers instead of the workload's own W")
+    ap.add_argument("--first-buckets", type=int, default=None,
+                    help="keep only the first K buckets of every worker's gradient (quality runs "
+                         "with many workers; not the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="few launches + a copy of known size, for rocprofv3 --pmc runs")
@@ -525,7 +528,13 @@ def main():
     s_in = 2 if wl.dtype == "bf16" else 4
     W = wl.W
 
-    xs = [generate(wl, w, dev) for w in range(W)]
+    if a.first_buckets:
+        keep = min(wl.n, a.first_buckets * (wl.bucket or wl.n))
+        xs = [generate(wl, w, dev)[:keep].clone() for w in range(W)]
+        import dataclasses
+        wl = dataclasses.replace(wl, n=keep, name=f"{wl.name}[first {a.first_buckets} buckets]")
+    else:
+        xs = [generate(wl, w, dev) for w in range(W)]
     if a.quality:
         print(json.dumps(quality(thc, torch, wl, bits, xs, dev)))
         return 0
@@ -565,6 +574,27 @@ def main():
         t = time_region(torch, run, max(2, a.steps // 2))
         kernels[name] = dict(ms_per_step=round(t, 4), launches_per_step=nb * per_bucket,
                              us_per_launch=round(1e3 * t / (nb * per_bucket), 3))
+
+    # The same launches timed inside whole steps (an event after every phase of every bucket):
+    # a kernel that reads what the previous one just wrote finds part of it in the 256 MB
+    # last-level cache, so its duration there differs from that of the back-to-back loop above.
+    if not a.full_rotation:
+        tot = dict.fromkeys(path.phases, 0.0)
+        reps = 3
+        for _ in range(reps):
+            evs = [torch.cuda.Event(enable_timing=True)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for it in path.items:
+                for fn, _ in path.phases.values():
+                    fn(it)
+                    evs.append(torch.cuda.Event(enable_timing=True))
+                    evs[-1].record()
+            torch.cuda.synchronize()
+            for i, name in enumerate(list(path.phases) * nb):
+                tot[name] += evs[i].elapsed_time(evs[i + 1])
+        for name, (_, per_bucket) in path.phases.items():
+            kernels[name]["us_per_launch_in_step"] = round(1e3 * tot[name] / (reps * nb * per_bucket), 3)
 
     # Dominant kernel and its algorithmic bytes per launch.  Per worker-coordinate the
     # encode step must read the gradient once and write its payload once.
