@@ -50,7 +50,10 @@
 extern "C" {
 #endif
 
-typedef enum { THC_F32 = 0, THC_BF16 = 1 } thc_dtype;
+/* Element type of a gradient buffer.  A plain int at the boundary, so that a caller's
+ * out-of-range value is an error code (THC_ERR_DTYPE), not undefined behaviour. */
+typedef int thc_dtype;
+enum { THC_F32 = 0, THC_BF16 = 1 };
 
 typedef enum {
     THC_OK = 0,

@@ -186,3 +186,63 @@ def test_sat_entry_points_validate_on_the_host(L):
     assert L.thc_sat_aggregate_decode_is_fused(8, 14, 4) == 1
     assert L.thc_sat_aggregate_decode_is_fused(8, 10, 4) == 0
     assert L.thc_sat_aggregate_decode_is_fused(65, 14, 4) == 0
+
+
+def test_batched_and_static_entry_points_validate_on_the_host(L):
+    """Every call below fails validation, or has nothing to do, before any HIP call."""
+    p = ctypes.c_void_p(0x1000)
+    nul = ctypes.c_void_p(0)
+    F32, BF16 = thc.THC_F32, thc.THC_BF16
+
+    def buckets(*ns, ptr=0x1000, W=4):
+        arr = (thc.binding.ThcBucket * max(len(ns), 1))()
+        keep = []
+        for i, n in enumerate(ns):
+            g = (ctypes.c_void_p * W)(*([ptr] * W))
+            q = (ctypes.c_void_p * W)(*([ptr] * W))
+            keep += [g, q]
+            arr[i].grads = ctypes.cast(g, type(arr[i].grads))
+            arr[i].payloads = ctypes.cast(q, type(arr[i].payloads))
+            arr[i].scale = 0x1000
+            arr[i].out = 0x1000
+            arr[i].n = n
+            arr[i].seed = i
+        return keep, arr
+
+    keep, one = buckets(100)
+    # sizes: 16-byte header, one record of 40 + 16 W bytes rounded up to 16, (8 W + 1) words per chunk
+    assert L.thc_batch_workspace_bytes(one, 1, 4, 14) == 16 + 112 + 4 * (8 * 4 + 1)
+    assert L.thc_batch_workspace_bytes(one, 1, 4, 10) == 0
+    assert L.thc_batch_workspace_bytes(one, 0, 4, 14) == 16
+    for fn, extra in ((L.thc_encode_all_batch, (F32,)), (L.thc_aggregate_decode_batch, ())):
+        def call(arr, count, W, l, bits, ws, ws_bytes):
+            return fn(arr, count, *extra, W, l, bits, ws, ws_bytes, nul)
+        assert call(one, 1, 4, 10, 4, p, 1 << 20) == -3          # chunk size
+        assert call(one, 1, 4, 14, 3, p, 1 << 20) == -2          # bits
+        assert call(one, 1, 0, 14, 4, p, 1 << 20) == -4          # workers
+        assert call(one, 1, 65, 14, 2, p, 1 << 20) == -4
+        assert call(one, 4097, 4, 14, 4, p, 1 << 20) == -6       # too many buckets
+        assert call(ctypes.cast(nul, ctypes.POINTER(thc.binding.ThcBucket)), 1, 4, 14, 4, p, 1 << 20) == -1
+        assert call(one, 1, 4, 14, 4, nul, 1 << 20) == -1        # workspace
+        assert call(one, 1, 4, 14, 4, ctypes.c_void_p(0x1004), 1 << 20) == -8
+        assert call(one, 1, 4, 14, 4, p, 16) == -6               # workspace too small
+        assert call(one, 0, 4, 14, 4, nul, 0) == 0               # nothing to do
+        keep0, empty = buckets(0, 0)
+        assert call(empty, 2, 4, 14, 4, nul, 0) == 0
+        keep1, odd = buckets(100, ptr=0x1008)
+        assert call(odd, 1, 4, 14, 4, p, 1 << 20) == -8          # unaligned bucket pointers
+    assert L.thc_encode_all_batch(one, 1, 9, 4, 14, 4, p, 1 << 20, nul) == -5
+    assert L.thc_aggregate_decode_batch(one, 1, 18, 14, 4, p, 1 << 20, nul) == -4   # sums need 16 bits: not fused
+
+    # static-scratch form
+    g = (ctypes.c_void_p * 4)(*([0x1000] * 4))
+    pg = ctypes.cast(g, ctypes.POINTER(ctypes.c_void_p))
+    assert thc.THC_STATIC_SCRATCH_BYTES == 2 << 20
+    assert L.thc_encode_all_static(pg, F32, 4, 100, 15, 0, 4, pg, p, nul, nul) == -3
+    assert L.thc_encode_all_static(pg, 5, 4, 100, 14, 0, 4, pg, p, nul, nul) == -5
+    assert L.thc_encode_all_static(pg, F32, 4, 100, 14, 0, 7, pg, p, nul, nul) == -2
+    assert L.thc_encode_all_static(pg, F32, 0, 100, 14, 0, 4, pg, p, nul, nul) == -4
+    assert L.thc_encode_all_static(pg, BF16, 4, 0, 14, 0, 4, pg, p, nul, nul) == 0
+    assert L.thc_encode_all_static(pg, F32, 4, 100, 14, 0, 4, pg, p, ctypes.c_void_p(0x1002), nul) == -8
+    big = ((2 << 20) // (4 * (8 * 4 + 1)) + 1) * (1 << 14)       # one chunk more than the array has words for
+    assert L.thc_encode_all_static(pg, F32, 4, big, 14, 0, 4, pg, p, nul, nul) == -6
