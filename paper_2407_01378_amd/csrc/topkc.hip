@@ -293,6 +293,73 @@ __global__ __launch_bounds__(256) void scatter_kernel(const uint16_t* values, co
     }
 }
 
+// The dense estimate in ONE pass over the output: every coordinate is written exactly once,
+// float(value) / W inside the selected chunks and 0 elsewhere.  `indices` is ascending, so a
+// workgroup that owns a contiguous range of chunks finds its first selected chunk by one
+// binary search and then walks the list: per tile of kTileChunks chunks, thread t looks at
+// indices[j + t] and, if that chunk lies in the tile, records its rank j + t for the
+// chunk; no more than kTileChunks selected chunks can lie in a tile, so one look per thread
+// sees them all.  `out` must be 16-byte aligned.
+constexpr int kScatterThreads = 256;
+constexpr int kTileChunks = kScatterThreads;
+__global__ __launch_bounds__(kScatterThreads) void scatter_dense_kernel(
+    const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C, uint32_t W, uint64_t n, uint64_t P,
+    uint64_t chunks_per_group, float* out) {
+    __shared__ int32_t rank[kTileChunks];
+    __shared__ uint32_t first;
+    const uint32_t t = threadIdx.x;
+    const uint64_t begin = (uint64_t)blockIdx.x * chunks_per_group;
+    if (begin >= P) return;
+    const uint64_t end = begin + chunks_per_group < P ? begin + chunks_per_group : P;
+    if (t == 0) {   // first j with indices[j] >= begin
+        uint32_t lo = 0, hi = J;
+        while (lo < hi) {
+            const uint32_t mid = lo + (hi - lo) / 2u;
+            if ((uint64_t)indices[mid] < begin) lo = mid + 1u;
+            else hi = mid;
+        }
+        first = lo;
+    }
+    __syncthreads();
+    uint32_t j = first;
+    const float Wf = (float)W;
+    const uint32_t units_per_chunk = C / 4u;            // 16-byte units of fp32 output per chunk
+    const uint32_t shift = 31u - (uint32_t)__builtin_clz(units_per_chunk);
+    for (uint64_t c0 = begin; c0 < end; c0 += kTileChunks) {
+        const uint64_t c1 = c0 + kTileChunks < end ? c0 + kTileChunks : end;
+        rank[t] = -1;
+        __syncthreads();
+        const uint64_t cand = (uint64_t)j + t < (uint64_t)J ? (uint64_t)indices[j + t] : ~0ull;
+        const bool inside = cand >= c0 && cand < c1;    // cand >= c0 whenever the list is ascending
+        if (inside) rank[cand - c0] = (int32_t)(j + t);
+        j += (uint32_t)__syncthreads_count(inside);     // also orders the writes of rank before its reads
+        const uint64_t unit0 = c0 * units_per_chunk;
+        const uint64_t units = (c1 - c0) * units_per_chunk;
+        for (uint64_t u = t; u < units; u += kScatterThreads) {
+            const uint32_t lc = (uint32_t)(u >> shift);
+            const uint32_t e0 = ((uint32_t)u & (units_per_chunk - 1u)) * 4u;
+            const int32_t r = rank[lc];
+            float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (r >= 0) {
+                const uint2 q = *reinterpret_cast<const uint2*>(values + (uint64_t)(uint32_t)r * C + e0);
+                x[0] = f16_bits_to_f32(q.x & 0xFFFFu) / Wf;
+                x[1] = f16_bits_to_f32(q.x >> 16) / Wf;
+                x[2] = f16_bits_to_f32(q.y & 0xFFFFu) / Wf;
+                x[3] = f16_bits_to_f32(q.y >> 16) / Wf;
+            }
+            const uint64_t g = (unit0 + u) * 4u;
+            if (g + 4u <= n) {
+                store_streaming(out + g, x[0], x[1], x[2], x[3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (g + e < n) out[g + e] = x[e];
+            }
+        }
+        __syncthreads();                                // rank is rewritten by the next tile
+    }
+}
+
 uint32_t blocks_for(uint64_t threads, uint32_t per_block) {
     return (uint32_t)((threads + per_block - 1) / per_block);
 }
@@ -354,6 +421,20 @@ hipError_t launch_topkc_gather_sum(const FusedWorkerPtrs& ptrs, bool bf16, uint3
 
 hipError_t launch_topkc_scatter(const uint16_t* values, const uint32_t* indices, uint32_t J, uint32_t C,
                                 uint32_t W, uint64_t n, float* out, hipStream_t stream) {
+    const uint64_t P = (n + C - 1) / C;
+    if (P == 0) return hipSuccess;
+    if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        // one pass: contiguous ranges of whole tiles, 16 workgroups for each of the 256 CUs
+        const uint64_t tiles = (P + kTileChunks - 1) / kTileChunks;
+        uint64_t groups = 4096u;
+        if (groups > tiles) groups = tiles;
+        const uint64_t chunks_per_group = (tiles + groups - 1) / groups * kTileChunks;
+        groups = (P + chunks_per_group - 1) / chunks_per_group;
+        hipLaunchKernelGGL(scatter_dense_kernel, dim3((uint32_t)groups), dim3(kScatterThreads), 0, stream, values,
+                           indices, J, C, W, n, P, chunks_per_group, out);
+        return hipGetLastError();
+    }
+    // an output that is only 4-byte aligned: fill, then scatter
     hipError_t e = launch_zero_words(reinterpret_cast<uint32_t*>(out), n, stream);
     if (e != hipSuccess) return e;
     const uint64_t threads = (uint64_t)J * (C / 8u);
