@@ -406,10 +406,21 @@ def quality(thc, torch, wl, bits, xs, dev):
         thc.thc_aggregate(payloads, ln, l, bits, sums)
         thc.thc_decode_minmax(sums, rng, W, ln, l, 0, bits, rotate, out)
 
+    ws_mm = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, ln, l), dtype=torch.uint8, device=dev) \
+        if l == 14 and thc.thc_aggregate_decode_is_fused(W, l, bits) else None
+
+    def minmax_one_pass(rotate):
+        thc.thc_encode_all_minmax(grads, l, 0, bits, rotate, payloads, rng, ws_mm)
+        thc.thc_aggregate_decode_minmax(payloads, rng, ln, l, 0, bits, rotate, out)
+
+    variants = [("symmetric_partial_rotation", symmetric)]
+    if ws_mm is not None:
+        variants += [("minmax_partial_rotation", lambda: minmax_one_pass(True)),
+                     ("minmax_no_rotation", lambda: minmax_one_pass(False))]
+    variants += [("minmax_partial_rotation_per_step_calls", lambda: minmax(True)),
+                 ("minmax_no_rotation_per_step_calls", lambda: minmax(False))]
     res = {}
-    for name, fn in (("symmetric_partial_rotation", symmetric),
-                     ("minmax_partial_rotation", lambda: minmax(True)),
-                     ("minmax_no_rotation", lambda: minmax(False))):
+    for name, fn in variants:
         fn()
         ms = time_region(torch, fn, 5)
         err = float(((out - mean) ** 2).sum() / (mean ** 2).sum())

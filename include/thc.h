@@ -361,6 +361,27 @@ int thc_encode_minmax(const void* grad, thc_dtype dt, uint64_t n, uint32_t chunk
 int thc_decode_minmax(const void* sums, const float* range, uint32_t W, uint64_t n, uint32_t chunk_log2,
                       uint64_t seed, uint32_t bits, int rotate, thc_dtype out_dt, void* out, void* stream);
 
+/* One-pass forms of the variant for chunk_log2 == 14 (THC_ERR_CHUNK otherwise), the
+ * counterparts of thc_encode_all / thc_aggregate_decode: every gradient is read once.
+ * The same results, bit for bit, as thc_chunk_minmax + thc_range_reduce + thc_encode_minmax
+ * per worker, and as thc_aggregate + thc_decode_minmax with out_dt = THC_F32.
+ *   grads, payloads   HOST arrays of W (<= 64, THC_ERR_WORKERS) device pointers, 16-byte aligned
+ *   range             2 floats per chunk, written by the encoder ((lo, hi) shared by all workers),
+ *                     read by the decoder; 8-byte aligned
+ *   workspace         thc_encode_all_minmax_workspace_bytes(W, n, 14) bytes, 16-byte aligned, any
+ *                     state (the call clears what it uses; its first 32-bit word is set to 1 if
+ *                     a bounded wait between workgroups expired, as for thc_encode_all)
+ *   out               n fp32 values, 16-byte aligned
+ * The decoder with rotate != 0 accepts the shapes for which thc_aggregate_decode_is_fused is
+ * 1 (THC_ERR_WORKERS otherwise); with rotate == 0 every W up to 64. */
+uint64_t thc_encode_all_minmax_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2);
+int thc_encode_all_minmax(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                          uint64_t seed, uint32_t bits, int rotate, uint8_t* const* payloads, float* range,
+                          void* workspace, uint64_t workspace_bytes, void* stream);
+int thc_aggregate_decode_minmax(const uint8_t* const* payloads, uint32_t W, const float* range, uint64_t n,
+                                uint32_t chunk_log2, uint64_t seed, uint32_t bits, int rotate, float* out,
+                                void* stream);
+
 /* ---- full rotation (l' = l): the baseline the paper's "Partial rotation" paragraph and
  * its THC throughput table compare against ---------------------------------------------
  * The whole gradient, zero-padded to 2^log2_size coordinates (the notation table pads

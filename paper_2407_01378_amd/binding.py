@@ -109,6 +109,15 @@ _SIGNATURES = {
                                          ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
                                          ctypes.c_uint32, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p]),
+    "thc_encode_all_minmax_workspace_bytes": (ctypes.c_uint64, [ctypes.c_uint32, ctypes.c_uint64,
+                                                                ctypes.c_uint32]),
+    "thc_encode_all_minmax": (ctypes.c_int, [_u8pp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint64,
+                                             ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
+                                             _u8pp, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                             ctypes.c_void_p]),
+    "thc_aggregate_decode_minmax": (ctypes.c_int, [_u8pp, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_uint64,
+                                                   ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint32,
+                                                   ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_full_log2": (ctypes.c_uint32, [ctypes.c_uint64]),
     "rht_forward_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
@@ -528,6 +537,35 @@ def thc_decode_minmax(sums, range_, W, n, chunk_log2, seed, bits, rotate, out, s
     _check(lib().thc_decode_minmax(_ptr(sums), _ptr(range_), W, n, chunk_log2, seed, bits,
                                    int(bool(rotate)), _dtype_code(out), _ptr(out), _stream(stream)),
            "thc_decode_minmax")
+    return out
+
+
+def thc_encode_all_minmax_workspace_bytes(W, n, chunk_log2):
+    return lib().thc_encode_all_minmax_workspace_bytes(W, n, chunk_log2)
+
+
+def thc_encode_all_minmax(grads, chunk_log2, seed, bits, rotate, payloads, range_, workspace, stream=None):
+    W = len(grads)
+    n = grads[0].numel()
+    for g in grads:
+        _flat(g)
+        if g.numel() != n or g.dtype != grads[0].dtype:
+            raise ValueError("all workers must have gradients of one size and dtype")
+    keep_g, pg = _ptr_array(grads)
+    keep_p, pp = _ptr_array(payloads)
+    _check(lib().thc_encode_all_minmax(pg, _dtype_code(grads[0]), W, n, chunk_log2, seed, bits,
+                                       int(bool(rotate)), pp, _ptr(range_), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "thc_encode_all_minmax")
+
+
+def thc_aggregate_decode_minmax(payloads, range_, n, chunk_log2, seed, bits, rotate, out, stream=None):
+    W = len(payloads)
+    keep_p, pp = _ptr_array(payloads)
+    _flat(out, torch.float32)
+    _check(lib().thc_aggregate_decode_minmax(pp, W, _ptr(range_), n, chunk_log2, seed, bits,
+                                             int(bool(rotate)), _ptr(out), _stream(stream)),
+           "thc_aggregate_decode_minmax")
     return out
 
 

@@ -924,4 +924,88 @@ int topkc_scatter_mean(const uint16_t* values, const uint32_t* indices, uint32_t
     return finish(thc::launch_topkc_scatter(values, indices, J, C, W, n, out, static_cast<hipStream_t>(stream)));
 }
 
+/* ---- one-pass forms of the min/max variant (chunk_log2 == 14) ---------------------------- */
+uint64_t thc_encode_all_minmax_workspace_bytes(uint32_t W, uint64_t n, uint32_t chunk_log2) {
+    if (chunk_log2 != 14 || n > kMaxCoords || W == 0 || W > (uint32_t)thc::kMaxFusedWorkers) return 0;
+    const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+    return 16 + 4 * ((uint64_t)thc::encode_all_minmax_slot_words(W) + 1u) * chunks;
+}
+
+int thc_encode_all_minmax(const void* const* grads, thc_dtype dt, uint32_t W, uint64_t n, uint32_t chunk_log2,
+                          uint64_t seed, uint32_t bits, int rotate, uint8_t* const* payloads, float* range,
+                          void* workspace, uint64_t workspace_bytes, void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK && chunk_log2 != 14) rc = THC_ERR_CHUNK;
+    if (rc == THC_OK) rc = check_dtype(dt);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0 || W > (uint32_t)thc::kMaxFusedWorkers) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!grads || !payloads || !range || !workspace) return THC_ERR_NULL;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!grads[w] || !payloads[w]) return THC_ERR_NULL;
+        if (!aligned(grads[w], 16) || !aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+    }
+    if (!aligned(range, 8) || !aligned(workspace, 16)) return THC_ERR_ALIGN;
+    if (workspace_bytes < thc_encode_all_minmax_workspace_bytes(W, n, chunk_log2)) return THC_ERR_SIZE;
+    const uint64_t chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+    if (chunks * W >= 0x7FFFFFFFull) return THC_ERR_SIZE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t* words = static_cast<uint32_t*>(workspace);
+    thc::EncodeAllArgs a{};
+    a.n = n;
+    a.chunks = chunks;
+    a.W = W;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.max_spins = g_spin_limit;
+    a.levels = thc::grid_levels(bits, false);
+    a.scale = range;
+    const uint64_t slot_words = (uint64_t)thc::encode_all_minmax_slot_words(W) * chunks;
+    a.error = words;
+    a.slots = words + 4;
+    a.done = words + 4 + slot_words;
+    thc::FusedWorkerPtrs ptrs{};
+    for (uint32_t w = 0; w < W; ++w) {
+        ptrs.grad[w] = grads[w];
+        ptrs.payload[w] = payloads[w];
+    }
+    if (thc::launch_zero_words(words, 4 + slot_words + chunks, st) != hipSuccess) return THC_ERR_HIP;
+    const hipError_t e = thc::launch_encode_all_minmax(a, ptrs, dt == THC_BF16, rotate != 0, bits, st);
+    if (e == hipErrorInvalidConfiguration) return THC_ERR_WORKERS;   // fewer resident workgroups than workers
+    return finish(e);
+}
+
+int thc_aggregate_decode_minmax(const uint8_t* const* payloads, uint32_t W, const float* range, uint64_t n,
+                                uint32_t chunk_log2, uint64_t seed, uint32_t bits, int rotate, float* out,
+                                void* stream) {
+    int rc = check_common(n, chunk_log2);
+    if (rc == THC_OK && chunk_log2 != 14) rc = THC_ERR_CHUNK;
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (thc_sum_bytes(W, bits) == 0 || W > (uint32_t)thc::kMaxFusedPayloads) return THC_ERR_WORKERS;
+    if (rotate && !thc::aggregate_decode_fused_applicable(W, chunk_log2, bits)) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!payloads || !range || !out) return THC_ERR_NULL;
+    thc::FusedPayloadPtrs ptrs{};
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!payloads[w]) return THC_ERR_NULL;
+        if (!aligned(payloads[w], 16)) return THC_ERR_ALIGN;
+        ptrs.p[w] = payloads[w];
+    }
+    if (!aligned(range, 8) || !aligned(out, 16)) return THC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!rotate) return finish(thc::launch_unrotated_aggregate_decode(ptrs, W, range, bits, n, out, st));
+    thc::AggDecodeArgs a{};
+    a.n = n;
+    a.chunks = padded_coords(n, chunk_log2) >> chunk_log2;
+    a.W = W;
+    a.key0 = (uint32_t)seed;
+    a.key1 = (uint32_t)(seed >> 32);
+    a.scale = range;
+    a.sums = nullptr;
+    a.out = out;
+    return finish(thc::launch_aggregate_decode_ranged(a, ptrs, bits, st));
+}
+
 }  // extern "C"

@@ -400,7 +400,8 @@ struct DecodeView {
     ConstU64Ptr pp;      // the bucket's W payload pointers
 };
 
-template <int BITS, bool BATCH>
+// RANGED: `scale` holds (lo, hi) pairs of the min/max grid instead of the symmetric scale.
+template <int BITS, bool BATCH, bool RANGED = false>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kernel(const AggDecodeArgs a,
                                                                        const FusedPayloadPtrs ptrs,
                                                                        const BatchArgs batch) {
@@ -446,8 +447,9 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         fill_sign_table<true, false>(sh.sign[0], g0, cur.key0, cur.key1, t);
 
         // sums -> rotated-domain estimate of the mean, layout L1
-        const float s = cur.scale[pl];
-        const float step = (s + s) / Lf;
+        // symmetric grid: yhat = S q - s;  min/max grid: yhat = S q + lo = S q - (-lo)
+        const float s = RANGED ? -cur.scale[2 * pl] : cur.scale[pl];
+        const float step = (RANGED ? cur.scale[2 * pl + 1] + s : s + s) / Lf;
         const float qf = step / Wf;
         float v[kRegs];
         uint32_t S[kRegs];
@@ -861,6 +863,26 @@ bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                          uint32_t bits, hipStream_t stream) {
     return k14::launch_aggregate_decode_pick<false>(a, ptrs, BatchArgs{}, bits, stream);
+}
+
+// a.scale holds (lo, hi) pairs.
+hipError_t launch_aggregate_decode_ranged(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                          uint32_t bits, hipStream_t stream) {
+    using namespace k14;
+    if (a.chunks == 0) return hipSuccess;
+    uint32_t G = bits == 2   ? resident_grid<aggregate_decode_kernel<2, false, true>>()
+                 : bits == 4 ? resident_grid<aggregate_decode_kernel<4, false, true>>()
+                             : resident_grid<aggregate_decode_kernel<8, false, true>>();
+    if (G == 0) return hipErrorInvalidValue;
+    if (G > a.chunks) G = (uint32_t)a.chunks;
+    const BatchArgs none{};
+    if (bits == 2)
+        hipLaunchKernelGGL((aggregate_decode_kernel<2, false, true>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, none);
+    else if (bits == 4)
+        hipLaunchKernelGGL((aggregate_decode_kernel<4, false, true>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, none);
+    else
+        hipLaunchKernelGGL((aggregate_decode_kernel<8, false, true>), dim3(G), dim3(kThreads), 0, stream, a, ptrs, none);
+    return hipGetLastError();
 }
 
 hipError_t launch_aggregate_decode_batch(const AggDecodeArgs& a, const BatchArgs& batch, uint32_t bits,

@@ -122,6 +122,16 @@ struct AggDecodeArgs {
 bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits);
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                          uint32_t bits, hipStream_t stream);
+// min/max grid: a.scale holds (lo, hi) pairs
+hipError_t launch_aggregate_decode_ranged(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
+                                          uint32_t bits, hipStream_t stream);
+// One-pass encoder of the min/max variant (thc_fused14_minmax.hip): a.scale receives (lo, hi)
+// pairs, a.slots has encode_all_minmax_slot_words(W) words per chunk.
+uint32_t encode_all_minmax_slot_words(uint32_t W);
+hipError_t launch_encode_all_minmax(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16, bool rotate,
+                                    uint32_t bits, hipStream_t stream);
+hipError_t launch_unrotated_aggregate_decode(const FusedPayloadPtrs& ptrs, uint32_t W, const float* range,
+                                             uint32_t bits, uint64_t n, float* out, hipStream_t stream);
 bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes);
 hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
                                  uint64_t payload_bytes, void* sums, hipStream_t stream);

@@ -246,3 +246,37 @@ def test_batched_and_static_entry_points_validate_on_the_host(L):
     assert L.thc_encode_all_static(pg, F32, 4, 100, 14, 0, 4, pg, p, ctypes.c_void_p(0x1002), nul) == -8
     big = ((2 << 20) // (4 * (8 * 4 + 1)) + 1) * (1 << 14)       # one chunk more than the array has words for
     assert L.thc_encode_all_static(pg, F32, 4, big, 14, 0, 4, pg, p, nul, nul) == -6
+
+
+def test_one_pass_minmax_entry_points_validate_on_the_host(L):
+    p = ctypes.c_void_p(0x1000)
+    nul = ctypes.c_void_p(0)
+    F32 = thc.THC_F32
+    g = (ctypes.c_void_p * 4)(*([0x1000] * 4))
+    pg = ctypes.cast(g, ctypes.POINTER(ctypes.c_void_p))
+    odd = (ctypes.c_void_p * 4)(0x1000, 0x1008, 0x1000, 0x1000)
+    podd = ctypes.cast(odd, ctypes.POINTER(ctypes.c_void_p))
+    # two words per wave and worker, one counter per chunk, 16-byte header
+    assert L.thc_encode_all_minmax_workspace_bytes(4, 100, 14) == 16 + 4 * (2 * 8 * 4 + 1)
+    assert L.thc_encode_all_minmax_workspace_bytes(4, 100, 10) == 0
+    assert L.thc_encode_all_minmax_workspace_bytes(65, 100, 14) == 0
+    enc = L.thc_encode_all_minmax
+    assert enc(pg, F32, 4, 100, 10, 0, 4, 1, pg, p, p, 1 << 20, nul) == -3
+    assert enc(pg, 3, 4, 100, 14, 0, 4, 1, pg, p, p, 1 << 20, nul) == -5
+    assert enc(pg, F32, 4, 100, 14, 0, 6, 1, pg, p, p, 1 << 20, nul) == -2
+    assert enc(pg, F32, 0, 100, 14, 0, 4, 1, pg, p, p, 1 << 20, nul) == -4
+    assert enc(pg, F32, 65, 100, 14, 0, 2, 1, pg, p, p, 1 << 20, nul) == -4
+    assert enc(pg, F32, 4, 0, 14, 0, 4, 0, pg, nul, nul, 0, nul) == 0
+    assert enc(pg, F32, 4, 100, 14, 0, 4, 0, pg, nul, p, 1 << 20, nul) == -1
+    assert enc(podd, F32, 4, 100, 14, 0, 4, 0, pg, p, p, 1 << 20, nul) == -8
+    assert enc(pg, F32, 4, 100, 14, 0, 4, 0, pg, ctypes.c_void_p(0x1004), p, 1 << 20, nul) == -8
+    assert enc(pg, F32, 4, 100, 14, 0, 4, 0, pg, p, p, 100, nul) == -6
+    dec = L.thc_aggregate_decode_minmax
+    assert dec(pg, 4, p, 100, 10, 0, 4, 1, p, nul) == -3
+    assert dec(pg, 4, p, 100, 14, 0, 5, 1, p, nul) == -2
+    assert dec(pg, 18, p, 100, 14, 0, 4, 1, p, nul) == -4        # rotated: 16-bit sums are not fused
+    assert dec(pg, 65, p, 100, 14, 0, 2, 0, p, nul) == -4
+    assert dec(pg, 4, p, 0, 14, 0, 4, 1, nul, nul) == 0
+    assert dec(pg, 4, nul, 100, 14, 0, 4, 1, p, nul) == -1
+    assert dec(podd, 4, p, 100, 14, 0, 4, 0, p, nul) == -8
+    assert dec(pg, 4, p, 100, 14, 0, 4, 0, ctypes.c_void_p(0x1004), nul) == -8

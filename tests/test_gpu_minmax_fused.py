@@ -1,0 +1,135 @@
+"""One-pass forms of the min/max-range variant (thc_encode_all_minmax,
+thc_aggregate_decode_minmax) on the GPU: shared ranges and payloads bit-identical to the
+oracle and to the one-call-per-step entry points; fp32 output bit-identical to the fp32
+canonical order and within 1e-5 relative L2 of the float64 definition; error paths."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import thc_minmax as M
+from synth import to_numpy_bits
+
+from gpu_util import DEV
+from test_gpu_minmax import _rand, run_minmax
+
+pytestmark = pytest.mark.gpu
+L14 = 14
+
+
+def run_fused(xs, seed, bits, rotate, fill=0x5A):
+    W, n = len(xs), xs[0].numel()
+    P = thc.thc_num_chunks(n, L14)
+    rng = torch.full((P * 2,), float("nan"), device=DEV)
+    nb = thc.thc_payload_bytes(n, L14, bits)
+    payloads = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    out = torch.full((n,), float("nan"), device=DEV)
+    ws = torch.full((thc.thc_encode_all_minmax_workspace_bytes(W, n, L14),), fill, dtype=torch.uint8, device=DEV)
+    thc.thc_encode_all_minmax(xs, L14, seed, bits, rotate, payloads, rng, ws)
+    thc.thc_aggregate_decode_minmax(payloads, rng, n, L14, seed, bits, rotate, out)
+    torch.cuda.synchronize()
+    assert not thc.thc_encode_all_timed_out(ws)
+    # the workspace comes back clear: header, range words and arrival counters
+    assert int(ws.view(torch.int32).abs().max().item()) == 0
+    return dict(range=rng.view(P, 2), payloads=payloads, out=out)
+
+
+@pytest.mark.parametrize("bits,W,dtype,n,rotate", [
+    (4, 8, torch.bfloat16, (5 << 14) + 8193, True),
+    (4, 8, torch.bfloat16, (5 << 14) + 8193, False),
+    (4, 3, torch.float32, (3 << 14) + 5, True),
+    (4, 3, torch.float32, (3 << 14) + 5, False),
+    (2, 17, torch.bfloat16, (2 << 14) + 77, True),        # odd bf16 count, more workers than a wave has bytes
+    (2, 17, torch.bfloat16, (2 << 14) + 77, False),
+    (8, 2, torch.bfloat16, (2 << 14) + 100, True),
+    (8, 5, torch.float32, 1 << 14, False),
+    (4, 1, torch.float32, 40, True),                      # one worker, one ragged chunk
+    (4, 64, torch.bfloat16, (1 << 14) + 2, False),        # the largest worker count
+    (4, 8, torch.bfloat16, 700 << 14, True),              # more chunks than resident workgroups: several rounds
+    (4, 8, torch.bfloat16, (700 << 14) + 3, False),
+])
+def test_one_pass_minmax_matches_the_oracle_and_the_per_step_calls(bits, W, dtype, n, rotate):
+    print(f"minmax one-pass bits={bits} W={W} dtype={dtype} n={n} rotate={rotate}", flush=True)
+    xs = [_rand(n, dtype, 31 * bits + w, scale=10.0 ** (-2 - (w % 3)), shift=3e-3) for w in range(W)]
+    got = run_fused(xs, 23, bits, rotate)
+    # the per-step entry points on the same inputs
+    if thc.thc_sum_bytes(W, bits):
+        ref_gpu = run_minmax(xs, L14, 23, bits, rotate, torch.float32)
+        assert torch.equal(got["range"], ref_gpu["range"]), "shared ranges differ from the per-step calls"
+        for w in range(W):
+            assert torch.equal(got["payloads"][w], ref_gpu["payloads"][w]), f"payload {w} differs from thc_encode_minmax"
+        assert torch.equal(got["out"], ref_gpu["out"]), "output differs from thc_decode_minmax"
+    if n > (9 << 14):
+        return   # the big shapes are covered by the comparison above and by sampled chunks below
+    ref = M.pipeline_minmax([to_numpy_bits(x) for x in xs], L14, 23, bits, rotate=rotate, dtype=np.float32,
+                            bf16=dtype == torch.bfloat16, out_bf16=False)
+    assert (got["range"].cpu().numpy() == ref["range"]).all(), "shared ranges differ"
+    for w in range(W):
+        same = got["payloads"][w].cpu().numpy() == ref["payloads"][w]
+        assert same.all(), f"payload {w} differs at bytes {np.flatnonzero(~same)[:8]}"
+    out = got["out"].cpu().numpy()
+    assert (out == ref["out"]).all(), "output differs from the fp32 canonical order"
+    d64 = M.decode_minmax(ref["sums"], ref["range"].astype(np.float64), W, n, L14, 23, bits, rotate)
+    assert np.linalg.norm(out - d64) <= 1e-5 * np.linalg.norm(d64)
+
+
+@pytest.mark.parametrize("rotate", [True, False])
+def test_one_pass_minmax_sampled_chunks_of_a_large_gradient(rotate):
+    """700 chunks per worker (several rounds of the persistent grid): the first, the last
+    (ragged) and a few chunks in between against the oracle run on those chunks alone."""
+    bits, W, l = 4, 8, L14
+    n = (700 << l) + 1234
+    xs = [_rand(n, torch.bfloat16, 900 + w, scale=10.0 ** (-1 - (w % 4)), shift=-2e-3) for w in range(W)]
+    got = run_fused(xs, 5, bits, rotate)
+    P = thc.thc_num_chunks(n, l)
+    per = (1 << l) * bits // 8
+    for p in (0, 1, 255, 256, 511, 512, 513, 698, 699, P - 1):
+        g0, g1 = p << l, min(n, (p + 1) << l)
+        ref = M.pipeline_minmax([to_numpy_bits(x[g0:g1]) for x in xs], l, 5, bits, rotate=rotate, dtype=np.float32,
+                                bf16=True, out_bf16=False, g0=g0)
+        assert (got["range"][p].cpu().numpy() == ref["range"][0]).all(), f"range of chunk {p}"
+        for w in range(W):
+            assert (got["payloads"][w][p * per:(p + 1) * per].cpu().numpy() == ref["payloads"][w]).all(), (p, w)
+        assert (got["out"][g0:g1].cpu().numpy() == ref["out"]).all(), f"output of chunk {p}"
+
+
+def test_one_pass_minmax_constant_and_zero_chunks():
+    """A constant chunk has an empty range: every index 0, decoded exactly; an all-zero
+    gradient likewise."""
+    bits, W, n = 4, 4, (2 << 14) + 10
+    xs = [torch.zeros(n, device=DEV) for _ in range(W)]
+    for x in xs:
+        x[:1 << 14] = 0.375
+    got = run_fused(xs, 1, bits, False)
+    assert torch.equal(got["range"][0], torch.tensor([0.375, 0.375], device=DEV))
+    assert torch.equal(got["range"][1], torch.zeros(2, device=DEV))
+    assert all(int(p.max().item()) == 0 for p in got["payloads"])
+    assert torch.equal(got["out"], xs[0])
+    got = run_fused([torch.zeros(n, device=DEV) for _ in range(W)], 1, bits, True)
+    assert int(got["range"].abs().max().item()) == 0 and int(got["out"].abs().max().item()) == 0
+
+
+def test_one_pass_minmax_refuses_what_it_does_not_cover():
+    n, W = 1 << 14, 4
+    xs = [torch.zeros(n, device=DEV) for _ in range(W)]
+    pay = [torch.empty(n // 2, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    rng = torch.empty(2, device=DEV)
+    out = torch.empty(n, device=DEV)
+    ws = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, n, L14), dtype=torch.uint8, device=DEV)
+    assert thc.thc_encode_all_minmax_workspace_bytes(W, n, 10) == 0
+    with pytest.raises(thc.ThcError) as e:
+        thc.thc_encode_all_minmax(xs, 10, 0, 4, True, pay, rng, ws)
+    assert e.value.status == -3
+    with pytest.raises(thc.ThcError) as e:
+        thc.thc_encode_all_minmax(xs, L14, 0, 4, True, pay, rng, ws[:64])
+    assert e.value.status == -6
+    with pytest.raises(thc.ThcError) as e:
+        thc.thc_aggregate_decode_minmax(pay, rng, n, 10, 0, 4, True, out)
+    assert e.value.status == -3
+    with pytest.raises(thc.ThcError) as e:                 # 18 workers of 4 bits need 16-bit sums: not fused
+        thc.thc_aggregate_decode_minmax(pay * 5, rng, n, L14, 0, 4, True, out)
+    assert e.value.status == -4
+    with pytest.raises(thc.ThcError) as e:
+        thc.thc_aggregate_decode_minmax(pay, rng, n, L14, 0, 4, True, torch.empty(n + 1, device=DEV)[1:])
+    assert e.value.status == -8
+    torch.cuda.synchronize()
