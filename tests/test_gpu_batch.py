@@ -93,3 +93,41 @@ def test_batched_calls_refuse_what_they_do_not_cover():
     assert e.value.status == -4
     torch.cuda.synchronize()
     assert thc.thc_batch_workspace_bytes([1 << 14], 4, 10) == 0
+
+
+def test_payloads_do_not_depend_on_which_workgroup_takes_which_chunk():
+    """Determinism under a permuted workgroup order: the same bucket placed after 0, 1, 7 and
+    100 chunks of another bucket in a batched call is handled by other workgroups, in other
+    rounds of the persistent grid and next to other neighbours each time; payloads, scales and
+    outputs must be the same bytes (the random streams are keyed by seed, worker and global
+    coordinate, no result passes through an atomic, and every chunk is reduced in one fixed
+    order)."""
+    l, bits, W = 14, 4, 8
+    n = (37 << l) + 4321
+    xs = [_rand(n, torch.bfloat16, 4000 + w, scale=10.0 ** (-1 - (w % 3))) for w in range(W)]
+    nb = thc.thc_payload_bytes(n, l, bits)
+    P = thc.thc_num_chunks(n, l)
+    seen = None
+    for lead in (0, 1, 7, 100):
+        lead_n = lead << l
+        first = dict(grads=[_rand(lead_n, torch.bfloat16, 77 + w) for w in range(W)] if lead else
+                     [torch.empty(0, dtype=torch.bfloat16, device=DEV) for _ in range(W)],
+                     n=lead_n, seed=9,
+                     payloads=[torch.empty(thc.thc_payload_bytes(lead_n, l, bits), dtype=torch.uint8, device=DEV)
+                               for _ in range(W)],
+                     scale=torch.empty(max(lead, 1), device=DEV), out=torch.empty(max(lead_n, 1), device=DEV))
+        mine = dict(grads=xs, n=n, seed=1234,
+                    payloads=[torch.full((nb,), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(W)],
+                    scale=torch.full((P,), -1.0, device=DEV), out=torch.full((n,), float("nan"), device=DEV))
+        batch = [first, mine]
+        ws = torch.empty(thc.thc_batch_workspace_bytes([lead_n, n], W, l), dtype=torch.uint8, device=DEV)
+        print(f"determinism: bucket of {P} chunks after {lead} chunks", flush=True)
+        thc.thc_encode_all_batch(batch, l, bits, ws)
+        thc.thc_aggregate_decode_batch(batch, l, bits, ws)
+        torch.cuda.synchronize()
+        assert not thc.thc_encode_all_timed_out(ws)
+        got = (torch.cat(mine["payloads"]).clone(), mine["scale"].clone(), mine["out"].clone())
+        if seen is None:
+            seen = got
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(seen, got)), f"results moved with {lead} leading chunks"
