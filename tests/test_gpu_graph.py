@@ -68,3 +68,82 @@ def test_graph_replays_match_eager_calls(cleared):
         for a, b in zip(pay, ref_pay):
             assert torch.equal(a, b)
         assert torch.equal(out, ref_out)
+
+
+def _capture(step):
+    step()                                   # warm-up outside the capture (one-time queries)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()               # default priority
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    return graph
+
+
+@pytest.mark.parametrize("form", ["static", "batch", "minmax"])
+def test_graph_replays_of_the_other_one_launch_forms(form):
+    """thc_encode_all_static (no workspace argument at all), the batched pair (records
+    written by argument-carrying kernels) and the one-pass min/max pair under capture:
+    every replay against the eager per-bucket calls on the same inputs."""
+    l, bits, W = 14, 4, 8
+    ns = [40 * (1 << 14) + 77, 25 << 14] if form == "batch" else [120 * (1 << 14) + 77]
+    xs = [[_rand(n, 7 + w + 50 * k) for w in range(W)] for k, n in enumerate(ns)]
+    pay = [[torch.empty(thc.thc_payload_bytes(n, l, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
+           for n in ns]
+    per_chunk = 2 if form == "minmax" else 1
+    scale = [torch.empty(per_chunk * thc.thc_num_chunks(n, l), device=DEV) for n in ns]
+    out = [torch.empty(n, device=DEV) for n in ns]
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    if form == "static":
+        def step():
+            thc.thc_encode_all_static(xs[0], l, 5, bits, pay[0], scale[0], flag)
+            thc.thc_aggregate_decode(pay[0], scale[0], ns[0], l, 5, bits, None, out[0])
+    elif form == "batch":
+        bk = [dict(grads=xs[k], payloads=pay[k], scale=scale[k], out=out[k], n=n, seed=5 + k) for k, n in enumerate(ns)]
+        ws = torch.empty(thc.thc_batch_workspace_bytes(ns, W, l), dtype=torch.uint8, device=DEV)
+
+        def step():
+            thc.thc_encode_all_batch(bk, l, bits, ws)
+            thc.thc_aggregate_decode_batch(bk, l, bits, ws)
+    else:
+        ws = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, ns[0], l), dtype=torch.uint8, device=DEV)
+
+        def step():
+            thc.thc_encode_all_minmax(xs[0], l, 5, bits, True, pay[0], scale[0], ws)
+            thc.thc_aggregate_decode_minmax(pay[0], scale[0], ns[0], l, 5, bits, True, out[0])
+    graph = _capture(step)
+
+    for rep in range(3):
+        print(f"graph replay {rep} form={form}", flush=True)
+        for k in range(len(ns)):
+            for w in range(W):               # new inputs in the recorded buffers
+                xs[k][w].copy_(_rand(ns[k], 100 * rep + w + 50 * k))
+            for p in pay[k]:
+                p.fill_(0xEE)
+            out[k].fill_(float("nan"))
+            scale[k].fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        if form == "static":
+            assert int(flag.item()) == 0
+        else:
+            assert not thc.thc_encode_all_timed_out(ws)
+        for k, n in enumerate(ns):           # eager, between replays
+            ref_pay = [torch.empty_like(p) for p in pay[k]]
+            ref_scale, ref_out = torch.empty_like(scale[k]), torch.empty_like(out[k])
+            if form == "minmax":
+                w2 = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
+                thc.thc_encode_all_minmax(xs[k], l, 5, bits, True, ref_pay, ref_scale, w2)
+                thc.thc_aggregate_decode_minmax(ref_pay, ref_scale, n, l, 5, bits, True, ref_out)
+            else:
+                w2 = torch.empty(thc.thc_encode_all_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
+                thc.thc_encode_all(xs[k], l, 5 + k, bits, ref_pay, ref_scale, w2)
+                thc.thc_aggregate_decode(ref_pay, ref_scale, n, l, 5 + k, bits, None, ref_out)
+            torch.cuda.synchronize()
+            assert torch.equal(scale[k], ref_scale)
+            for a, b in zip(pay[k], ref_pay):
+                assert torch.equal(a, b)
+            assert torch.equal(out[k], ref_out)
