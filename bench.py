@@ -517,6 +517,22 @@ def read_traffic(workload_name, bits, kernel):
     return None
 
 
+def read_executed_ops(workload_name, bits):
+    """VALU lane-operations per worker-coordinate that the one-pass encoder executed when it
+    was last counted with rocprofv3 --pmc SQ_INSTS_VALU (first bucket of the headline
+    workload; profiles/encode_all_aggregate_decode_gpt_1p3b_sq_counters.txt)."""
+    path = os.path.join(ROOT, "profiles", "encode_all_aggregate_decode_gpt_1p3b_sq_counters.txt")
+    if workload_name != "gpt_1p3b" or bits != 4 or not os.path.exists(path):
+        return None
+    seen_kernel = False
+    for line in open(path):
+        if line.startswith("encode_all_kernel"):
+            seen_kernel = True
+        if seen_kernel and line.strip().startswith("all VALU"):
+            return float(line.split()[-1])
+    return None
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -671,7 +687,9 @@ def main():
         "roofline_alu": {"bound": "alu", "kernel": dom_name, "achieved": round(alu_achieved, 2),
                          "peak": round(VALU_PEAK_TOPS, 2), "unit": "Top/s",
                          "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
-                         "ops_per_worker_coord": ENCODE_OPS_PER_COORD},
+                         "ops_per_worker_coord": ENCODE_OPS_PER_COORD,
+                         "ops_per_worker_coord_executed": read_executed_ops(wl.name, bits) if path.fused and not a.sat
+                         and not a.full_rotation else None},
         "roofline_second": second,
         "pct_hbm_peak": round(100.0 * wl.n * alg_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "copy_GBps": round(copy_gbs, 1),
