@@ -703,6 +703,14 @@ def main():
                          "moved_frac_of_peak": round(wl.n * moved_bytes_per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "kernels": kernels,
     }
+    # by the traffic counters: bytes the two kernels were measured to move per launch of the
+    # first bucket (rocprofv3, committed under profiles/), per coordinate of that bucket
+    t_enc = read_traffic(wl.name, bits, "thc_encode_all")
+    t_dec = read_traffic(wl.name, bits, "thc_aggregate_decode")
+    if path.fused and not a.sat and not a.full_rotation and t_enc and t_dec:
+        per_coord = (t_enc + t_dec) / float(path.items[0]["ln"])
+        res["pipeline_hbm"]["counter_bytes_per_coord"] = round(per_coord, 3)
+        res["pipeline_hbm"]["counter_frac_of_peak"] = round(wl.n * per_coord / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     if a.full_rotation:
         path.step()   # the per-kernel loops above left scratch in the buffers: one clean pass
         torch.cuda.synchronize()
