@@ -36,6 +36,15 @@ constexpr int kPollSleep = 8;
 #define THC_CONSTANT __attribute__((address_space(4)))
 typedef const BatchRecord THC_CONSTANT* ConstRecordPtr;
 typedef const uint64_t THC_CONSTANT* ConstU64Ptr;
+// A pointer that was read from a record as an integer, as a pointer into global memory: the
+// compiler then uses global loads and stores for it, as it does for pointers that arrive as
+// kernel arguments, instead of the slower generic (flat) ones, which also count as LDS
+// operations in the wait counters.
+template <typename T>
+__device__ __forceinline__ T* global_ptr(uint64_t address) {
+    typedef T __attribute__((address_space(1))) * Global;
+    return (T*)(Global)address;
+}
 __device__ __forceinline__ ConstRecordPtr batch_record(const BatchArgs& batch, uint32_t k) {
     return (ConstRecordPtr)(batch.records + (uint64_t)k * batch.record_bytes);
 }
@@ -86,8 +95,16 @@ struct EncodeAllCtx {
             ConstRecordPtr r = batch_record(batch, bidx);
             boundary = bidx + 1u < batch.count ? batch_record(batch, bidx + 1u)->chunk0 : ~0ull;
             ConstU64Ptr ptr = (ConstU64Ptr)(r + 1);   // W gradients, then W payloads
-            return BucketView{r->n, r->chunk0, r->key0, r->key1, reinterpret_cast<const void*>(ptr[w]),
-                              reinterpret_cast<uint8_t*>(ptr[a.W + w]), r->scale};
+            BucketView bv{r->n, r->chunk0, r->key0, r->key1, reinterpret_cast<const void*>(ptr[w]),
+                          reinterpret_cast<uint8_t*>(ptr[a.W + w]), r->scale};
+            // The record has arrived before the look-up returns.  Scalar loads complete out of
+            // order, so one that is still in flight when the item's LDS exchanges start would
+            // make every wait on an LDS load a wait for ALL of them (no overlap of the
+            // exchange with the arithmetic that follows it), on every item, although a
+            // look-up happens once per bucket.
+            asm volatile("" : "+s"(bv.n), "+s"(bv.chunk0), "+s"(bv.key0), "+s"(bv.key1), "+s"(bv.grad),
+                         "+s"(bv.payload), "+s"(bv.scale), "+s"(boundary), "+s"(bidx));
+            return bv;
         } else {
             return BucketView{a.n, 0u, a.key0, a.key1, ptrs.grad[w], ptrs.payload[w], a.scale};
         }
@@ -216,8 +233,11 @@ struct EncodeAllCtx {
         prev = (uint32_t)p;
         const float s = __uint_as_float(sbits);
         const uint64_t pl = p - cur.chunk0;   // the chunk's number inside its bucket
-        if (w == 0 && t == 0) cur.scale[pl] = s;
-        quantize_store<BITS, false>(v, s, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1, cur.payload, t);
+        // (the view's pointers are re-tagged as global here: in a batched launch they come out of
+        // the look-up's register barrier as plain addresses)
+        if (w == 0 && t == 0) global_ptr<float>(reinterpret_cast<uint64_t>(cur.scale))[pl] = s;
+        quantize_store<BITS, false>(v, s, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1,
+                                    global_ptr<uint8_t>(reinterpret_cast<uint64_t>(cur.payload)), t);
     }
 
     // After the workgroup's last item: its words have no later chunk to vouch for them, so
@@ -357,7 +377,7 @@ struct PayloadSum {
 #pragma unroll
         for (int j = 0; j < kGroup; ++j)
             if (group * kGroup + j < W) {
-                const uint8_t* src = BATCH ? reinterpret_cast<const uint8_t*>(pp[group * kGroup + j])
+                const uint8_t* src = BATCH ? global_ptr<const uint8_t>(pp[group * kGroup + j])
                                            : ptrs.p[group * kGroup + j];
                 x[j] = load_payload_words<BITS>(src + byte0);
             }
@@ -421,7 +441,11 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
             ConstRecordPtr r = batch_record(batch, bidx);
             boundary = bidx + 1u < batch.count ? batch_record(batch, bidx + 1u)->chunk0 : ~0ull;
             ConstU64Ptr pp = (ConstU64Ptr)(r + 1) + a.W;   // the payload pointers follow the gradient pointers
-            return DecodeView{r->n, r->chunk0, r->key0, r->key1, r->scale, r->out, pp};
+            DecodeView dv{r->n, r->chunk0, r->key0, r->key1, r->scale, r->out, pp};
+            // the record has arrived before the look-up returns (see EncodeAllCtx::view_of)
+            asm volatile("" : "+s"(dv.n), "+s"(dv.chunk0), "+s"(dv.key0), "+s"(dv.key1), "+s"(dv.scale),
+                         "+s"(dv.out), "+s"(boundary), "+s"(bidx));
+            return dv;
         } else {
             return DecodeView{a.n, 0u, a.key0, a.key1, a.scale, a.out, nullptr};
         }
@@ -448,8 +472,9 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
 
         // sums -> rotated-domain estimate of the mean, layout L1
         // symmetric grid: yhat = S q - s;  min/max grid: yhat = S q + lo = S q - (-lo)
-        const float s = RANGED ? -cur.scale[2 * pl] : cur.scale[pl];
-        const float step = (RANGED ? cur.scale[2 * pl + 1] + s : s + s) / Lf;
+        const float* scale = global_ptr<const float>(reinterpret_cast<uint64_t>(cur.scale));
+        const float s = RANGED ? -scale[2 * pl] : scale[pl];
+        const float step = (RANGED ? scale[2 * pl + 1] + s : s + s) / Lf;
         const float qf = step / Wf;
         float v[kRegs];
         uint32_t S[kRegs];
@@ -512,7 +537,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
             }
         }
         l3_to_l4d<false>(sh, v, lane, wave);
-        store_signed_l4d(sh.sign[0], v, cur.out + g0, valid, t);
+        store_signed_l4d(sh.sign[0], v, global_ptr<float>(reinterpret_cast<uint64_t>(cur.out)) + g0, valid, t);
         cur = nxt;
     }
 }
