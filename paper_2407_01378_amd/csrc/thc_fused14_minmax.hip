@@ -47,76 +47,26 @@ __device__ __forceinline__ MinMax thread_minmax(const float (&v)[kRegs]) {
     return MinMax{lo, hi};
 }
 
-template <bool BF16, int BITS, bool ROTATE>
-__global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_minmax_kernel(const EncodeAllArgs a,
-                                                                                    const FusedWorkerPtrs ptrs) {
-    __shared__ Shared sh;
-    constexpr int kUnits = BF16 ? 4 : 8;
-    constexpr int kElem = BF16 ? 2 : 4;
-    constexpr uint32_t kNone = 0xFFFFFFFFu;
-    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t p0 = blockIdx.x / a.W;
-    const uint32_t w = blockIdx.x - p0 * a.W;      // the grid is a multiple of W
-    const uint32_t dp = gridDim.x / a.W;
-    const uint32_t half = kWaves * a.W;            // words of one kind per chunk: maxima, then minima
-    const uint32_t nwords = 2u * half;
-    const uint32_t mine = kWaves * w + wave;
-    if (p0 >= a.chunks) return;
-    uint32_t prev = kNone;
-    // bf16 input (16 registers per thread) is loaded one item ahead; fp32 input (32 registers)
-    // when its item starts
-    constexpr bool kAhead = BF16;
-    Raw<kUnits> raw;
-    auto load = [&](uint64_t p) {
-        const uint64_t g0 = p << kChunkLog2;
-        const uint64_t left = a.n - g0;
-        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-        const uint8_t* src = static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem;
-        // rotated: coalesced order, dealt out through the buffer.  Unrotated bf16: thread t
-        // loads its own 64 consecutive bytes (coordinates 32 t .. 32 t + 31).  Unrotated fp32
-        // would be 128 bytes per thread, and the 16 waves of a CU would keep 128 KB of
-        // half-used lines in a 32 KB vector cache: coalesced order as well.
-        load_raw<kUnits, kElem, !ROTATE && BF16>(raw, src, valid, t);
-    };
-    if (kAhead) load(p0);
-    for (uint64_t p = p0; p < a.chunks; p += dp) {
-        const uint64_t g0 = p << kChunkLog2;
-        const bool more = p + dp < a.chunks;
-        float v[kRegs];
-        if (!kAhead) load(p);
-        if constexpr (ROTATE || !BF16) {
-            __syncthreads();   // the previous item's last reads of the buffer and the table are done
-            if (ROTATE) fill_sign_table<!BF16, BF16>(sh.sign[0], g0, a.key0, a.key1, t);
-            raw_to_lds<kUnits>(sh, raw, t);
-            __syncthreads();
-            if (kAhead && more) load(p + dp);
-            lds_to_l1<kUnits, ROTATE>(sh, sh.sign[0], v, t);
-            if (ROTATE) rotate_l1_to_l3<true>(sh, v, lane, wave);
-        } else {
-            // y is the zero-padded gradient itself, already in the layout the quantizer wants
-            units_to_l1<kUnits, false>(sh.sign[0], raw.u, v, t);
-#pragma unroll
-            for (int i = 0; i < kRegs; ++i) asm volatile("" : "+v"(v[i]));   // converted before `raw` is reloaded
-            asm volatile("" ::: "memory");
-            if (more) load(p + dp);
-        }
-        // this wave's share of the chunk's range, one word each for max and -min (so that
-        // both are combined by a maximum), value in the rotation's normalised units
-        MinMax r = thread_minmax(v);
-        if (ROTATE) {
-            r.lo *= kInvSqrtC;   // exact, and monotone: the order of min and scaling does not matter
-            r.hi *= kInvSqrtC;
-        }
-        const uint32_t khi = wave_umax(order_key(r.hi));
-        const uint32_t klo = wave_umax(order_key(-r.lo));
+// ---- the range words of a chunk: two per wave of every worker's workgroup, the maxima
+// first, then the negated minima (so that both are combined by a maximum) ----------------
+struct Words {
+    const EncodeAllArgs& a;
+    uint32_t half;     // words of one kind per chunk
+    uint32_t nwords;   // 2 * half
+    uint32_t mine;     // this wave's index among the words of one kind
+    uint32_t lane;
+
+    __device__ __forceinline__ void publish(uint64_t p, uint32_t khi, uint32_t klo) const {
         if (lane == 0) {
             __hip_atomic_store(&a.slots[p * nwords + mine], khi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&a.slots[p * nwords + half + mine], klo, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (ROTATE) l3_to_l4e<true>(sh, v, lane, wave);
-
-        // wait for every wave of every worker of the chunk; bounded, as in encode_all_kernel
+    }
+    // Waits until every wave of every worker of chunk p has published; bounded by
+    // a.max_spins polls, after which the error word is set and the wave carries on with
+    // what it has seen and its own range (khi, klo).  Returns the keys of (hi, -lo).
+    __device__ __forceinline__ bool wait(uint64_t p, uint32_t& khi, uint32_t& klo) const {
         const uint32_t* slot = a.slots + p * nwords;
         uint32_t mxh = 0u, mxl = 0u;
         bool done = false;
@@ -142,43 +92,181 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_minmax_ker
         }
         if (!done && lane == 0)
             __hip_atomic_store(a.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The workspace leaves the kernel all zero: with every word of this chunk seen, no
-        // peer will read the words of the workgroup's previous chunk again (a peer publishes
-        // for this chunk only after all its waves have finished reading the previous one's
-        // words, which the barriers of the rotation - or, without a rotation, the barrier
-        // below - guarantee), and this wave clears its own two.
-        if (done && prev != kNone && lane == 0) {
-            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + mine], 0u, __ATOMIC_RELAXED,
+        const uint32_t kh = wave_umax(mxh), kl = wave_umax(mxl);
+        khi = kh > khi ? kh : khi;
+        klo = kl > klo ? kl : klo;
+        return done;
+    }
+    // This wave's two words of an earlier chunk back to zero.
+    __device__ __forceinline__ void clear_mine(uint32_t chunk) const {
+        if (lane == 0) {
+            __hip_atomic_store(&a.slots[(uint64_t)chunk * nwords + mine], 0u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + half + mine], 0u, __ATOMIC_RELAXED,
+            __hip_atomic_store(&a.slots[(uint64_t)chunk * nwords + half + mine], 0u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+    // A workgroup's last chunks have no later chunk to vouch for them: the W workgroups of the
+    // chunk count themselves off and the last one clears all its words and the counter.  Called
+    // by one wave, after a barrier behind the workgroup's last read of the words.
+    __device__ __forceinline__ void count_off(uint32_t chunk) const {
+        uint32_t arrived = 0u;
+        if (lane == 0)
+            arrived = __hip_atomic_fetch_add(&a.done[chunk], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)arrived);
+        if (arrived == a.W - 1u) {
+            uint32_t* words = a.slots + (uint64_t)chunk * nwords;
+            for (uint32_t i = lane; i < nwords; i += 64u)
+                __hip_atomic_store(&words[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_store(&a.done[chunk], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+};
+
+// "no chunk"
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+
+// With the rotation.  One item at a time: rotate, publish, last exchange, wait, quantize.
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_minmax_kernel(const EncodeAllArgs a,
+                                                                                    const FusedWorkerPtrs ptrs) {
+    __shared__ Shared sh;
+    constexpr int kUnits = BF16 ? 4 : 8;
+    constexpr int kElem = BF16 ? 2 : 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t p0 = blockIdx.x / a.W;
+    const uint32_t w = blockIdx.x - p0 * a.W;      // the grid is a multiple of W
+    const uint32_t dp = gridDim.x / a.W;
+    const Words words{a, kWaves * a.W, 2u * kWaves * a.W, kWaves * w + wave, lane};
+    if (p0 >= a.chunks) return;
+    uint32_t prev = kNone;
+    // bf16 input (16 registers per thread) is loaded one item ahead; fp32 input (32 registers)
+    // when its item starts.  Coalesced order, dealt out through the buffer.
+    constexpr bool kAhead = BF16;
+    Raw<kUnits> raw;
+    auto load = [&](uint64_t p) {
+        const uint64_t g0 = p << kChunkLog2;
+        const uint64_t left = a.n - g0;
+        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem, valid, t);
+    };
+    if (kAhead) load(p0);
+    for (uint64_t p = p0; p < a.chunks; p += dp) {
+        const uint64_t g0 = p << kChunkLog2;
+        float v[kRegs];
+        if (!kAhead) load(p);
+        __syncthreads();   // the previous item's last reads of the buffer and the table are done
+        fill_sign_table<!BF16, BF16>(sh.sign[0], g0, a.key0, a.key1, t);
+        raw_to_lds<kUnits>(sh, raw, t);
+        __syncthreads();
+        if (kAhead && p + dp < a.chunks) load(p + dp);
+        lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
+        rotate_l1_to_l3<true>(sh, v, lane, wave);
+        // this wave's share of the chunk's range in normalised units (the scaling by 2^-7 is
+        // exact and monotone, so it commutes with min and max)
+        const MinMax r = thread_minmax(v);
+        uint32_t khi = wave_umax(order_key(r.hi * kInvSqrtC));
+        uint32_t klo = wave_umax(order_key(-(r.lo * kInvSqrtC)));
+        words.publish(p, khi, klo);
+        l3_to_l4e<true>(sh, v, lane, wave);
+        const bool done = words.wait(p, khi, klo);
+        // The workspace leaves the kernel all zero: with every word of this chunk seen, no
+        // peer will read the words of the workgroup's previous chunk again (a peer publishes
+        // for this chunk only after the barriers of this item's rotation, which all its
+        // waves reach only after reading the previous chunk's words): this wave clears its two.
+        if (done && prev != kNone) words.clear_mine(prev);
         prev = (uint32_t)p;
-        // a timed-out wait may have seen no word at all: fall back to this wave's own range
-        const uint32_t kh = wave_umax(mxh), kl = wave_umax(mxl);
-        const float hi = order_value(kh > khi ? kh : khi);
-        const float lo = -order_value(kl > klo ? kl : klo);
+        const float hi = order_value(khi), lo = -order_value(klo);
         if (w == 0 && t == 0) {
             a.scale[2 * p] = lo;
             a.scale[2 * p + 1] = hi;
         }
-        quantize_store_range<BITS, ROTATE>(v, lo, hi, a.levels, g0, w, a.key0, a.key1, ptrs.payload[w], t);
-        if (!ROTATE) __syncthreads();   // every wave has read this chunk's words before any publishes the next
+        quantize_store_range<BITS, true>(v, lo, hi, a.levels, g0, w, a.key0, a.key1, ptrs.payload[w], t);
     }
-    // The workgroup's last chunk has no later chunk to vouch for it: the W workgroups of the
-    // chunk count themselves off and the last one clears the chunk's words and the counter.
-    __syncthreads();
-    if (wave != 0) return;
-    uint32_t arrived = 0u;
-    if (lane == 0)
-        arrived = __hip_atomic_fetch_add(&a.done[prev], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)arrived);
-    if (arrived == a.W - 1u) {
-        uint32_t* words = a.slots + (uint64_t)prev * nwords;
-        for (uint32_t i = lane; i < nwords; i += 64u)
-            __hip_atomic_store(&words[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (lane == 0) __hip_atomic_store(&a.done[prev], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();   // every wave of this workgroup has read the last chunk's words
+    if (wave == 0) words.count_off(prev);
+}
+
+// Without the rotation: y is the zero-padded gradient itself, already in the layout the
+// quantizer wants.  An item has nothing to do between publishing its range and reading its
+// peers', so the time the words take to travel is exposed; what hides it is more workgroups
+// per CU: the bf16 form needs no LDS at all and is compiled for three workgroups per CU
+// (85 registers) instead of two.  (Handling items in pairs - publish both, then wait for
+// the first while the second one's words travel - was measured and is slower: 64 live
+// values per thread spill.)
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(kThreads, BF16 ? 6 : kWavesPerSimd) void encode_all_unrotated_kernel(
+    const EncodeAllArgs a, const FusedWorkerPtrs ptrs) {
+    __shared__ Shared sh;   // fp32 only (the bf16 form never touches it, so it is not allocated)
+    __shared__ uint32_t bcast[3];
+    constexpr int kUnits = BF16 ? 4 : 8;
+    constexpr int kElem = BF16 ? 2 : 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t p0 = blockIdx.x / a.W;
+    const uint32_t w = blockIdx.x - p0 * a.W;
+    const uint32_t dp = gridDim.x / a.W;
+    const Words words{a, kWaves * a.W, 2u * kWaves * a.W, kWaves * w + wave, lane};
+    if (p0 >= a.chunks) return;
+    // bf16: thread t loads its own 64 consecutive bytes (coordinates 32 t .. 32 t + 31), an
+    // item ahead.  fp32 would be 128 bytes per thread, and the 16 waves of a CU would keep
+    // 128 KB of half-used lines in a 32 KB vector cache: coalesced order, dealt out through
+    // the buffer, loaded when the item starts.
+    Raw<kUnits> raw;
+    auto load = [&](uint64_t p) {
+        const uint64_t g0 = p << kChunkLog2;
+        const uint64_t left = a.n - g0;
+        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+        load_raw<kUnits, kElem, BF16>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem, valid, t);
+    };
+    if (BF16) load(p0);
+    uint32_t prev = kNone;
+    for (uint64_t p = p0; p < a.chunks; p += dp) {
+        float v[kRegs];
+        if constexpr (BF16) {
+            units_to_l1<kUnits, false>(sh.sign[0], raw.u, v, t);
+            // the conversion is complete before the registers of `raw` are loaded again
+#pragma unroll
+            for (int i = 0; i < kRegs; ++i) asm volatile("" : "+v"(v[i]));
+            asm volatile("" ::: "memory");
+            if (p + dp < a.chunks) load(p + dp);
+        } else {
+            load(p);
+            raw_to_lds<kUnits>(sh, raw, t);
+            __syncthreads();
+            lds_to_l1<kUnits, false>(sh, sh.sign[0], v, t);
+        }
+        const MinMax m = thread_minmax(v);
+        uint32_t khi = wave_umax(order_key(m.hi));
+        uint32_t klo = wave_umax(order_key(-m.lo));
+        words.publish(p, khi, klo);
+        // One wave polls for the workgroup.  Without a rotation the waves would spend most of
+        // an item polling, eight of them per workgroup, and that traffic (uncached reads served
+        // at the memory side) delays the very words it is waiting for.
+        if (wave == 0) {
+            const bool ok = words.wait(p, khi, klo);
+            if (lane == 0) {
+                bcast[0] = khi;
+                bcast[1] = klo;
+                bcast[2] = ok ? 1u : 0u;
+            }
+        }
+        __syncthreads();
+        khi = bcast[0];
+        klo = bcast[1];
+        const bool done = bcast[2] != 0u;
+        // as in the rotated kernel; the barrier that lets a peer conclude that this workgroup
+        // has finished with the previous chunk's words is the one at the end of the item
+        if (done && prev != kNone) words.clear_mine(prev);
+        prev = (uint32_t)p;
+        const float hi = order_value(khi), lo = -order_value(klo);
+        if (w == 0 && t == 0) {
+            a.scale[2 * p] = lo;
+            a.scale[2 * p + 1] = hi;
+        }
+        quantize_store_range<BITS, false>(v, lo, hi, a.levels, p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        __syncthreads();   // every wave has read this chunk's words (and the buffer) before the next item
     }
+    if (wave == 0) words.count_off(prev);   // behind the barrier that ended the last item
 }
 
 // out[g] = float(sum of the W indices of coordinate g) * (step / W) + lo, no rotation.
@@ -243,17 +331,22 @@ uint32_t resident_grid_minmax() {
     return cached;
 }
 
-template <bool BF16, int BITS, bool ROTATE>
-hipError_t launch_minmax_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid_minmax<encode_all_minmax_kernel<BF16, BITS, ROTATE>>();
+template <auto kernel>
+hipError_t launch_minmax_kernel(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
+    uint32_t G = resident_grid_minmax<kernel>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
     // the W workgroups of a chunk wait for one another: all of them must be resident
     if (G < a.W) return hipErrorInvalidConfiguration;
     G -= G % a.W;
-    hipLaunchKernelGGL((encode_all_minmax_kernel<BF16, BITS, ROTATE>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    hipLaunchKernelGGL(kernel, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
     return hipGetLastError();
+}
+template <bool BF16, int BITS, bool ROTATE>
+hipError_t launch_minmax_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
+    if constexpr (ROTATE) return launch_minmax_kernel<encode_all_minmax_kernel<BF16, BITS>>(a, ptrs, stream);
+    else return launch_minmax_kernel<encode_all_unrotated_kernel<BF16, BITS>>(a, ptrs, stream);
 }
 
 template <bool BF16, bool ROTATE>
