@@ -286,8 +286,6 @@ def cpu_baseline(wl, bits, xs, log2_sample):
     """The NumPy oracle (float32 canonical-order mode), as it stands, on the first coordinates
     of every worker: once in this process (NumPy runs these operations on one thread), once
     with a process pool over slices of whole chunks on the host cores this job may use."""
-    import multiprocessing as mp
-
     import numpy as np
 
     from oracle import thc as O
@@ -307,36 +305,48 @@ def cpu_baseline(wl, bits, xs, log2_sample):
     piece = 1 << 21                              # 128 chunks of 2^14 per task
     m_all = min(wl.n, max(m, piece * cores * 2)) // piece * piece
     if cores > 1 and m_all >= 2 * piece:
-        from multiprocessing import shared_memory
-        first = to_numpy_bits(xs[0][:m_all])
-        shm = shared_memory.SharedMemory(create=True, size=wl.W * m_all * first.itemsize)
         try:
-            host = np.ndarray((wl.W, m_all), dtype=first.dtype, buffer=shm.buf)
-            host[0] = first
-            for w in range(1, wl.W):
-                host[w] = to_numpy_bits(xs[w][:m_all])
-            tasks = [(g, piece, wl.chunk_log2, bits, bf16) for g in range(0, m_all, piece)]
-            ctx = mp.get_context("spawn")            # the parent holds a GPU context: no fork
-            # an executor, not multiprocessing.Pool: a worker that dies ends the run with
-            # an error instead of being replaced for ever
-            from concurrent.futures import ProcessPoolExecutor
-            with ProcessPoolExecutor(cores, mp_context=ctx, initializer=_oracle_pool_init,
-                                     initargs=(shm.name, wl.W, m_all, first.dtype.str)) as pool:
-                list(pool.map(_oracle_slice,
-                              [(0, 1 << wl.chunk_log2, wl.chunk_log2, bits, bf16)] * cores))   # start-up, untimed
-                t0 = time.perf_counter()
-                done = sum(pool.map(_oracle_slice, tasks))
-                dt_all = time.perf_counter() - t0
-            del host
-        finally:
-            shm.close()
-            shm.unlink()
-        res["all_cores"] = dict(value=round(wl.W * done * s_in / dt_all / 1e9, 5), unit="GB/s", cores=cores,
-                                host_cpu_count=os.cpu_count(),
-                                kind="oracle, process pool over slices of 2^21 coordinates",
-                                sample=f"first {done} coordinates of each of the {wl.W} workers "
-                                       f"({dt_all:.1f} s wall)")
+            res["all_cores"] = _cpu_baseline_pool(wl, bits, xs, m_all, piece, cores, bf16, s_in)
+        except Exception as e:   # the reported baseline must not take the GPU measurement down with it
+            res["all_cores"] = dict(error=f"{type(e).__name__}: {e}", cores=cores, host_cpu_count=os.cpu_count())
     return res
+
+
+def _cpu_baseline_pool(wl, bits, xs, m_all, piece, cores, bf16, s_in):
+    """The all-cores leg: the sample in shared memory, a spawned process pool over its slices."""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    from multiprocessing import shared_memory
+
+    import numpy as np
+
+    from synth import to_numpy_bits
+    first = to_numpy_bits(xs[0][:m_all])
+    shm = shared_memory.SharedMemory(create=True, size=wl.W * m_all * first.itemsize)
+    try:
+        host = np.ndarray((wl.W, m_all), dtype=first.dtype, buffer=shm.buf)
+        host[0] = first
+        for w in range(1, wl.W):
+            host[w] = to_numpy_bits(xs[w][:m_all])
+        tasks = [(g, piece, wl.chunk_log2, bits, bf16) for g in range(0, m_all, piece)]
+        ctx = mp.get_context("spawn")            # the parent holds a GPU context: no fork
+        # an executor, not multiprocessing.Pool: a worker that dies ends the leg with an
+        # error instead of being replaced for ever
+        with ProcessPoolExecutor(cores, mp_context=ctx, initializer=_oracle_pool_init,
+                                 initargs=(shm.name, wl.W, m_all, first.dtype.str)) as pool:
+            list(pool.map(_oracle_slice,
+                          [(0, 1 << wl.chunk_log2, wl.chunk_log2, bits, bf16)] * cores))   # start-up, untimed
+            t0 = time.perf_counter()
+            done = sum(pool.map(_oracle_slice, tasks))
+            dt_all = time.perf_counter() - t0
+        del host
+    finally:
+        shm.close()
+        shm.unlink()
+    return dict(value=round(wl.W * done * s_in / dt_all / 1e9, 5), unit="GB/s", cores=cores,
+                host_cpu_count=os.cpu_count(),
+                kind="oracle, process pool over slices of 2^21 coordinates",
+                sample=f"first {done} coordinates of each of the {wl.W} workers ({dt_all:.1f} s wall)")
 
 
 def copy_bandwidth(torch, dev):
