@@ -345,6 +345,29 @@ __device__ __forceinline__ MinMax chunk_minmax(Shared& sh, const float (&v)[kReg
     return MinMax{lo, hi};
 }
 
+// (min, max) over this thread's registers.
+__device__ __forceinline__ MinMax thread_minmax(const float (&v)[kRegs]) {
+    float lo = v[0], hi = v[0];
+#pragma unroll
+    for (int i = 1; i < kRegs; ++i) {
+        lo = fminf(lo, v[i]);
+        hi = fmaxf(hi, v[i]);
+    }
+    return MinMax{lo, hi};
+}
+
+// Order-preserving map of floats onto unsigned words that are never zero for anything
+// but a NaN (in the words workgroups exchange, zero means "not published yet"):
+// x <= y  <=>  order_key(x) <= order_key(y).
+__device__ __forceinline__ uint32_t order_key(float x) {
+    const uint32_t b = __float_as_uint(x);
+    const uint32_t k = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return k != 0u ? k : 1u;
+}
+__device__ __forceinline__ float order_value(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
 // L3 -> L4e through the buffer (two barriers); v then holds coordinates 32 t .. 32 t + 31.
 template <bool PRIO>
 __device__ __forceinline__ void l3_to_l4e(Shared& sh, float (&v)[kRegs], uint32_t lane, uint32_t wave) {

@@ -66,7 +66,11 @@ struct BucketView {
 // that shape keeps the element-wise loader; every other shape loads through a descriptor.
 // BATCH: the launch covers several buckets (a.chunks is their total, chunks are numbered
 // through all of them); everything per bucket comes from the records in device memory.
-template <bool BF16, bool ODD, bool BATCH>
+// MINMAX: the grid runs from the chunk's smallest to its largest value instead of
+// symmetrically around zero: every wave publishes two words (the maximum, then the negated
+// minimum, both through order_key() so that both are combined by a maximum), `scale` receives
+// (lo, hi) pairs, and the quantizer subtracts lo.
+template <bool BF16, bool ODD, bool BATCH, bool MINMAX = false>
 struct EncodeAllCtx {
     static constexpr int kUnits = BF16 ? 4 : 8;
     static constexpr int kElem = BF16 ? 2 : 4;
@@ -168,15 +172,28 @@ struct EncodeAllCtx {
             if (BATCH && more && p + dp >= boundary) nxt = view_of(p + dp);
         }
         rotate_l1_to_l3<true>(sh, v, lane, wave);
-        const float m = wave_absmax(v) * kInvSqrtC;
         // One word per wave, value | valid bit (non-negative floats order like their bit
         // patterns and leave bit 31 free).  The words travel between workgroups only
         // through device-scope stores and loads, which are served at the memory side, so
         // no cache write-back or invalidate is needed.  The slots start zeroed.
-        if (lane == 0)
-            __hip_atomic_store(&a.slots[p * nwords + kWaves * w + wave],
-                               __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        if constexpr (MINMAX) {
+            // (the scaling by 2^-7 is exact and monotone: it commutes with min and max)
+            const MinMax r = thread_minmax(v);
+            const uint32_t khi = wave_umax(order_key(r.hi * kInvSqrtC));
+            const uint32_t klo = wave_umax(order_key(-(r.lo * kInvSqrtC)));
+            if (lane == 0) {
+                __hip_atomic_store(&a.slots[p * nwords + kWaves * w + wave], khi, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&a.slots[p * nwords + kWaves * a.W + kWaves * w + wave], klo, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else {
+            const float m = wave_absmax(v) * kInvSqrtC;
+            if (lane == 0)
+                __hip_atomic_store(&a.slots[p * nwords + kWaves * w + wave],
+                                   __float_as_uint(m) | 0x80000000u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
         l3_to_l4e<true>(sh, v, lane, wave);
     }
 
@@ -186,7 +203,7 @@ struct EncodeAllCtx {
     template <int BITS>
     __device__ __forceinline__ void back(const float (&v)[kRegs], uint64_t p) {
         const uint32_t* slot = a.slots + p * nwords;
-        uint32_t mx = 0u;
+        uint32_t mx = 0u, mx2 = 0u;   // mx2: MINMAX only, the negated minima
         bool done = false;
         // The peers of a chunk publish up to about 2 us apart and a word takes about as long
         // to travel, so the first read waits a little: reads that come back incomplete are not
@@ -195,18 +212,38 @@ struct EncodeAllCtx {
         // 3 % faster than reading at once and every 64 clocks.
         __builtin_amdgcn_s_sleep(kFirstPollSleep);
         for (uint32_t spins = 0;; ++spins) {
-            uint32_t all_valid = 0x80000000u;
-            mx = 0u;
-            for (uint32_t base = 0; base < nwords; base += 64u) {
-                const uint32_t i = base + lane;
-                const uint32_t val =
-                    i < nwords ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                               : 0x80000000u;
-                all_valid &= val;
-                const uint32_t mag = val & 0x7FFFFFFFu;
-                mx = mag > mx ? mag : mx;
+            if constexpr (MINMAX) {
+                const uint32_t half = kWaves * a.W;
+                bool all_valid = true;
+                mx = mx2 = 0u;
+                for (uint32_t base = 0; base < half; base += 64u) {
+                    const uint32_t i = base + lane;
+                    const bool in = i < half;
+                    const uint32_t vh =
+                        in ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+                    const uint32_t vl =
+                        in ? __hip_atomic_load(&slot[half + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+                    all_valid = all_valid && vh != 0u && vl != 0u;
+                    if (in) {
+                        mx = vh > mx ? vh : mx;
+                        mx2 = vl > mx2 ? vl : mx2;
+                    }
+                }
+                done = __all(all_valid);
+            } else {
+                uint32_t all_valid = 0x80000000u;
+                mx = 0u;
+                for (uint32_t base = 0; base < nwords; base += 64u) {
+                    const uint32_t i = base + lane;
+                    const uint32_t val =
+                        i < nwords ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                   : 0x80000000u;
+                    all_valid &= val;
+                    const uint32_t mag = val & 0x7FFFFFFFu;
+                    mx = mag > mx ? mag : mx;
+                }
+                done = __all(all_valid != 0u);
             }
-            done = __all(all_valid != 0u);
             if (done || spins >= a.max_spins) break;
             __builtin_amdgcn_s_sleep(kPollSleep);
         }
@@ -226,13 +263,31 @@ struct EncodeAllCtx {
         // which every wave of its workgroup reaches only after reading the words of
         // the workgroup's previous chunk; with all of this chunk's words seen, nobody
         // will read the previous chunk's words again, and this wave clears its own.
-        if (done && prev != kNone && lane == 0)
+        if (done && prev != kNone && lane == 0) {
             __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (MINMAX)
+                __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * a.W + kWaves * w + wave], 0u,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         const uint32_t sbits = wave_umax(mx);
         prev = (uint32_t)p;
-        const float s = __uint_as_float(sbits);
         const uint64_t pl = p - cur.chunk0;   // the chunk's number inside its bucket
+        if constexpr (MINMAX) {
+            // (after an expired wait a word may be missing; zero then stands for "nothing seen")
+            const uint32_t lbits = wave_umax(mx2);
+            const float hi = sbits != 0u ? order_value(sbits) : 0.0f;
+            const float lo = lbits != 0u ? -order_value(lbits) : 0.0f;
+            float* range = global_ptr<float>(reinterpret_cast<uint64_t>(cur.scale));
+            if (w == 0 && t == 0) {
+                range[2 * pl] = lo;
+                range[2 * pl + 1] = hi;
+            }
+            quantize_store_range<BITS, true>(v, lo, hi, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1,
+                                             global_ptr<uint8_t>(reinterpret_cast<uint64_t>(cur.payload)), t);
+            return;
+        }
+        const float s = __uint_as_float(sbits);
         // (the view's pointers are re-tagged as global here: in a batched launch they come out of
         // the look-up's register barrier as plain addresses)
         if (w == 0 && t == 0) global_ptr<float>(reinterpret_cast<uint64_t>(cur.scale))[pl] = s;
@@ -264,15 +319,15 @@ struct EncodeAllCtx {
 // Items are (chunk, worker) pairs; workgroup g of a grid of G (a multiple of W) takes worker
 // g mod W of chunks g / W, g / W + G / W, ...  The peers of an item are therefore items of
 // the same round of other workgroups, and with every workgroup resident no wait is circular.
-template <bool BF16, int BITS, bool ODD, bool BATCH>
+template <bool BF16, int BITS, bool ODD, bool BATCH, bool MINMAX = false>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
                                                                  const FusedWorkerPtrs ptrs,
                                                                  const BatchArgs batch) {
     __shared__ Shared sh;
-    using Ctx = EncodeAllCtx<BF16, ODD, BATCH>;
+    using Ctx = EncodeAllCtx<BF16, ODD, BATCH, MINMAX>;
     const uint32_t t = threadIdx.x;
     const uint32_t p0 = blockIdx.x / a.W;
-    Ctx c{a, ptrs, batch, sh, {}, t, t & 63u, t >> 6, kWaves * a.W, blockIdx.x - p0 * a.W,
+    Ctx c{a, ptrs, batch, sh, {}, t, t & 63u, t >> 6, (MINMAX ? 2u : 1u) * kWaves * a.W, blockIdx.x - p0 * a.W,
           gridDim.x / a.W, 0u, Ctx::kNone, 0u, 0u, {}, {}};
     if (p0 >= a.chunks) return;
     c.cur = c.nxt = c.view_of(p0);
@@ -855,6 +910,42 @@ hipError_t launch_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stre
 hipError_t launch_encode_all_fused(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
                                    uint32_t bits, hipStream_t stream) {
     return k14::launch_encode_all_pick<false>(a, ptrs, BatchArgs{}, bf16, (a.n & 1u) != 0u, bits, stream);
+}
+
+// The min/max grid through the same kernel: a.scale receives (lo, hi) pairs and a.slots has
+// twice the words per chunk.
+hipError_t launch_encode_all_ranged(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
+                                    uint32_t bits, hipStream_t stream) {
+    using namespace k14;
+    const BatchArgs none{};
+    const bool odd = (a.n & 1u) != 0u;
+#define THC_RANGED(BF, B, O)                                                                       \
+    do {                                                                                           \
+        uint32_t G = resident_grid<encode_all_kernel<BF, B, O, false, true>>();                    \
+        if (G == 0) return hipErrorInvalidValue;                                                   \
+        const uint64_t total = a.chunks * a.W;                                                     \
+        if (G > total) G = (uint32_t)total;                                                        \
+        if (G < a.W) return hipErrorInvalidConfiguration;                                          \
+        G -= G % a.W;                                                                              \
+        hipLaunchKernelGGL((encode_all_kernel<BF, B, O, false, true>), dim3(G), dim3(kThreads), 0, \
+                           stream, a, ptrs, none);                                                 \
+        return hipGetLastError();                                                                  \
+    } while (0)
+    if (a.chunks == 0) return hipSuccess;
+    if (bf16 && odd) {
+        if (bits == 2) THC_RANGED(true, 2, true);
+        if (bits == 4) THC_RANGED(true, 4, true);
+        THC_RANGED(true, 8, true);
+    }
+    if (bf16) {
+        if (bits == 2) THC_RANGED(true, 2, false);
+        if (bits == 4) THC_RANGED(true, 4, false);
+        THC_RANGED(true, 8, false);
+    }
+    if (bits == 2) THC_RANGED(false, 2, false);
+    if (bits == 4) THC_RANGED(false, 4, false);
+    THC_RANGED(false, 8, false);
+#undef THC_RANGED
 }
 
 hipError_t launch_encode_all_batch(const EncodeAllArgs& a, const BatchArgs& batch, bool bf16, bool any_odd,

@@ -1,13 +1,13 @@
-// One-pass kernels of the min/max-range variant for chunk_log2 = 14 (with or without the
-// rotation): the counterpart of thc_fused14.hip's encode_all / aggregate_decode for the grid
-// that runs from the chunk's smallest to its largest value.
+// One-pass kernels of the min/max-range variant for chunk_log2 = 14 that have no counterpart
+// in thc_fused14.hip (with the rotation the variant runs in that file's encode_all_kernel and
+// aggregate_decode_kernel, compiled for the min/max grid).
 //
-// encode_all_minmax: a work item is (chunk p, worker w).  The workgroup that owns it brings
-// the chunk into registers (rotated or as it is), publishes its (min, max) to per-chunk
-// words in global memory, waits until all W workers of the chunk have published, and
-// quantizes onto the shared range - every gradient is read from HBM once (the
-// one-call-per-step form reads it twice).  Grid, item order, bounded waits and the
-// self-clearing workspace follow thc_fused14.hip's encode_all_kernel, with two words per wave.
+// encode_all_unrotated: a work item is (chunk p, worker w).  The workgroup that owns it brings
+// the chunk into registers as it is, publishes its (min, max) to per-chunk words in global
+// memory, waits until all W workers of the chunk have published, and quantizes onto the
+// shared range - every gradient is read from HBM once (the one-call-per-step form reads it
+// twice).  Grid, item order, bounded waits and the self-clearing workspace follow
+// encode_all_kernel, with two words per wave.
 //
 // unrotated_aggregate_decode: without the rotation the decoder is elementwise, so it is
 // written for coalescing instead of for the rotation's register layout.
@@ -24,28 +24,6 @@ constexpr uint32_t kWaves = kThreads / 64;
 constexpr int kWavesPerSimd = 4;   // two workgroups of 8 waves per CU
 constexpr int kFirstPollSleep = 32;
 constexpr int kPollSleep = 8;
-
-// Order-preserving map of floats onto unsigned words that are never zero for anything
-// but a NaN (zero means "not published yet"): x <= y  <=>  key(x) <= key(y).
-__device__ __forceinline__ uint32_t order_key(float x) {
-    const uint32_t b = __float_as_uint(x);
-    const uint32_t k = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-    return k != 0u ? k : 1u;
-}
-__device__ __forceinline__ float order_value(uint32_t k) {
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
-}
-
-// (min, max) over this thread's registers.
-__device__ __forceinline__ MinMax thread_minmax(const float (&v)[kRegs]) {
-    float lo = v[0], hi = v[0];
-#pragma unroll
-    for (int i = 1; i < kRegs; ++i) {
-        lo = fminf(lo, v[i]);
-        hi = fmaxf(hi, v[i]);
-    }
-    return MinMax{lo, hi};
-}
 
 // ---- the range words of a chunk: two per wave of every worker's workgroup, the maxima
 // first, then the negated minima (so that both are combined by a maximum) ----------------
@@ -125,67 +103,6 @@ struct Words {
 
 // "no chunk"
 constexpr uint32_t kNone = 0xFFFFFFFFu;
-
-// With the rotation.  One item at a time: rotate, publish, last exchange, wait, quantize.
-template <bool BF16, int BITS>
-__global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_minmax_kernel(const EncodeAllArgs a,
-                                                                                    const FusedWorkerPtrs ptrs) {
-    __shared__ Shared sh;
-    constexpr int kUnits = BF16 ? 4 : 8;
-    constexpr int kElem = BF16 ? 2 : 4;
-    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t p0 = blockIdx.x / a.W;
-    const uint32_t w = blockIdx.x - p0 * a.W;      // the grid is a multiple of W
-    const uint32_t dp = gridDim.x / a.W;
-    const Words words{a, kWaves * a.W, 2u * kWaves * a.W, kWaves * w + wave, lane};
-    if (p0 >= a.chunks) return;
-    uint32_t prev = kNone;
-    // bf16 input (16 registers per thread) is loaded one item ahead; fp32 input (32 registers)
-    // when its item starts.  Coalesced order, dealt out through the buffer.
-    constexpr bool kAhead = BF16;
-    Raw<kUnits> raw;
-    auto load = [&](uint64_t p) {
-        const uint64_t g0 = p << kChunkLog2;
-        const uint64_t left = a.n - g0;
-        const uint32_t valid = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-        load_raw<kUnits, kElem>(raw, static_cast<const uint8_t*>(ptrs.grad[w]) + g0 * kElem, valid, t);
-    };
-    if (kAhead) load(p0);
-    for (uint64_t p = p0; p < a.chunks; p += dp) {
-        const uint64_t g0 = p << kChunkLog2;
-        float v[kRegs];
-        if (!kAhead) load(p);
-        __syncthreads();   // the previous item's last reads of the buffer and the table are done
-        fill_sign_table<!BF16, BF16>(sh.sign[0], g0, a.key0, a.key1, t);
-        raw_to_lds<kUnits>(sh, raw, t);
-        __syncthreads();
-        if (kAhead && p + dp < a.chunks) load(p + dp);
-        lds_to_l1<kUnits, true>(sh, sh.sign[0], v, t);
-        rotate_l1_to_l3<true>(sh, v, lane, wave);
-        // this wave's share of the chunk's range in normalised units (the scaling by 2^-7 is
-        // exact and monotone, so it commutes with min and max)
-        const MinMax r = thread_minmax(v);
-        uint32_t khi = wave_umax(order_key(r.hi * kInvSqrtC));
-        uint32_t klo = wave_umax(order_key(-(r.lo * kInvSqrtC)));
-        words.publish(p, khi, klo);
-        l3_to_l4e<true>(sh, v, lane, wave);
-        const bool done = words.wait(p, khi, klo);
-        // The workspace leaves the kernel all zero: with every word of this chunk seen, no
-        // peer will read the words of the workgroup's previous chunk again (a peer publishes
-        // for this chunk only after the barriers of this item's rotation, which all its
-        // waves reach only after reading the previous chunk's words): this wave clears its two.
-        if (done && prev != kNone) words.clear_mine(prev);
-        prev = (uint32_t)p;
-        const float hi = order_value(khi), lo = -order_value(klo);
-        if (w == 0 && t == 0) {
-            a.scale[2 * p] = lo;
-            a.scale[2 * p + 1] = hi;
-        }
-        quantize_store_range<BITS, true>(v, lo, hi, a.levels, g0, w, a.key0, a.key1, ptrs.payload[w], t);
-    }
-    __syncthreads();   // every wave of this workgroup has read the last chunk's words
-    if (wave == 0) words.count_off(prev);
-}
 
 // Without the rotation: y is the zero-padded gradient itself, already in the layout the
 // quantizer wants.  An item has nothing to do between publishing its range and reading its
@@ -331,29 +248,25 @@ uint32_t resident_grid_minmax() {
     return cached;
 }
 
-template <auto kernel>
-hipError_t launch_minmax_kernel(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid_minmax<kernel>();
+template <bool BF16, int BITS>
+hipError_t launch_unrotated_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
+    uint32_t G = resident_grid_minmax<encode_all_unrotated_kernel<BF16, BITS>>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;
     if (G > total) G = (uint32_t)total;
     // the W workgroups of a chunk wait for one another: all of them must be resident
     if (G < a.W) return hipErrorInvalidConfiguration;
     G -= G % a.W;
-    hipLaunchKernelGGL(kernel, dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+    hipLaunchKernelGGL((encode_all_unrotated_kernel<BF16, BITS>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
     return hipGetLastError();
 }
-template <bool BF16, int BITS, bool ROTATE>
-hipError_t launch_minmax_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
-    if constexpr (ROTATE) return launch_minmax_kernel<encode_all_minmax_kernel<BF16, BITS>>(a, ptrs, stream);
-    else return launch_minmax_kernel<encode_all_unrotated_kernel<BF16, BITS>>(a, ptrs, stream);
-}
 
-template <bool BF16, bool ROTATE>
-hipError_t launch_minmax_bits(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t bits, hipStream_t stream) {
-    if (bits == 2) return launch_minmax_t<BF16, 2, ROTATE>(a, ptrs, stream);
-    if (bits == 4) return launch_minmax_t<BF16, 4, ROTATE>(a, ptrs, stream);
-    return launch_minmax_t<BF16, 8, ROTATE>(a, ptrs, stream);
+template <bool BF16>
+hipError_t launch_unrotated_bits(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, uint32_t bits,
+                                 hipStream_t stream) {
+    if (bits == 2) return launch_unrotated_t<BF16, 2>(a, ptrs, stream);
+    if (bits == 4) return launch_unrotated_t<BF16, 4>(a, ptrs, stream);
+    return launch_unrotated_t<BF16, 8>(a, ptrs, stream);
 }
 
 }  // namespace
@@ -364,10 +277,10 @@ uint32_t encode_all_minmax_slot_words(uint32_t W) { return 2u * k14::kWaves * W;
 hipError_t launch_encode_all_minmax(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16, bool rotate,
                                     uint32_t bits, hipStream_t stream) {
     if (a.chunks == 0) return hipSuccess;
-    if (bf16) return rotate ? k14::launch_minmax_bits<true, true>(a, ptrs, bits, stream)
-                            : k14::launch_minmax_bits<true, false>(a, ptrs, bits, stream);
-    return rotate ? k14::launch_minmax_bits<false, true>(a, ptrs, bits, stream)
-                  : k14::launch_minmax_bits<false, false>(a, ptrs, bits, stream);
+    // with the rotation: the kernel of thc_encode_all, compiled for the min/max grid
+    if (rotate) return launch_encode_all_ranged(a, ptrs, bf16, bits, stream);
+    return bf16 ? k14::launch_unrotated_bits<true>(a, ptrs, bits, stream)
+                : k14::launch_unrotated_bits<false>(a, ptrs, bits, stream);
 }
 
 hipError_t launch_unrotated_aggregate_decode(const FusedPayloadPtrs& ptrs, uint32_t W, const float* range,

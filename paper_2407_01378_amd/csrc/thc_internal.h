@@ -125,6 +125,9 @@ hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayl
 // min/max grid: a.scale holds (lo, hi) pairs
 hipError_t launch_aggregate_decode_ranged(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                           uint32_t bits, hipStream_t stream);
+// The rotated one-pass encoder on the min/max grid (thc_fused14.hip, the kernel of thc_encode_all).
+hipError_t launch_encode_all_ranged(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, bool bf16,
+                                    uint32_t bits, hipStream_t stream);
 // One-pass encoder of the min/max variant (thc_fused14_minmax.hip): a.scale receives (lo, hi)
 // pairs, a.slots has encode_all_minmax_slot_words(W) words per chunk.
 uint32_t encode_all_minmax_slot_words(uint32_t W);
