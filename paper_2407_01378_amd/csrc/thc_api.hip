@@ -747,6 +747,11 @@ int thc_decode_minmax(const void* sums, const float* range, uint32_t W, uint64_t
     if (!sums || !range || !out) return THC_ERR_NULL;
     if (!aligned(sums, 16) || !aligned(range, 8) || !aligned(out, out_dt == THC_F32 ? 4 : 2))
         return THC_ERR_ALIGN;
+    // without the rotation the decoder is elementwise: a kernel written for coalescing, whenever
+    // groups of 8 coordinates stay inside the sums buffer and the output allows 16-byte stores
+    if (!rotate && aligned(out, 16) && (padded_coords(n, chunk_log2) & 7u) == 0u)
+        return finish(thc::launch_unrotated_decode(sums, sum_bytes, range, W, bits, chunk_log2, n,
+                                                   out_dt == THC_BF16, out, static_cast<hipStream_t>(stream)));
     ChunkArgs a = base_args(n, chunk_log2, seed);
     a.in = sums;
     a.out = out;

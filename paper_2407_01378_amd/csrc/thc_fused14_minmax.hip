@@ -235,6 +235,76 @@ __global__ __launch_bounds__(256) void unrotated_aggregate_decode_kernel(const F
     }
 }
 
+// The same estimate from stored sums (thc_decode_minmax without rotation), any chunk size:
+// out[g] = float(S_g) * (step / W) + lo.  8 coordinates per thread: one 8- or 16-byte load,
+// 32 (fp32) or 16 (bf16) bytes stored.  bf16: round to nearest, ties to even.
+template <typename SUM, bool OUT_BF16>
+__global__ __launch_bounds__(256) void unrotated_decode_kernel(const SUM* sums, const float* range, uint32_t W,
+                                                               uint32_t levels, uint32_t chunk_log2, uint64_t n,
+                                                               uint64_t groups, void* out) {
+    const float Lf = (float)levels, Wf = (float)W;
+    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < groups;
+         k += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t g = k * 8u;
+        uint32_t S[8];
+        if constexpr (sizeof(SUM) == 1) {
+            const uint2 x = load_last_use(reinterpret_cast<const uint2*>(sums + g));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                S[e] = (x.x >> (8 * e)) & 0xFFu;
+                S[4 + e] = (x.y >> (8 * e)) & 0xFFu;
+            }
+        } else {
+            const uint4 x = load_last_use(reinterpret_cast<const uint4*>(sums + g));
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) S[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+        }
+        float x[8];
+        if (chunk_log2 >= 3u) {   // the 8 coordinates share a chunk
+            const uint64_t p = g >> chunk_log2;
+            const float lo = range[2 * p], hi = range[2 * p + 1];
+            const float q = ((hi - lo) / Lf) / Wf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = (float)S[e] * q + lo;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t p = (g + e) >> chunk_log2;
+                const float lo = range[2 * p], hi = range[2 * p + 1];
+                x[e] = (float)S[e] * (((hi - lo) / Lf) / Wf) + lo;
+            }
+        }
+        if constexpr (OUT_BF16) {
+            uint16_t* dst = static_cast<uint16_t*>(out) + g;
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t u = __float_as_uint(x[e]);
+                h[e] = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+            }
+            if (g + 8u <= n) {
+                *reinterpret_cast<uint4*>(dst) =
+                    make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (g + e < n) dst[e] = (uint16_t)h[e];
+            }
+        } else {
+            float* dst = static_cast<float*>(out) + g;
+            if (g + 8u <= n) {
+                store_streaming(dst, x[0], x[1], x[2], x[3]);
+                store_streaming(dst + 4, x[4], x[5], x[6], x[7]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (g + e < n) dst[e] = x[e];
+            }
+        }
+    }
+}
+
 template <auto kernel>
 uint32_t resident_grid_minmax() {
     static uint32_t cached = 0;   // one per kernel
@@ -300,6 +370,33 @@ hipError_t launch_unrotated_aggregate_decode(const FusedPayloadPtrs& ptrs, uint3
     else
         hipLaunchKernelGGL(k14::unrotated_aggregate_decode_kernel<8>, grid, block, 0, stream, ptrs, W, range, levels,
                            n, groups, out);
+    return hipGetLastError();
+}
+
+// Tuned form of the unrotated thc_decode_minmax: sums, range and out as for that call; `out`
+// 16-byte aligned.  The sums buffer holds whole chunks, so groups of 8 never run past it
+// (chunks of fewer than 8 coordinates: the padded size is still a multiple of 8 only if
+// chunks * c is; the caller checks).
+hipError_t launch_unrotated_decode(const void* sums, uint32_t sum_bytes, const float* range, uint32_t W,
+                                   uint32_t bits, uint32_t chunk_log2, uint64_t n, bool out_bf16, void* out,
+                                   hipStream_t stream) {
+    const uint64_t groups = (n + 7u) / 8u;
+    if (groups == 0) return hipSuccess;
+    uint64_t blocks = (groups + 255u) / 256u;
+    if (blocks > 256u * 16u) blocks = 256u * 16u;
+    const dim3 grid((uint32_t)blocks), block(256);
+    const uint32_t levels = grid_levels(bits, false);
+#define THC_UNROT(T, B)                                                                                      \
+    hipLaunchKernelGGL((k14::unrotated_decode_kernel<T, B>), grid, block, 0, stream, static_cast<const T*>(sums), \
+                       range, W, levels, chunk_log2, n, groups, out)
+    if (sum_bytes == 1) {
+        if (out_bf16) THC_UNROT(uint8_t, true);
+        else THC_UNROT(uint8_t, false);
+    } else {
+        if (out_bf16) THC_UNROT(uint16_t, true);
+        else THC_UNROT(uint16_t, false);
+    }
+#undef THC_UNROT
     return hipGetLastError();
 }
 

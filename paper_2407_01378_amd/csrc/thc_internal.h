@@ -135,6 +135,9 @@ hipError_t launch_encode_all_minmax(const EncodeAllArgs& a, const FusedWorkerPtr
                                     uint32_t bits, hipStream_t stream);
 hipError_t launch_unrotated_aggregate_decode(const FusedPayloadPtrs& ptrs, uint32_t W, const float* range,
                                              uint32_t bits, uint64_t n, float* out, hipStream_t stream);
+hipError_t launch_unrotated_decode(const void* sums, uint32_t sum_bytes, const float* range, uint32_t W,
+                                   uint32_t bits, uint32_t chunk_log2, uint64_t n, bool out_bf16, void* out,
+                                   hipStream_t stream);
 bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes);
 hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
                                  uint64_t payload_bytes, void* sums, hipStream_t stream);
