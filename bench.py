@@ -226,20 +226,6 @@ class FullPath:
         return False
 
 
-def time_region(torch, fn, reps):
-    """Milliseconds per repetition of fn(): HIP events recorded on the stream the
-    kernels are launched on (torch's current stream)."""
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
-
-
 def time_steps(torch, fn, steps):
     """Exactly `steps` repetitions of fn(), bracketed by synchronisation on both sides, with
     one HIP event between consecutive repetitions (no synchronisation in between).
@@ -354,7 +340,7 @@ def copy_bandwidth(torch, dev):
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
     dst.copy_(src)
-    ms = time_region(torch, lambda: dst.copy_(src), 10)
+    ms = time_steps(torch, lambda: dst.copy_(src), 10)[0]
     return 2.0 * src.numel() * 4 / (ms * 1e-3) / 1e9
 
 
@@ -432,7 +418,7 @@ def quality(thc, torch, wl, bits, xs, dev):
     res = {}
     for name, fn in variants:
         fn()
-        ms = time_region(torch, fn, 5)
+        ms = time_steps(torch, fn, 5)[0]
         err = float(((out - mean) ** 2).sum() / (mean ** 2).sum())
         res[name] = {"vnmse": err, "ms_per_bucket": round(ms, 4),
                      "gradient_GBps": round(W * ln * (2 if wl.dtype == "bf16" else 4) / (ms * 1e-3) / 1e9, 1)}
@@ -475,10 +461,10 @@ def topkc_bench(thc, torch, wl, xs, dev, a):
         torch.cuda.synchronize()
     for _ in range(a.warmup):
         step()
-    ms = time_region(torch, step, a.steps)
+    ms = time_steps(torch, step, a.steps)[0]
     kernels = {}
     for name, (fn, calls) in phases.items():
-        t = time_region(torch, fn, max(2, a.steps // 2))
+        t = time_steps(torch, fn, max(3, a.steps // 2))[0]
         kernels[name] = dict(ms_per_step=round(t, 4), launches_per_step=calls,
                              us_per_launch=round(1e3 * t / calls, 3))
     step()
@@ -608,7 +594,7 @@ def main():
         def run(fn=fn):
             for it in path.items:
                 fn(it)
-        t = time_region(torch, run, max(2, a.steps // 2))
+        t = time_steps(torch, run, max(3, a.steps // 2))[0]   # median: one disturbed repetition must not show
         kernels[name] = dict(ms_per_step=round(t, 4), launches_per_step=nb * per_bucket,
                              us_per_launch=round(1e3 * t / (nb * per_bucket), 3))
 
@@ -616,9 +602,8 @@ def main():
     # a kernel that reads what the previous one just wrote finds part of it in the 256 MB
     # last-level cache, so its duration there differs from that of the back-to-back loop above.
     if not a.full_rotation:
-        tot = dict.fromkeys(path.phases, 0.0)
-        reps = 3
-        for _ in range(reps):
+        per_rep = {name: [] for name in path.phases}
+        for _ in range(3):
             evs = [torch.cuda.Event(enable_timing=True)]
             torch.cuda.synchronize()
             evs[0].record()
@@ -628,10 +613,13 @@ def main():
                     evs.append(torch.cuda.Event(enable_timing=True))
                     evs[-1].record()
             torch.cuda.synchronize()
+            tot = dict.fromkeys(path.phases, 0.0)
             for i, name in enumerate(list(path.phases) * nb):
                 tot[name] += evs[i].elapsed_time(evs[i + 1])
+            for name in tot:
+                per_rep[name].append(tot[name])
         for name, (_, per_bucket) in path.phases.items():
-            kernels[name]["us_per_launch_in_step"] = round(1e3 * tot[name] / (reps * nb * per_bucket), 3)
+            kernels[name]["us_per_launch_in_step"] = round(1e3 * sorted(per_rep[name])[1] / (nb * per_bucket), 3)
 
     # Dominant kernel and its algorithmic bytes per launch.  Per worker-coordinate the
     # encode step must read the gradient once and write its payload once.
@@ -749,8 +737,8 @@ def main():
             torch.cuda.synchronize()
             assert not thc.thc_encode_all_timed_out(wsb) and torch.equal(ref_out, path.items[-1]["out"])
             b_med, b_mean, b_min, b_max = time_steps(torch, batched, max(3, a.steps // 2))
-            enc_b = time_region(torch, lambda: thc.thc_encode_all_batch(bk, wl.chunk_log2, bits, wsb), 3)
-            dec_b = time_region(torch, lambda: thc.thc_aggregate_decode_batch(bk, wl.chunk_log2, bits, wsb), 3)
+            enc_b = time_steps(torch, lambda: thc.thc_encode_all_batch(bk, wl.chunk_log2, bits, wsb), 5)[0]
+            dec_b = time_steps(torch, lambda: thc.thc_aggregate_decode_batch(bk, wl.chunk_log2, bits, wsb), 5)[0]
             res["batched"] = {"form": "thc_encode_all_batch + thc_aggregate_decode_batch, all buckets per call",
                               "ms_per_step": round(b_med, 4), "value": round(W * wl.n * s_in / (b_med * 1e-3) / 1e9, 2),
                               "pct_hbm_peak": round(100.0 * wl.n * alg_bytes_per_coord / (b_med * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
