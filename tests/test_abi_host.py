@@ -280,3 +280,20 @@ def test_one_pass_minmax_entry_points_validate_on_the_host(L):
     assert dec(pg, 4, nul, 100, 14, 0, 4, 1, p, nul) == -1
     assert dec(podd, 4, p, 100, 14, 0, 4, 0, p, nul) == -8
     assert dec(pg, 4, p, 100, 14, 0, 4, 0, ctypes.c_void_p(0x1004), nul) == -8
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/thc.h is a C header: it compiles as C99 with pedantic warnings as errors, and
+    as C++ (the library's own translation units include it that way)."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use_thc.c"
+    src.write_text('#include "thc.h"\nint main(void) { thc_dtype d = THC_BF16; thc_bucket b; (void)b; '
+                   "return d == 1 && THC_ERR_ALIGN == -8 ? 0 : 1; }\n")
+    inc = os.path.join(ROOT, "include")
+    for cc, flags in (("gcc", ["-std=c99", "-pedantic-errors"]), ("g++", ["-std=c++17", "-x", "c++"])):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} is not installed")
+        res = subprocess.run([cc, *flags, "-Wall", "-Wextra", "-Werror", f"-I{inc}", "-fsyntax-only", str(src)],
+                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout
