@@ -28,6 +28,11 @@ constexpr int kWavesPerSimd = 4;
 // Pauses of the wait for the peers' range words, in units of 64 clocks (s_sleep).
 constexpr int kFirstPollSleep = 32;
 constexpr int kPollSleep = 8;
+// Above this many workers the one-pass encoder publishes one range word per workgroup.
+#ifndef THC_WGWORD_ABOVE
+#define THC_WGWORD_ABOVE 16
+#endif
+constexpr uint32_t kPerWaveWordsMaxWorkers = THC_WGWORD_ABOVE;
 // ------------------------------------------------------------------ encode_all
 // The records of a batched launch were written by earlier kernels and are never written by
 // this one: reading them through the constant address space lets the compiler use scalar
@@ -70,8 +75,15 @@ struct BucketView {
 // symmetrically around zero: every wave publishes two words (the maximum, then the negated
 // minimum, both through order_key() so that both are combined by a maximum), `scale` receives
 // (lo, hi) pairs, and the quantizer subtracts lo.
-template <bool BF16, bool ODD, bool BATCH, bool MINMAX = false>
+// WGWORD: one range word per WORKGROUP instead of one per wave (the waves' maxima are combined
+// through LDS at the barrier that opens the last exchange, and wave 0 publishes and clears).
+// For many workers: with W = 64 a chunk would otherwise have 512 words, every polling wave
+// would read 2 KB per poll, and that traffic delays the words it waits for.  At W = 8 the
+// later publication costs more than the lighter polls save, so the per-wave form stays.
+template <bool BF16, bool ODD, bool BATCH, bool MINMAX = false, bool WGWORD = false>
 struct EncodeAllCtx {
+    static_assert(!(MINMAX && WGWORD), "the per-workgroup word exists for the symmetric grid only");
+    static constexpr uint32_t kWordsPerWorker = WGWORD ? 1u : kWaves;
     static constexpr int kUnits = BF16 ? 4 : 8;
     static constexpr int kElem = BF16 ? 2 : 4;
     // bf16: every thread loads its own 64 consecutive bytes one item ahead, so the input
@@ -187,6 +199,23 @@ struct EncodeAllCtx {
                 __hip_atomic_store(&a.slots[p * nwords + kWaves * a.W + kWaves * w + wave], klo, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
+        } else if constexpr (WGWORD) {
+            const float m = wave_absmax(v) * kInvSqrtC;
+            if (lane == 0) sh.red[wave] = m;
+            // l3_to_l4e with the publication behind its first barrier
+            __syncthreads();
+            set_prio<true, kPrioExchange>();
+            if (wave == 0 && lane == 0) {
+                float mw = fmaxf(fmaxf(fmaxf(sh.red[0], sh.red[1]), fmaxf(sh.red[2], sh.red[3])),
+                                 fmaxf(fmaxf(sh.red[4], sh.red[5]), fmaxf(sh.red[6], sh.red[7])));
+                __hip_atomic_store(&a.slots[p * nwords + w], __float_as_uint(mw) | 0x80000000u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+            x3e_store(sh, v, lane, wave);
+            __syncthreads();
+            x3e_load(sh, v, lane, wave);
+            set_prio<true, kPrioTail>();
+            return;
         } else {
             const float m = wave_absmax(v) * kInvSqrtC;
             if (lane == 0)
@@ -263,8 +292,8 @@ struct EncodeAllCtx {
         // which every wave of its workgroup reaches only after reading the words of
         // the workgroup's previous chunk; with all of this chunk's words seen, nobody
         // will read the previous chunk's words again, and this wave clears its own.
-        if (done && prev != kNone && lane == 0) {
-            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * w + wave], 0u,
+        if (done && prev != kNone && lane == 0 && (!WGWORD || wave == 0)) {
+            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWordsPerWorker * w + (WGWORD ? 0u : wave)], 0u,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (MINMAX)
                 __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * a.W + kWaves * w + wave], 0u,
@@ -319,15 +348,15 @@ struct EncodeAllCtx {
 // Items are (chunk, worker) pairs; workgroup g of a grid of G (a multiple of W) takes worker
 // g mod W of chunks g / W, g / W + G / W, ...  The peers of an item are therefore items of
 // the same round of other workgroups, and with every workgroup resident no wait is circular.
-template <bool BF16, int BITS, bool ODD, bool BATCH, bool MINMAX = false>
+template <bool BF16, int BITS, bool ODD, bool BATCH, bool MINMAX = false, bool WGWORD = false>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(const EncodeAllArgs a,
                                                                  const FusedWorkerPtrs ptrs,
                                                                  const BatchArgs batch) {
     __shared__ Shared sh;
-    using Ctx = EncodeAllCtx<BF16, ODD, BATCH, MINMAX>;
+    using Ctx = EncodeAllCtx<BF16, ODD, BATCH, MINMAX, WGWORD>;
     const uint32_t t = threadIdx.x;
     const uint32_t p0 = blockIdx.x / a.W;
-    Ctx c{a, ptrs, batch, sh, {}, t, t & 63u, t >> 6, (MINMAX ? 2u : 1u) * kWaves * a.W, blockIdx.x - p0 * a.W,
+    Ctx c{a, ptrs, batch, sh, {}, t, t & 63u, t >> 6, (MINMAX ? 2u : 1u) * Ctx::kWordsPerWorker * a.W, blockIdx.x - p0 * a.W,
           gridDim.x / a.W, 0u, Ctx::kNone, 0u, 0u, {}, {}};
     if (p0 >= a.chunks) return;
     c.cur = c.nxt = c.view_of(p0);
@@ -824,6 +853,13 @@ hipError_t launch_encode_all_t(const EncodeAllArgs& a, const FusedWorkerPtrs& pt
     // fewer resident workgroups than workers would leave peers that never run
     if (G < a.W) return hipErrorInvalidConfiguration;
     G -= G % a.W;
+    if constexpr (!BATCH) {
+        if (a.W > kPerWaveWordsMaxWorkers) {   // many workers: one range word per workgroup
+            hipLaunchKernelGGL((encode_all_kernel<BF16, BITS, ODD, false, false, true>), dim3(G), dim3(kThreads), 0,
+                               stream, a, ptrs, batch);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((encode_all_kernel<BF16, BITS, ODD, BATCH>), dim3(G), dim3(kThreads), 0, stream, a, ptrs,
                        batch);
     return hipGetLastError();
