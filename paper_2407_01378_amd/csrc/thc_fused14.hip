@@ -439,11 +439,16 @@ __device__ __forceinline__ PayloadWords<BITS> load_payload_words(const uint8_t* 
 
 // Sum of the workers' payload words of one thread (its 32 coordinates) in sub-word lanes,
 // built up group by group: a group is the payload of kGroup workers in flight at once.
-template <int BITS, bool BATCH = false>
+// WIDE: 16-bit accumulators for 4-bit payloads too (W * L > 255: more than 17 workers); lane q
+// then holds coordinates q (low half) and q + 16 / BITS (high half) of the dword's 32 / BITS.
+template <int BITS, bool BATCH = false, bool WIDE = false>
 struct PayloadSum {
+    static_assert(!(WIDE && BITS == 8), "8-bit payloads always sum in 16-bit lanes");
     static constexpr int kWords = BITS;                        // payload dwords per worker per thread
-    static constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;    // sub-word accumulators per dword
-    static constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    static constexpr int kLanes = BITS == 8 ? 2 : (WIDE ? 16 : 8) / BITS;   // sub-word accumulators per dword
+    static constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu
+                                      : WIDE    ? (BITS == 4 ? 0x000F000Fu : 0x00030003u)
+                                                : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
     static constexpr int kGroup = BITS == 8 ? 2 : 4;           // at most 16 registers in flight
     const FusedPayloadPtrs& ptrs;   // single bucket: the payload pointers, in the kernel arguments
     ConstU64Ptr pp;                 // batched: those of the bucket being summed, in its record
@@ -481,9 +486,9 @@ struct PayloadSum {
 
 // Called from inside the rotation of the current chunk: loads and sums the first three
 // worker groups of the workgroup's NEXT chunk, one exchange of latency apart.
-template <int BITS, bool BATCH>
+template <int BITS, bool BATCH, bool WIDE>
 struct NextChunkLoads {
-    PayloadSum<BITS, BATCH>& sum;
+    PayloadSum<BITS, BATCH, WIDE>& sum;
     uint64_t byte0;
     bool active;
     template <int K>
@@ -505,12 +510,12 @@ struct DecodeView {
 };
 
 // RANGED: `scale` holds (lo, hi) pairs of the min/max grid instead of the symmetric scale.
-template <int BITS, bool BATCH, bool RANGED = false>
+template <int BITS, bool BATCH, bool RANGED = false, bool WIDE = false>
 __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kernel(const AggDecodeArgs a,
                                                                        const FusedPayloadPtrs ptrs,
                                                                        const BatchArgs batch) {
     __shared__ Shared sh;
-    using Sum = PayloadSum<BITS, BATCH>;
+    using Sum = PayloadSum<BITS, BATCH, WIDE>;
     constexpr int kWords = Sum::kWords, kLanes = Sum::kLanes;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const float Lf = (float)((1u << BITS) - 1u);
@@ -569,6 +574,13 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
                 S[4 * d + 1] = sum.acc[d][1] & 0xFFFFu;
                 S[4 * d + 2] = sum.acc[d][0] >> 16;
                 S[4 * d + 3] = sum.acc[d][1] >> 16;
+            } else if (WIDE) {       // dword d: 32/BITS coordinates; lane q = coordinates q and q + 16/BITS
+                constexpr int per = 32 / BITS;
+#pragma unroll
+                for (int q = 0; q < kLanes; ++q) {
+                    S[per * d + q] = sum.acc[d][q] & 0xFFFFu;
+                    S[per * d + kLanes + q] = sum.acc[d][q] >> 16;
+                }
             } else {                 // dword d: 32/BITS coordinates; lane q byte b = coordinate (8/BITS) b + q
                 constexpr int per = 32 / BITS;
 #pragma unroll
@@ -582,7 +594,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         for (int r = 0; r < kRegs; ++r) v[r] = (float)S[r] * qf - s;
 
         if (!BATCH && a.sums) {   // the caller also wants the integer aggregate
-            if (BITS == 8) {
+            if (BITS == 8 || WIDE) {
                 uint16_t* dst = static_cast<uint16_t*>(a.sums) + g0 + 32u * t;
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -610,7 +622,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void aggregate_decode_kern
         DecodeView nxt = cur;
         if (BATCH && more && pn >= boundary) nxt = view_of(pn);   // rarely: a new bucket
         sum.pp = nxt.pp;
-        NextChunkLoads<BITS, BATCH> next{sum, (((pn - nxt.chunk0) << kChunkLog2) * BITS) / 8u + thread_byte, more};
+        NextChunkLoads<BITS, BATCH, WIDE> next{sum, (((pn - nxt.chunk0) << kChunkLog2) * BITS) / 8u + thread_byte, more};
         sum.clear();
         rotate_l1_to_l3<false>(sh, v, lane, wave, next);
         if (next.active) {
@@ -753,8 +765,11 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void sat_aggregate_decode_
 template <int BITS, typename SumT>
 __global__ __launch_bounds__(256) void aggregate_fast_kernel(const FusedPayloadPtrs ptrs, uint32_t W,
                                                              uint64_t vecs, SumT* sums) {
-    constexpr int kLanes = BITS == 8 ? 2 : 8 / BITS;
-    constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
+    constexpr bool kWide = BITS != 8 && sizeof(SumT) == 2;   // 16-bit lanes for 2- and 4-bit payloads
+    constexpr int kLanes = BITS == 8 ? 2 : (kWide ? 16 : 8) / BITS;
+    constexpr uint32_t kMask = BITS == 8 ? 0x00FF00FFu
+                               : kWide   ? (BITS == 4 ? 0x000F000Fu : 0x00030003u)
+                                         : (BITS == 4 ? 0x0F0F0F0Fu : 0x03030303u);
     constexpr int kCoords = 128 / BITS;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vecs;
          i += (uint64_t)gridDim.x * blockDim.x) {
@@ -779,7 +794,22 @@ __global__ __launch_bounds__(256) void aggregate_fast_kernel(const FusedPayloadP
                 }
         }
         SumT* dst = sums + i * kCoords;
-        if (BITS == 8) {   // u16 sums: (even, odd) pairs
+        if constexpr (kWide) {   // lane q = coordinates q (low half) and q + kLanes (high half) of the dword
+            constexpr int per = 32 / BITS;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t o[per / 2];   // pairs of consecutive coordinates
+#pragma unroll
+                for (int c = 0; c < per; c += 2) {
+                    const uint32_t lo = c < kLanes ? (acc[d][c] & 0xFFFFu) : (acc[d][c - kLanes] >> 16);
+                    const uint32_t hi = c + 1 < kLanes ? (acc[d][c + 1] & 0xFFFFu) : (acc[d][c + 1 - kLanes] >> 16);
+                    o[c / 2] = lo | (hi << 16);
+                }
+#pragma unroll
+                for (int k = 0; k < per / 8; ++k)
+                    reinterpret_cast<uint4*>(dst + per * d)[k] = make_uint4(o[4 * k], o[4 * k + 1], o[4 * k + 2], o[4 * k + 3]);
+            }
+        } else if (BITS == 8) {   // u16 sums: (even, odd) pairs
             uint32_t o[8];
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -883,10 +913,27 @@ hipError_t launch_encode_all_pick(const EncodeAllArgs& a, const FusedWorkerPtrs&
     return launch_encode_all_t<false, 8, false, BATCH>(a, ptrs, batch, stream);
 }
 
+// 2- and 4-bit payloads of so many workers that the sums need 16 bits (single-bucket forms only).
+template <int BITS, bool RANGED>
+hipError_t launch_aggregate_decode_wide(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, hipStream_t stream) {
+    uint32_t G = resident_grid<aggregate_decode_kernel<BITS, false, RANGED, true>>();
+    if (G == 0) return hipErrorInvalidValue;
+    if (G > a.chunks) G = (uint32_t)a.chunks;
+    const BatchArgs none{};
+    hipLaunchKernelGGL((aggregate_decode_kernel<BITS, false, RANGED, true>), dim3(G), dim3(kThreads), 0, stream, a,
+                       ptrs, none);
+    return hipGetLastError();
+}
+// (2-bit payloads would need more than 85 workers, beyond what the one-launch forms take)
+__host__ inline bool wide_sums(uint32_t W, uint32_t bits) { return bits == 4u && W * 15u > 255u; }
+
 template <bool BATCH>
 hipError_t launch_aggregate_decode_pick(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, const BatchArgs& batch,
                                         uint32_t bits, hipStream_t stream) {
     if (a.chunks == 0) return hipSuccess;
+    if constexpr (!BATCH) {
+        if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, false>(a, ptrs, stream);
+    }
     uint32_t G = 0;
     if (bits == 2) G = resident_grid<aggregate_decode_kernel<2, BATCH>>();
     else if (bits == 4) G = resident_grid<aggregate_decode_kernel<4, BATCH>>();
@@ -1009,7 +1056,12 @@ bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t
     // when that is also the width the caller's buffer has (one worker of 8-bit payloads
     // has one-byte sums and takes the unfused path).
     const uint32_t top = W * ((1u << bits) - 1u);
-    return bits == 8 ? (top > 255u && top <= 65535u) : top <= 255u;
+    return bits == 8 ? (top > 255u && top <= 65535u) : top <= 65535u;
+}
+
+bool aggregate_decode_batch_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
+    // the batched kernels are compiled for the narrow accumulators only
+    return aggregate_decode_fused_applicable(W, chunk_log2, bits) && !k14::wide_sums(W, bits);
 }
 
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
@@ -1022,6 +1074,7 @@ hipError_t launch_aggregate_decode_ranged(const AggDecodeArgs& a, const FusedPay
                                           uint32_t bits, hipStream_t stream) {
     using namespace k14;
     if (a.chunks == 0) return hipSuccess;
+    if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, true>(a, ptrs, stream);
     uint32_t G = bits == 2   ? resident_grid<aggregate_decode_kernel<2, false, true>>()
                  : bits == 4 ? resident_grid<aggregate_decode_kernel<4, false, true>>()
                              : resident_grid<aggregate_decode_kernel<8, false, true>>();
@@ -1074,7 +1127,7 @@ hipError_t launch_sat_aggregate_decode_fused(const SatAggDecodeArgs& a, const Fu
 
 bool aggregate_fast_applicable(uint32_t W, uint32_t bits, uint32_t sum_bytes, uint64_t payload_bytes) {
     if (W > (uint32_t)kMaxFusedPayloads || (payload_bytes & 15u)) return false;
-    return (bits == 8 && sum_bytes == 2) || (bits != 8 && sum_bytes == 1);
+    return (bits != 2 && sum_bytes == 2) || (bits != 8 && sum_bytes == 1);
 }
 
 hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint32_t bits,
@@ -1087,7 +1140,10 @@ hipError_t launch_aggregate_fast(const FusedPayloadPtrs& ptrs, uint32_t W, uint3
     const uint64_t cap = (uint64_t)(cus > 0 ? cus : 256) * 16u;
     if (blocks > cap) blocks = cap;
     const dim3 grid((uint32_t)blocks), block(256);
-    if (bits == 2)
+    if (wide_sums(W, bits))   // 4-bit payloads of more than 17 workers: the sums take 16 bits
+        hipLaunchKernelGGL((aggregate_fast_kernel<4, uint16_t>), grid, block, 0, stream, ptrs, W, vecs,
+                           static_cast<uint16_t*>(sums));
+    else if (bits == 2)
         hipLaunchKernelGGL((aggregate_fast_kernel<2, uint8_t>), grid, block, 0, stream, ptrs, W, vecs,
                            static_cast<uint8_t*>(sums));
     else if (bits == 4)

@@ -80,7 +80,8 @@ def test_scales_outside_and_across_the_folded_range(dtype, bits):
 def test_is_fused_predicate():
     assert thc.thc_aggregate_decode_is_fused(8, 14, 4)
     assert thc.thc_aggregate_decode_is_fused(17, 14, 4)
-    assert not thc.thc_aggregate_decode_is_fused(18, 14, 4)
+    assert thc.thc_aggregate_decode_is_fused(18, 14, 4) and thc.thc_aggregate_decode_is_fused(64, 14, 4)   # 16-bit lanes
+    assert not thc.thc_aggregate_decode_is_fused(65, 14, 4)
     assert thc.thc_aggregate_decode_is_fused(8, 14, 8)
     # one worker of 8-bit payloads has one-byte sums; the fused kernel stores 16-bit lanes
     assert thc.thc_sum_bytes(1, 8) == 1 and not thc.thc_aggregate_decode_is_fused(1, 14, 8)

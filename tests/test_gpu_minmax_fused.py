@@ -45,6 +45,7 @@ def run_fused(xs, seed, bits, rotate, fill=0x5A):
     (8, 5, torch.float32, 1 << 14, False),
     (4, 1, torch.float32, 40, True),                      # one worker, one ragged chunk
     (4, 64, torch.bfloat16, (1 << 14) + 2, False),        # the largest worker count
+    (4, 20, torch.bfloat16, (2 << 14) + 2, True),         # sums of 20 workers need 16-bit accumulators
     (4, 8, torch.bfloat16, 700 << 14, True),              # more chunks than resident workgroups: several rounds
     (4, 8, torch.bfloat16, (700 << 14) + 3, False),
 ])
@@ -126,8 +127,8 @@ def test_one_pass_minmax_refuses_what_it_does_not_cover():
     with pytest.raises(thc.ThcError) as e:
         thc.thc_aggregate_decode_minmax(pay, rng, n, 10, 0, 4, True, out)
     assert e.value.status == -3
-    with pytest.raises(thc.ThcError) as e:                 # 18 workers of 4 bits need 16-bit sums: not fused
-        thc.thc_aggregate_decode_minmax(pay * 5, rng, n, L14, 0, 4, True, out)
+    with pytest.raises(thc.ThcError) as e:                 # more workers than the one-launch forms take
+        thc.thc_aggregate_decode_minmax(pay * 17, rng, n, L14, 0, 4, True, out)
     assert e.value.status == -4
     with pytest.raises(thc.ThcError) as e:
         thc.thc_aggregate_decode_minmax(pay, rng, n, L14, 0, 4, True, torch.empty(n + 1, device=DEV)[1:])
