@@ -1055,6 +1055,7 @@ bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t
     // The kernel stores the sums at the width of its lanes, so the shape qualifies only
     // when that is also the width the caller's buffer has (one worker of 8-bit payloads
     // has one-byte sums and takes the unfused path).
+    static_assert(kMaxFusedPayloads * 3 <= 255, "2-bit payloads have narrow lanes only");
     const uint32_t top = W * ((1u << bits) - 1u);
     return bits == 8 ? (top > 255u && top <= 65535u) : top <= 65535u;
 }
