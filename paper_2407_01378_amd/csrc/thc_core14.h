@@ -399,9 +399,12 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 //     t = y * inv + L/2 + (r + 0.5) / 256.
 // Min/max grid on [lo, hi] (RANGED):  sub = lo, mul = L / (hi - lo), base = 2^-9.
 //   g        global index of the thread's first coordinate
-//   CLAMP    false only for the symmetric grid with s the largest |y| of the chunk: then
-//            0 < t < L + 1 for every coordinate (|y * inv| <= L/2 (1 + 2^-24) and
-//            2^-9 <= c - L/2 <= 255.5 / 256), so the minimum with L never binds
+//   CLAMP    false only when the range is the chunk's own: the symmetric grid with s the
+//            largest |y| of the chunk (then 0 < t < L + 1 for every coordinate: |y * inv| <=
+//            L/2 (1 + 2^-24) and 2^-9 <= c - L/2 <= 255.5 / 256), or the min/max grid with
+//            lo and hi the chunk's extremes (fl(y - lo) <= fl(hi - lo) = width, and width *
+//            fl(L / width) <= L (1 + 2^-24), so t < L + 255.5/256 + L 2^-24 < L + 1); the
+//            minimum with L never binds.  A range handed in by a caller keeps the clamp.
 //   FOLD     y = v * 2^-7 is not formed; mul already carries the factor 2^-7 and sub is given
 //            in v's units (v - 2^7 lo = 2^7 (y - lo), rounded alike).  Exact as long
 //            as the power of two moves nothing into the subnormal range or past the largest
@@ -508,7 +511,7 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
 
 // Min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo) (0 for a constant chunk).
 // ROTATED false: v holds y itself (the unrotated, zero-padded gradient), not 2^7 y.
-template <int BITS, bool ROTATED = true>
+template <int BITS, bool ROTATED = true, bool CLAMP = true>
 __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], float lo, float hi, uint32_t L,
                                                      uint64_t g0, uint32_t worker, uint32_t key0,
                                                      uint32_t key1, uint8_t* payload, uint32_t t) {
@@ -516,7 +519,7 @@ __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], fl
     const float inv = width != 0.0f ? (float)L / width : 0.0f;
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];
-    quantize_pack<BITS, true, !ROTATED, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);
+    quantize_pack<BITS, CLAMP, !ROTATED, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);
     store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 

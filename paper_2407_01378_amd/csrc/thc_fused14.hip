@@ -312,7 +312,8 @@ struct EncodeAllCtx {
                 range[2 * pl] = lo;
                 range[2 * pl + 1] = hi;
             }
-            quantize_store_range<BITS, true>(v, lo, hi, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1,
+            // (no clamp: lo and hi are the chunk's own extremes, see quantize_pack)
+            quantize_store_range<BITS, true, false>(v, lo, hi, a.levels, pl << kChunkLog2, w, cur.key0, cur.key1,
                                              global_ptr<uint8_t>(reinterpret_cast<uint64_t>(cur.payload)), t);
             return;
         }

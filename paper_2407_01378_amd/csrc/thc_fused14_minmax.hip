@@ -24,6 +24,10 @@ constexpr uint32_t kWaves = kThreads / 64;
 constexpr int kWavesPerSimd = 4;   // two workgroups of 8 waves per CU
 constexpr int kFirstPollSleep = 32;
 constexpr int kPollSleep = 8;
+// lo and hi are the chunk's own extremes over all workers: fl(y - lo) <= fl(hi - lo) and
+// (hi - lo) * fl(L / (hi - lo)) <= L (1 + 2^-24), so t < L + 255.5/256 + L 2^-24 < L + 1 and
+// the minimum with L never binds
+constexpr bool kClampRanged = false;
 
 // ---- the range words of a chunk: two per wave of every worker's workgroup, the maxima
 // first, then the negated minima (so that both are combined by a maximum) ----------------
@@ -44,11 +48,12 @@ struct Words {
     // Waits until every wave of every worker of chunk p has published; bounded by
     // a.max_spins polls, after which the error word is set and the wave carries on with
     // what it has seen and its own range (khi, klo).  Returns the keys of (hi, -lo).
+    template <bool SLEEP_FIRST = true>
     __device__ __forceinline__ bool wait(uint64_t p, uint32_t& khi, uint32_t& klo) const {
         const uint32_t* slot = a.slots + p * nwords;
         uint32_t mxh = 0u, mxl = 0u;
         bool done = false;
-        __builtin_amdgcn_s_sleep(kFirstPollSleep);
+        if (SLEEP_FIRST) __builtin_amdgcn_s_sleep(kFirstPollSleep);
         for (uint32_t spins = 0;; ++spins) {
             uint32_t all_valid = 1u;
             mxh = mxl = 0u;
@@ -108,9 +113,8 @@ constexpr uint32_t kNone = 0xFFFFFFFFu;
 // quantizer wants.  An item has nothing to do between publishing its range and reading its
 // peers', so the time the words take to travel is exposed; what hides it is more workgroups
 // per CU: the bf16 form needs no LDS at all and is compiled for three workgroups per CU
-// (85 registers) instead of two.  (Handling items in pairs - publish both, then wait for
-// the first while the second one's words travel - was measured and is slower: 64 live
-// values per thread spill.)
+// (85 registers) instead of two.  This kernel serves fp32 input and bf16 input with an odd
+// number of coordinates; bf16 input otherwise takes the pipelined kernel below.
 template <bool BF16, int BITS>
 __global__ __launch_bounds__(kThreads, BF16 ? 6 : kWavesPerSimd) void encode_all_unrotated_kernel(
     const EncodeAllArgs a, const FusedWorkerPtrs ptrs) {
@@ -180,10 +184,117 @@ __global__ __launch_bounds__(kThreads, BF16 ? 6 : kWavesPerSimd) void encode_all
             a.scale[2 * p] = lo;
             a.scale[2 * p + 1] = hi;
         }
-        quantize_store_range<BITS, false>(v, lo, hi, a.levels, p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        quantize_store_range<BITS, false, kClampRanged>(v, lo, hi, a.levels, p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
         __syncthreads();   // every wave has read this chunk's words (and the buffer) before the next item
     }
     if (wave == 0) words.count_off(prev);   // behind the barrier that ended the last item
+}
+
+// A thread's 32 consecutive bf16 coordinates (four 16-byte units) as fp32 values.
+__device__ __forceinline__ void widen_bf16(const uint4 (&unit)[4], float (&v)[kRegs]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t x[4] = {unit[k].x, unit[k].y, unit[k].z, unit[k].w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            v[8 * k + 2 * d] = __uint_as_float(x[d] << 16);
+            v[8 * k + 2 * d + 1] = __uint_as_float(x[d] & 0xFFFF0000u);
+        }
+    }
+}
+
+// The bf16 form of the same, as a pipeline three items deep.  A thread's 32 coordinates are
+// 16 registers while they stay packed, so a wave can hold the item it quantizes, the next
+// one (whose range it has already published) and the loads of the one after that: by the
+// time an item is quantized its peers' words were published a whole item ago and the wait
+// is one read.  No LDS and no barrier: every wave publishes, polls and clears for itself.
+// A wave that has seen all words of item k knows that every wave of every peer has
+// published k, which a wave does after its wait for item k - 2: nobody reads the words of
+// k - 2 again, and the wave clears its own.  The last two items of a workgroup are counted
+// off by the workgroups of their chunks as in the other kernels.
+template <int BITS>
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_unrotated_bf16_kernel(
+    const EncodeAllArgs a, const FusedWorkerPtrs ptrs) {
+    constexpr int kUnits = 4;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t p0 = blockIdx.x / a.W;
+    const uint32_t w = blockIdx.x - p0 * a.W;
+    const uint32_t dp = gridDim.x / a.W;
+    const Words words{a, kWaves * a.W, 2u * kWaves * a.W, kWaves * w + wave, lane};
+    if (p0 >= a.chunks) return;
+    // Through a buffer descriptor whose range is the part of the chunk that exists (n is even:
+    // the range check works on dwords): reads beyond it return zero, and a chunk past the end
+    // has range 0, so the loads are unconditional.
+    auto load = [&](Raw<kUnits>& raw, uint64_t p) {
+        const uint64_t g0 = p << kChunkLog2;
+        uint64_t left = p < a.chunks ? a.n - g0 : 0u;
+        if (left > (uint64_t)kChunk) left = kChunk;
+        uint64_t addr = reinterpret_cast<uint64_t>(ptrs.grad[w]) + (p < a.chunks ? g0 * 2u : 0u);
+        addr = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(addr >> 32)) << 32) |
+               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr);
+        __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, (uint32_t)left * 2u, 0x00020000);
+        typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < kUnits; ++j) {
+            const u4v q = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (kUnits * t + j) * 16u, 0, 0);
+            raw.u[j] = make_uint4(q.x, q.y, q.z, q.w);
+        }
+    };
+    // this wave's share of the item's range, published
+    auto announce = [&](const Raw<kUnits>& raw, uint64_t p, uint32_t& khi, uint32_t& klo) {
+        float v[kRegs];
+        widen_bf16(raw.u, v);
+        const MinMax m = thread_minmax(v);
+        khi = wave_umax(order_key(m.hi));
+        klo = wave_umax(order_key(-m.lo));
+        words.publish(p, khi, klo);
+    };
+    Raw<kUnits> r0, r1, r2;
+    load(r0, p0);
+    load(r1, (uint64_t)p0 + dp);
+    uint32_t khi, klo, nhi = 0u, nlo = 0u;
+    announce(r0, p0, khi, klo);
+    uint32_t prev1 = kNone, prev2 = kNone;
+    // One item: `cur` holds item p, `next` item p + dp (in flight since the item before),
+    // `far` is free and receives item p + 2 dp.
+    auto item = [&](Raw<kUnits>& cur, Raw<kUnits>& next, Raw<kUnits>& far, uint64_t p) {
+        if (p + dp < a.chunks) announce(next, p + dp, nhi, nlo);
+        const bool done = words.wait<false>(p, khi, klo);
+        // (after the wait: vector-memory operations complete in order, so a load issued before
+        // the read of the words would have to arrive before that read is seen)
+        load(far, p + 2u * dp);
+        if (done && prev2 != kNone) words.clear_mine(prev2);
+        prev2 = prev1;
+        prev1 = (uint32_t)p;
+        const float hi = order_value(khi), lo = -order_value(klo);
+        if (w == 0 && t == 0) {
+            a.scale[2 * p] = lo;
+            a.scale[2 * p + 1] = hi;
+        }
+        float v[kRegs];
+        widen_bf16(cur.u, v);
+        quantize_store_range<BITS, false, kClampRanged>(v, lo, hi, a.levels, p << kChunkLog2, w, a.key0, a.key1, ptrs.payload[w], t);
+        khi = nhi;
+        klo = nlo;
+    };
+    // (three items per trip so that the register sets take turns without copies: a copy of a
+    // set whose loads are in flight would wait for them)
+    for (uint64_t p = p0; p < a.chunks;) {
+        item(r0, r1, r2, p);
+        p += dp;
+        if (p >= a.chunks) break;
+        item(r1, r2, r0, p);
+        p += dp;
+        if (p >= a.chunks) break;
+        item(r2, r0, r1, p);
+        p += dp;
+    }
+    __syncthreads();   // every wave has read the words of the last two items
+    if (wave == 0) {
+        if (prev2 != kNone) words.count_off(prev2);
+        words.count_off(prev1);
+    }
 }
 
 // out[g] = float(sum of the W indices of coordinate g) * (step / W) + lo, no rotation.
@@ -194,33 +305,28 @@ __global__ __launch_bounds__(256) void unrotated_aggregate_decode_kernel(const F
                                                                          const float* range, uint32_t levels,
                                                                          uint64_t n, uint64_t groups, float* out) {
     const float Lf = (float)levels, Wf = (float)W;
-    for (uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; k < groups;
-         k += (uint64_t)gridDim.x * blockDim.x) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    // the payload bytes of 8 coordinates of one worker, as one register pair
+    auto fetch = [&](uint32_t w, uint64_t k) -> uint2 {
+        const uint8_t* src = ptrs.p[w] + k * BITS;
+        if constexpr (BITS == 8) return load_last_use(reinterpret_cast<const uint2*>(src));
+        else if constexpr (BITS == 4) return make_uint2(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src)), 0u);
+        else return make_uint2(__builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(src)), 0u);
+    };
+    auto add = [&](uint32_t (&S)[8], const uint2 x) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if constexpr (BITS == 8) S[e] += ((e < 4 ? x.x : x.y) >> (8 * (e & 3))) & 0xFFu;
+            else if constexpr (BITS == 4) S[e] += (x.x >> (4 * e)) & 0xFu;
+            else S[e] += (x.x >> (2 * e)) & 0x3u;
+        }
+    };
+    auto finish = [&](const uint32_t (&S)[8], uint64_t k) {
         const uint64_t g = k * 8u;
         const uint64_t p = g >> kChunkLog2;
         const float lo = range[2 * p], hi = range[2 * p + 1];
         const float step = (hi - lo) / Lf;
         const float q = step / Wf;
-        uint32_t S[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-        for (uint32_t w = 0; w < W; ++w) {
-            const uint8_t* src = ptrs.p[w] + k * BITS;
-            if constexpr (BITS == 8) {
-                const uint2 x = load_last_use(reinterpret_cast<const uint2*>(src));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    S[e] += (x.x >> (8 * e)) & 0xFFu;
-                    S[4 + e] += (x.y >> (8 * e)) & 0xFFu;
-                }
-            } else if constexpr (BITS == 4) {
-                const uint32_t x = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(src));
-#pragma unroll
-                for (int e = 0; e < 8; ++e) S[e] += (x >> (4 * e)) & 0xFu;
-            } else {
-                const uint32_t x = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(src));
-#pragma unroll
-                for (int e = 0; e < 8; ++e) S[e] += (x >> (2 * e)) & 0x3u;
-            }
-        }
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = (float)S[e] * q + lo;
@@ -232,6 +338,23 @@ __global__ __launch_bounds__(256) void unrotated_aggregate_decode_kernel(const F
             for (int e = 0; e < 8; ++e)
                 if (g + e < n) out[g + e] = x[e];
         }
+    };
+    // two groups a grid apart per trip: twice the loads in flight, every access still coalesced
+    uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; k + stride < groups; k += 2u * stride) {
+        uint32_t S0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, S1[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        for (uint32_t w = 0; w < W; ++w) {
+            const uint2 a0 = fetch(w, k), a1 = fetch(w, k + stride);
+            add(S0, a0);
+            add(S1, a1);
+        }
+        finish(S0, k);
+        finish(S1, k + stride);
+    }
+    if (k < groups) {
+        uint32_t S0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        for (uint32_t w = 0; w < W; ++w) add(S0, fetch(w, k));
+        finish(S0, k);
     }
 }
 
@@ -320,6 +443,16 @@ uint32_t resident_grid_minmax() {
 
 template <bool BF16, int BITS>
 hipError_t launch_unrotated_t(const EncodeAllArgs& a, const FusedWorkerPtrs& ptrs, hipStream_t stream) {
+    if (BF16 && (a.n & 1u) == 0u) {
+        uint32_t G = resident_grid_minmax<encode_all_unrotated_bf16_kernel<BITS>>();
+        if (G == 0) return hipErrorInvalidValue;
+        const uint64_t total = a.chunks * a.W;
+        if (G > total) G = (uint32_t)total;
+        if (G < a.W) return hipErrorInvalidConfiguration;
+        G -= G % a.W;
+        hipLaunchKernelGGL((encode_all_unrotated_bf16_kernel<BITS>), dim3(G), dim3(kThreads), 0, stream, a, ptrs);
+        return hipGetLastError();
+    }
     uint32_t G = resident_grid_minmax<encode_all_unrotated_kernel<BF16, BITS>>();
     if (G == 0) return hipErrorInvalidValue;
     const uint64_t total = a.chunks * a.W;

@@ -48,6 +48,13 @@ def run_fused(xs, seed, bits, rotate, fill=0x5A):
     (4, 20, torch.bfloat16, (2 << 14) + 2, True),         # sums of 20 workers need 16-bit accumulators
     (4, 8, torch.bfloat16, 700 << 14, True),              # more chunks than resident workgroups: several rounds
     (4, 8, torch.bfloat16, (700 << 14) + 3, False),
+    # even bf16 counts without rotation take the pipelined kernel: one item per workgroup,
+    # one or two, two or three, and about eleven
+    (4, 8, torch.bfloat16, (5 << 14) + 8194, False),
+    (4, 8, torch.bfloat16, (100 << 14) + 2, False),
+    (2, 8, torch.bfloat16, (150 << 14) + 6, False),
+    (8, 2, torch.bfloat16, (300 << 14) + 10, False),
+    (4, 8, torch.bfloat16, (700 << 14) + 4, False),
 ])
 def test_one_pass_minmax_matches_the_oracle_and_the_per_step_calls(bits, W, dtype, n, rotate):
     print(f"minmax one-pass bits={bits} W={W} dtype={dtype} n={n} rotate={rotate}", flush=True)
