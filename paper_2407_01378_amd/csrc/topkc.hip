@@ -57,25 +57,72 @@ __device__ __forceinline__ void load8(const void* grad, uint64_t g, uint64_t n, 
 
 // Squared norm of every chunk of C = 8 * lanes_per_chunk coordinates: squares in fp32,
 // summed as a balanced tree over adjacent pairs (inside the thread, then across lanes
-// 1, 2, 4, ... apart), rounded to fp16.
+// 1, 2, 4, ... apart), rounded to fp16.  Group k (8 coordinates) belongs to thread k mod T of
+// a grid of T threads; a thread takes four groups T apart per trip, loaded before any is
+// used (streaming loads, the gradient is read once), so a wave keeps 4 KB in flight.  T is a
+// multiple of 64 and the loop bounds are too: the lanes of a wave stay together, which the
+// lane exchanges need.
 template <bool BF16>
-__global__ __launch_bounds__(256) void norms_kernel(const void* grad, uint64_t n, uint32_t lanes_per_chunk,
-                                                    uint64_t threads, uint16_t* norms) {
-    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    float x[8];
-    if (tid < threads) {
-        load8<BF16>(grad, tid * 8u, n, x);
+__device__ __forceinline__ void raw8(const void* grad, uint64_t g, uint64_t n, uint4 (&q)[2]) {
+    // whole groups only; BF16: one 16-byte unit, fp32: two
+    if (BF16) {
+        q[0] = load_last_use(reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(grad) + g));
     } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = 0.0f;
+        q[0] = load_last_use(reinterpret_cast<const uint4*>(static_cast<const float*>(grad) + g));
+        q[1] = load_last_use(reinterpret_cast<const uint4*>(static_cast<const float*>(grad) + g + 4));
     }
+}
+template <bool BF16>
+__device__ __forceinline__ void widen8(const uint4 (&q)[2], float (&x)[8]) {
+    if (BF16) {
+        const uint32_t w[4] = {q[0].x, q[0].y, q[0].z, q[0].w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            x[2 * d] = __uint_as_float(w[d] << 16);
+            x[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u);
+        }
+    } else {
+        const uint32_t w[8] = {q[0].x, q[0].y, q[0].z, q[0].w, q[1].x, q[1].y, q[1].z, q[1].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __uint_as_float(w[e]);
+    }
+}
+__device__ __forceinline__ void norm_of_group(const float (&x)[8], uint64_t k, uint64_t groups,
+                                              uint32_t lanes_per_chunk, uint16_t* norms) {
     float s[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) s[e] = x[e] * x[e];
     float t = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
     for (uint32_t o = 1; o < lanes_per_chunk; o <<= 1) t = t + __shfl_xor(t, (int)o, 64);
-    if (tid < threads && (tid & (uint64_t)(lanes_per_chunk - 1u)) == 0)
-        norms[tid / lanes_per_chunk] = (uint16_t)f32_to_f16_bits(t);
+    if (k < groups && (k & (uint64_t)(lanes_per_chunk - 1u)) == 0)
+        norms[k / lanes_per_chunk] = (uint16_t)f32_to_f16_bits(t);
+}
+template <bool BF16>
+__global__ __launch_bounds__(256) void norms_kernel(const void* grad, uint64_t n, uint32_t lanes_per_chunk,
+                                                    uint64_t groups, uint16_t* norms) {
+    const uint64_t T = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t whole = (n / 8u) & ~63ull;   // groups below this are complete, in complete waves
+    uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; k - (k & 63u) + 3u * T + 64u <= whole; k += 4u * T) {
+        uint4 q[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw8<BF16>(grad, (k + u * T) * 8u, n, q[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float x[8];
+            widen8<BF16>(q[u], x);
+            norm_of_group(x, k + u * T, groups, lanes_per_chunk, norms);
+        }
+    }
+    // the rest, a group per trip, with the element-wise loader where the gradient ends
+    const uint64_t bound = (groups + 63u) & ~63ull;
+    for (; k < bound; k += T) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = 0.0f;
+        if (k < groups) load8<BF16>(grad, k * 8u, n, x);
+        norm_of_group(x, k, groups, lanes_per_chunk, norms);
+    }
 }
 
 // s_p = fp16 sum over workers, in worker order, of norms_all[w * P + p].
@@ -86,6 +133,21 @@ __global__ __launch_bounds__(256) void sum_norms_kernel(const uint16_t* norms_al
     uint32_t acc = norms_all[p];
     for (uint32_t w = 1; w < W; ++w) acc = add_f16_bits(acc, norms_all[(uint64_t)w * P + p]);
     s[p] = (uint16_t)acc;
+}
+// The same, four chunks per thread through 8-byte loads (P a multiple of 4, both arrays
+// 8-byte aligned: then every worker's row is too).
+__global__ __launch_bounds__(256) void sum_norms4_kernel(const uint16_t* norms_all, uint32_t W, uint64_t P,
+                                                         uint16_t* s) {
+    const uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;   // chunks 4 q .. 4 q + 3
+    if (q * 4u >= P) return;
+    uint32_t acc[4];
+    for (uint32_t w = 0; w < W; ++w) {
+        const uint2 x = load_last_use(reinterpret_cast<const uint2*>(norms_all + (uint64_t)w * P) + q);
+        const uint32_t h[4] = {x.x & 0xFFFFu, x.x >> 16, x.y & 0xFFFFu, x.y >> 16};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = w == 0 ? h[e] : add_f16_bits(acc[e], h[e]);
+    }
+    reinterpret_cast<uint2*>(s)[q] = make_uint2(acc[0] | (acc[1] << 16), acc[2] | (acc[3] << 16));
 }
 
 // ---- selection -----------------------------------------------------------------------------
@@ -360,6 +422,10 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_dense_kernel(
     }
 }
 
+// Largest grid of the norm kernel, in blocks of 256 threads (measured on a 2.6 GB gradient:
+// 2048 .. 16384 blocks read at 4.8 .. 5.4 TB/s, 32768 and 65536 at 5.7, 262144 at 5.5).
+constexpr uint64_t kNormBlocks = 32768;
+
 uint32_t blocks_for(uint64_t threads, uint32_t per_block) {
     return (uint32_t)((threads + per_block - 1) / per_block);
 }
@@ -371,7 +437,10 @@ hipError_t launch_topkc_norms(const void* grad, bool bf16, uint64_t n, uint32_t 
     const uint64_t P = (n + C - 1) / C;
     const uint64_t threads = P * (C / 8u);
     if (threads == 0) return hipSuccess;
-    const dim3 grid(blocks_for(threads, 256)), block(256);
+    // (a thread per group while that is at most kNormBlocks blocks, grid-stride beyond)
+    uint64_t blocks = blocks_for(threads, 256);
+    if (blocks > kNormBlocks) blocks = kNormBlocks;
+    const dim3 grid((uint32_t)blocks), block(256);
     if (bf16)
         hipLaunchKernelGGL(norms_kernel<true>, grid, block, 0, stream, grad, n, C / 8u, threads, norms);
     else
@@ -382,7 +451,10 @@ hipError_t launch_topkc_norms(const void* grad, bool bf16, uint64_t n, uint32_t 
 hipError_t launch_topkc_sum_norms(const uint16_t* norms_all, uint32_t W, uint64_t P, uint16_t* s,
                                   hipStream_t stream) {
     if (P == 0) return hipSuccess;
-    hipLaunchKernelGGL(sum_norms_kernel, dim3(blocks_for(P, 256)), dim3(256), 0, stream, norms_all, W, P, s);
+    if (P % 4u == 0 && reinterpret_cast<uint64_t>(norms_all) % 8u == 0 && reinterpret_cast<uint64_t>(s) % 8u == 0)
+        hipLaunchKernelGGL(sum_norms4_kernel, dim3(blocks_for(P / 4u, 256)), dim3(256), 0, stream, norms_all, W, P, s);
+    else
+        hipLaunchKernelGGL(sum_norms_kernel, dim3(blocks_for(P, 256)), dim3(256), 0, stream, norms_all, W, P, s);
     return hipGetLastError();
 }
 

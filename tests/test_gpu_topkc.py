@@ -189,3 +189,77 @@ def test_topkc_offsets_beyond_2_to_32():
         assert (seg == ref["out"][k * C:k * C + ln]).all(), f"estimate differs in chunk {p}"
         nonzero += int(np.count_nonzero(seg))
     assert int(got["out"].count_nonzero()) == nonzero
+
+
+def _sampled_check(xs, C, J):
+    """Every stage of a TopKC round on inputs too large for the oracle to run whole: norms,
+    summed norms, chunk sums and the estimate against the oracle on sampled chunks (the
+    first and last ones, both sides of every 2^22-chunk boundary, 2000 random); the
+    selection by the properties that define it."""
+    W, n = len(xs), xs[0].numel()
+    bf16 = xs[0].dtype == torch.bfloat16
+    P = thc.topkc_num_chunks(n, C)
+    got = run_topkc(xs, C, J)
+    rng = np.random.default_rng(5)
+    picks = {0, 1, P - 2, P - 1}
+    for b in range(1 << 22, P, 1 << 22):
+        picks.update((b - 1, b))
+    picks.update(int(p) for p in rng.integers(0, P, 2000))
+    picks = np.array(sorted(picks), dtype=np.int64)
+
+    def chunks_of(x, which):   # the given chunks of one gradient, side by side, zero-padded, as raw bits
+        pos = (torch.as_tensor(which, device=DEV)[:, None] * C + torch.arange(C, device=DEV)[None, :]).reshape(-1)
+        v = x[pos.clamp_max(n - 1)]
+        v[pos >= n] = 0
+        return to_numpy_bits(v)
+
+    sel = torch.as_tensor(picks, device=DEV)
+    ref_norms = [K.chunk_norms(chunks_of(x, picks), C, bf16=bf16) for x in xs]
+    for w in range(W):
+        assert (_bits16(got["norms"][w][sel]) == ref_norms[w].view(np.uint16)).all(), f"norms of worker {w}"
+    assert (_bits16(got["s"][sel]) == K.sum_fp16(ref_norms).view(np.uint16)).all(), "summed norms"
+    # selection: J distinct chunks, ascending; nothing left out is larger than anything taken,
+    # and among equals of the smallest taken value the lowest chunk numbers are taken
+    idx = got["indices"].to(torch.int64)
+    assert int(idx.min()) >= 0 and int(idx.max()) < P and bool((idx[1:] > idx[:-1]).all())
+    s = got["s"].float()
+    taken = torch.zeros(P, dtype=torch.bool, device=DEV)
+    taken[idx] = True
+    thr = float(s[taken].min())
+    assert float(s[~taken].max()) <= thr
+    eq_taken = taken[torch.nonzero(s == thr).flatten()]
+    k = int(eq_taken.sum())
+    assert bool(eq_taken[:k].all()) and not bool(eq_taken[k:].any()), "ties: lowest chunk numbers first"
+    # chunk sums and estimate on sampled selected chunks, zeros on sampled chunks left out
+    js = np.unique(np.concatenate([[0, 1, J - 2, J - 1], rng.integers(0, J, 1500)])).astype(np.int64)
+    chosen = idx[torch.as_tensor(js, device=DEV)].cpu().numpy()
+    ref_vals = K.gather_sum([chunks_of(x, chosen) for x in xs], C, np.arange(len(chosen)), bf16=bf16)
+    assert (_bits16(got["values"][torch.as_tensor(js, device=DEV)]) == ref_vals.view(np.uint16)).all(), "chunk sums"
+    ref_out = K.scatter_mean(ref_vals, np.arange(len(chosen)), C, W, len(chosen) * C)
+    out_pos = torch.as_tensor(chosen, device=DEV)[:, None] * C + torch.arange(C, device=DEV)[None, :]
+    inside = (out_pos < n).cpu().numpy().reshape(-1)
+    assert (got["out"][out_pos.clamp_max(n - 1)].cpu().numpy().reshape(-1)[inside] == ref_out[inside]).all(), "estimate"
+    left_out = torch.as_tensor(picks[~taken[sel].cpu().numpy()], device=DEV)
+    gone = (left_out[:, None] * C + torch.arange(C, device=DEV)[None, :]).reshape(-1)
+    assert int(got["out"][gone[gone < n]].count_nonzero()) == 0
+    assert int(got["out"].count_nonzero()) == int(got["values"].count_nonzero())
+
+
+def test_topkc_full_size_sampled_against_the_oracle():
+    """The whole 1.3 B-coordinate gradients of the headline workload (bf16, W = 8, C = 64, J
+    for 2 bits per coordinate), the shapes and launch configurations `bench.py --topkc`
+    times: the norm kernel's grid-stride loop and the gather / scatter grids beyond 2^24
+    threads only run at this size."""
+    wl = workload("gpt_1p3b")
+    n, C = wl.n, 64
+    J = max(1, int((2.0 / 16.0 - 1.0 / C) * n / C))
+    print(f"topkc full size n={n} J={J}", flush=True)
+    _sampled_check([generate(wl, w, torch.device(DEV)) for w in range(wl.W)], C, J)
+
+
+def test_topkc_large_fp32_sampled_against_the_oracle():
+    """fp32 input long enough for the norm kernel's grid-stride loop (more than 2^25 groups
+    of 8), with a ragged last group and chunk."""
+    n, C, J, W = (300 << 20) + 13, 128, 50_000, 2
+    print(f"topkc large fp32 n={n} J={J}", flush=True)
+    _sampled_check(_data(n, torch.float32, W, seed=77), C, J)
