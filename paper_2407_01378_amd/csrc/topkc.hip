@@ -496,9 +496,9 @@ hipError_t launch_topkc_scatter(const uint16_t* values, const uint32_t* indices,
     const uint64_t P = (n + C - 1) / C;
     if (P == 0) return hipSuccess;
     if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
-        // one pass: contiguous ranges of whole tiles, 16 workgroups for each of the 256 CUs
+        // one pass: contiguous ranges of whole tiles
         const uint64_t tiles = (P + kTileChunks - 1) / kTileChunks;
-        uint64_t groups = 4096u;
+        uint64_t groups = 16384u;   // (5.2 GB written: 2048 groups 1.37 ms, 4096 1.20, 16384 1.12, 32768 1.11)
         if (groups > tiles) groups = tiles;
         const uint64_t chunks_per_group = (tiles + groups - 1) / groups * kTileChunks;
         groups = (P + chunks_per_group - 1) / chunks_per_group;
