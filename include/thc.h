@@ -206,8 +206,7 @@ int thc_encode_all_cleared(const void* const* grads, thc_dtype dt, uint32_t W, u
  * are paid once instead of once per bucket.  Results are byte for byte those of
  * thc_encode_all / thc_aggregate_decode called bucket by bucket.
  * Restrictions (negative status otherwise): chunk_log2 == 14 (THC_ERR_CHUNK); W <= 64 and,
- * for the decode side, the shapes for which thc_aggregate_decode_is_fused is 1 and whose sums
- * fit 8 bits for 2- and 4-bit payloads (W <= 17 at 4 bits)
+ * for the decode side, the shapes for which thc_aggregate_decode_is_fused is 1
  * (THC_ERR_WORKERS); gradients, payloads and outputs 16-byte aligned (THC_ERR_ALIGN); at
  * most 4096 buckets (THC_ERR_SIZE).  A bucket with n == 0 is skipped. */
 typedef struct {

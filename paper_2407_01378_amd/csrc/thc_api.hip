@@ -455,7 +455,7 @@ int thc_aggregate_decode_batch(const thc_bucket* buckets, uint32_t count, uint32
     BatchPlan plan;
     int rc = plan_batch(buckets, count, W, chunk_log2, bits, &plan);
     if (rc != THC_OK) return rc;
-    if (!thc::aggregate_decode_batch_applicable(W, chunk_log2, bits)) return THC_ERR_WORKERS;
+    if (!thc::aggregate_decode_fused_applicable(W, chunk_log2, bits)) return THC_ERR_WORKERS;
     if (plan.total_chunks == 0) return THC_OK;
     if (!workspace) return THC_ERR_NULL;
     if (!aligned(workspace, 16)) return THC_ERR_ALIGN;

@@ -914,15 +914,15 @@ hipError_t launch_encode_all_pick(const EncodeAllArgs& a, const FusedWorkerPtrs&
     return launch_encode_all_t<false, 8, false, BATCH>(a, ptrs, batch, stream);
 }
 
-// 2- and 4-bit payloads of so many workers that the sums need 16 bits (single-bucket forms only).
-template <int BITS, bool RANGED>
-hipError_t launch_aggregate_decode_wide(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, hipStream_t stream) {
-    uint32_t G = resident_grid<aggregate_decode_kernel<BITS, false, RANGED, true>>();
+// 4-bit payloads of so many workers that the sums need 16 bits.
+template <int BITS, bool BATCH, bool RANGED>
+hipError_t launch_aggregate_decode_wide(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, const BatchArgs& batch,
+                                        hipStream_t stream) {
+    uint32_t G = resident_grid<aggregate_decode_kernel<BITS, BATCH, RANGED, true>>();
     if (G == 0) return hipErrorInvalidValue;
     if (G > a.chunks) G = (uint32_t)a.chunks;
-    const BatchArgs none{};
-    hipLaunchKernelGGL((aggregate_decode_kernel<BITS, false, RANGED, true>), dim3(G), dim3(kThreads), 0, stream, a,
-                       ptrs, none);
+    hipLaunchKernelGGL((aggregate_decode_kernel<BITS, BATCH, RANGED, true>), dim3(G), dim3(kThreads), 0, stream, a,
+                       ptrs, batch);
     return hipGetLastError();
 }
 // (2-bit payloads would need more than 85 workers, beyond what the one-launch forms take)
@@ -932,9 +932,7 @@ template <bool BATCH>
 hipError_t launch_aggregate_decode_pick(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs, const BatchArgs& batch,
                                         uint32_t bits, hipStream_t stream) {
     if (a.chunks == 0) return hipSuccess;
-    if constexpr (!BATCH) {
-        if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, false>(a, ptrs, stream);
-    }
+    if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, BATCH, false>(a, ptrs, batch, stream);
     uint32_t G = 0;
     if (bits == 2) G = resident_grid<aggregate_decode_kernel<2, BATCH>>();
     else if (bits == 4) G = resident_grid<aggregate_decode_kernel<4, BATCH>>();
@@ -1061,11 +1059,6 @@ bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t
     return bits == 8 ? (top > 255u && top <= 65535u) : top <= 65535u;
 }
 
-bool aggregate_decode_batch_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits) {
-    // the batched kernels are compiled for the narrow accumulators only
-    return aggregate_decode_fused_applicable(W, chunk_log2, bits) && !k14::wide_sums(W, bits);
-}
-
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                          uint32_t bits, hipStream_t stream) {
     return k14::launch_aggregate_decode_pick<false>(a, ptrs, BatchArgs{}, bits, stream);
@@ -1076,7 +1069,7 @@ hipError_t launch_aggregate_decode_ranged(const AggDecodeArgs& a, const FusedPay
                                           uint32_t bits, hipStream_t stream) {
     using namespace k14;
     if (a.chunks == 0) return hipSuccess;
-    if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, true>(a, ptrs, stream);
+    if (wide_sums(a.W, bits)) return launch_aggregate_decode_wide<4, false, true>(a, ptrs, BatchArgs{}, stream);
     uint32_t G = bits == 2   ? resident_grid<aggregate_decode_kernel<2, false, true>>()
                  : bits == 4 ? resident_grid<aggregate_decode_kernel<4, false, true>>()
                              : resident_grid<aggregate_decode_kernel<8, false, true>>();

@@ -120,7 +120,6 @@ struct AggDecodeArgs {
     float* out;
 };
 bool aggregate_decode_fused_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits);
-bool aggregate_decode_batch_applicable(uint32_t W, uint32_t chunk_log2, uint32_t bits);
 hipError_t launch_aggregate_decode_fused(const AggDecodeArgs& a, const FusedPayloadPtrs& ptrs,
                                          uint32_t bits, hipStream_t stream);
 // min/max grid: a.scale holds (lo, hi) pairs

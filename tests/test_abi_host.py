@@ -232,7 +232,7 @@ def test_batched_and_static_entry_points_validate_on_the_host(L):
         keep1, odd = buckets(100, ptr=0x1008)
         assert call(odd, 1, 4, 14, 4, p, 1 << 20) == -8          # unaligned bucket pointers
     assert L.thc_encode_all_batch(one, 1, 9, 4, 14, 4, p, 1 << 20, nul) == -5
-    assert L.thc_aggregate_decode_batch(one, 1, 18, 14, 4, p, 1 << 20, nul) == -4   # sums need 16 bits: not fused
+    assert L.thc_aggregate_decode_batch(one, 1, 1, 14, 8, p, 1 << 20, nul) == -4    # one worker of 8-bit payloads: not fused
 
     # static-scratch form
     g = (ctypes.c_void_p * 4)(*([0x1000] * 4))

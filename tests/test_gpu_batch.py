@@ -40,6 +40,8 @@ def _make(ns, W, dtype, bits, l=14):
     (17, torch.bfloat16, 2, [(2 << 14) + 1, 3 << 14, 100]),
     (1, torch.float32, 4, [(70 << 14) + 3]),
     (64, torch.bfloat16, 2, [1 << 14, (1 << 14) + 2]),
+    (18, torch.bfloat16, 4, [(2 << 14) + 2, 1 << 14]),               # sums of 18 workers need 16-bit accumulators
+    (40, torch.float32, 4, [(1 << 14) + 7]),
 ])
 def test_batched_calls_match_the_per_bucket_calls(W, dtype, bits, ns):
     l = 14
@@ -69,7 +71,7 @@ def test_batched_calls_match_the_per_bucket_calls(W, dtype, bits, ns):
         assert torch.equal(b["out"], ref_out), f"output of bucket {k}"
     # and one bucket element by element against the oracle
     k = 1 if len(ns) > 1 and ns[1] else 0
-    if ns[k] <= (9 << 14) + 8193 and W <= 17:
+    if ns[k] <= (9 << 14) + 8193 and W <= 18:
         b = batch[k]
         check_against_oracle(b["grads"], dict(scale=b["scale"], payloads=b["payloads"], sums=None, out=b["out"]),
                              l, b["seed"], bits)
@@ -85,11 +87,11 @@ def test_batched_calls_refuse_what_they_do_not_cover():
     with pytest.raises(thc.ThcError) as e:
         thc.thc_encode_all_batch(batch, l, 4, ws[:64])
     assert e.value.status == -6
-    many = _make([1 << 14], 18, torch.bfloat16, 4)          # 18 x 15 > 255: the decode side is not fused
-    ws2 = torch.empty(thc.thc_batch_workspace_bytes([1 << 14], 18, l), dtype=torch.uint8, device=DEV)
-    thc.thc_encode_all_batch(many, l, 4, ws2)
+    one = _make([1 << 14], 1, torch.bfloat16, 8)            # one worker of 8-bit payloads: the decode side is not fused
+    ws2 = torch.empty(thc.thc_batch_workspace_bytes([1 << 14], 1, l), dtype=torch.uint8, device=DEV)
+    thc.thc_encode_all_batch(one, l, 8, ws2)
     with pytest.raises(thc.ThcError) as e:
-        thc.thc_aggregate_decode_batch(many, l, 4, ws2)
+        thc.thc_aggregate_decode_batch(one, l, 8, ws2)
     assert e.value.status == -4
     torch.cuda.synchronize()
     assert thc.thc_batch_workspace_bytes([1 << 14], 4, 10) == 0
