@@ -141,3 +141,32 @@ def test_one_pass_minmax_refuses_what_it_does_not_cover():
         thc.thc_aggregate_decode_minmax(pay, rng, n, L14, 0, 4, True, torch.empty(n + 1, device=DEV)[1:])
     assert e.value.status == -8
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("rotate", [True, False])
+def test_one_pass_minmax_expired_wait_sets_the_error_word_and_every_wave_exits(rotate):
+    """Failure handling forced from the host, as for thc_encode_all: with a poll limit of
+    zero the waits between workgroups give up at once; the kernels (the rotated one and the
+    pipelined unrotated one) must still finish and report it, and with the limit restored
+    the same call on the same workspace is correct again."""
+    bits, W = 4, 8
+    n = 600 << 14
+    xs = [_rand(n, torch.bfloat16, 60 + w, scale=1e-2, shift=1e-3) for w in range(W)]
+    P = thc.thc_num_chunks(n, L14)
+    pay = [torch.empty(thc.thc_payload_bytes(n, L14, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
+    rng = torch.empty(2 * P, device=DEV)
+    ws = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, n, L14), dtype=torch.uint8, device=DEV)
+    print(f"minmax one-pass expired wait rotate={rotate}", flush=True)
+    try:
+        thc.thc_set_spin_limit(0)
+        thc.thc_encode_all_minmax(xs, L14, 9, bits, rotate, pay, rng, ws)
+        torch.cuda.synchronize()            # returns: nothing hangs
+        expired = thc.thc_encode_all_timed_out(ws)
+    finally:
+        thc.thc_set_spin_limit(1 << 22)
+    assert expired                           # 4800 items: some wave had to wait at least once
+    got = run_fused(xs, 9, bits, rotate)
+    ref = run_minmax(xs, L14, 9, bits, rotate, torch.float32)
+    assert torch.equal(got["range"], ref["range"])
+    for w in range(W):
+        assert torch.equal(got["payloads"][w], ref["payloads"][w])
