@@ -7,7 +7,9 @@
 // memory, waits until all W workers of the chunk have published, and quantizes onto the
 // shared range - every gradient is read from HBM once (the one-call-per-step form reads it
 // twice).  Grid, item order, bounded waits and the self-clearing workspace follow
-// encode_all_kernel, with two words per wave.
+// encode_all_kernel, with two words per wave.  Two kernels: one item at a time with one
+// polling wave per workgroup (fp32 input, odd bf16 counts), and for bf16 input a pipeline
+// that publishes an item's range one item before it waits for it.
 //
 // unrotated_aggregate_decode: without the rotation the decoder is elementwise, so it is
 // written for coalescing instead of for the rotation's register layout.
