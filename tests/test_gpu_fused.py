@@ -29,6 +29,9 @@ def _rand(n, dtype, seed, scale=1e-3):
     (14, 2, 40, torch.float32, 2), (14, 8, 33, torch.bfloat16, 2),
     (14, 8, 1, torch.bfloat16, 3), (14, 8, 1, torch.float32, 2), (14, 8, 2, torch.bfloat16, 2),
     (10, 4, 4, torch.float32, 40), (12, 8, 5, torch.bfloat16, 9), (3, 2, 3, torch.float32, 1000),
+    # more than 16 workers (one range word per workgroup) over several rounds of the grid:
+    # 25 chunks per round at W = 20, 8 at W = 64
+    (14, 4, 20, torch.bfloat16, 60), (14, 2, 64, torch.bfloat16, 20), (14, 8, 33, torch.float32, 31),
 ])
 def test_fused_path_matches_oracle_and_unfused(l, bits, W, dtype, chunks):
     c = 1 << l
