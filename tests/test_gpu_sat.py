@@ -85,6 +85,7 @@ def check_sat(xs, got, l, seed, bits):
     (14, 4, 64, torch.bfloat16, 2), (14, 2, 33, torch.float32, 2),
     (10, 4, 4, torch.float32, 40), (12, 8, 5, torch.bfloat16, 9), (3, 2, 3, torch.float32, 1000),
     (7, 4, 8, torch.bfloat16, 129),
+    (14, 4, 8, torch.bfloat16, 150), (14, 4, 40, torch.bfloat16, 30),   # several rounds of the persistent grids
 ])
 def test_sat_path_matches_oracle_fused_and_unfused(l, bits, W, dtype, chunks):
     c = 1 << l
