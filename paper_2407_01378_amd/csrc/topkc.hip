@@ -176,25 +176,46 @@ __global__ __launch_bounds__(256) void hist_kernel(const uint16_t* s, uint64_t P
     if (c) atomicAdd(&ws[256 * PASS + threadIdx.x], c);
 }
 
-// One thread walks the 256-bin histogram from the top.  PASS 0: finds the bucket in which
-// the J-th largest key lies.  PASS 1: finds the key itself and how many of its equals to take.
+// One wave walks the 256-bin histogram from the top: the largest bin b whose count together
+// with the counts above it reaches `want` (bin 0 if none does), and the count above it.
+// PASS 0: finds the bucket in which the J-th largest key lies.  PASS 1: finds the key itself
+// and how many of its equals to take.  Lane i holds bins 4 i .. 4 i + 3.
 template <int PASS>
-__global__ void find_kernel(uint32_t* ws, uint32_t J) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__global__ __launch_bounds__(64) void find_kernel(uint32_t* ws, uint32_t J) {
+    if (blockIdx.x != 0) return;
+    const uint32_t lane = threadIdx.x;
     const uint32_t want = PASS == 0 ? J : ws[513];
-    uint32_t above = 0;
-    int b = 255;
-    for (; b > 0; --b) {
-        const uint32_t c = ws[256 * PASS + b];
-        if (above + c >= want) break;
-        above += c;
+    const uint32_t* bins = ws + 256 * PASS + 4u * lane;   // (the workspace is only 4-byte aligned)
+    const uint4 c = make_uint4(bins[0], bins[1], bins[2], bins[3]);
+    const uint32_t tot = c.x + c.y + c.z + c.w;
+    uint32_t suf = tot;   // -> this lane's bins and all above them
+    for (uint32_t o = 1; o < 64u; o <<= 1) {
+        const uint32_t y = __shfl_down(suf, o, 64);
+        if (lane + o < 64u) suf += y;
     }
-    if (PASS == 0) {
-        ws[512] = (uint32_t)b;
-        ws[513] = want - above;          // still to take inside bucket b (>= 1)
-    } else {
-        ws[514] = (ws[512] << 8) | (uint32_t)b;
-        ws[515] = want - above;          // keys equal to T that are taken (>= 1)
+    const uint32_t s4 = suf - tot;   // everything above bin 4 lane + 3
+    const uint32_t s3 = s4 + c.w, s2 = s3 + c.z, s1 = s2 + c.y, s0 = s1 + c.x;
+    int best = -1;
+    uint32_t above = 0;
+    if (s3 >= want) { best = 3; above = s4; }
+    else if (s2 >= want) { best = 2; above = s3; }
+    else if (s1 >= want) { best = 1; above = s2; }
+    else if (s0 >= want) { best = 0; above = s1; }
+    const unsigned long long found = __ballot(best >= 0);
+    uint32_t b = 0, ab = __shfl(s1, 0, 64);   // nothing reaches `want`: bin 0, as the walk from the top would end
+    if (found != 0ull) {
+        const int winner = 63 - __builtin_clzll(found);
+        b = 4u * (uint32_t)winner + (uint32_t)__shfl(best, winner, 64);
+        ab = __shfl(above, winner, 64);
+    }
+    if (lane == 0) {
+        if (PASS == 0) {
+            ws[512] = b;
+            ws[513] = want - ab;          // still to take inside bucket b (>= 1)
+        } else {
+            ws[514] = (ws[512] << 8) | b;
+            ws[515] = want - ab;          // keys equal to T that are taken (>= 1)
+        }
     }
 }
 
@@ -221,8 +242,8 @@ __global__ __launch_bounds__(256) void seg_count_kernel(const uint16_t* s, uint6
 
 // Exclusive scan of the per-segment pairs, one workgroup (segments are few: P / 2048).
 __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* ws, uint32_t segments) {
-    __shared__ uint32_t tot[2][1024];
-    const uint32_t t = threadIdx.x;
+    __shared__ uint32_t wave_tot[2][16];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t per = (segments + 1023u) / 1024u;
     const uint32_t lo = t * per, hi = min(lo + per, segments);
     uint32_t a = 0, e = 0;
@@ -230,22 +251,28 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* ws, uint32_t s
         a += ws[kHdr + 2u * i];
         e += ws[kHdr + 2u * i + 1u];
     }
-    tot[0][t] = a;
-    tot[1][t] = e;
-    __syncthreads();
-    if (t == 0) {
-        uint32_t ra = 0, re = 0;
-        for (uint32_t i = 0; i < 1024u; ++i) {
-            const uint32_t xa = tot[0][i], xe = tot[1][i];
-            tot[0][i] = ra;
-            tot[1][i] = re;
-            ra += xa;
-            re += xe;
+    // exclusive scan of the 1024 thread totals: inclusive inside each wave by lane shifts,
+    // then the totals of the waves before this one
+    uint32_t ia = a, ie = e;
+    for (uint32_t o = 1; o < 64u; o <<= 1) {
+        const uint32_t ya = __shfl_up(ia, o, 64), ye = __shfl_up(ie, o, 64);
+        if (lane >= o) {
+            ia += ya;
+            ie += ye;
         }
     }
+    if (lane == 63u) {
+        wave_tot[0][wave] = ia;
+        wave_tot[1][wave] = ie;
+    }
     __syncthreads();
-    a = tot[0][t];
-    e = tot[1][t];
+    uint32_t oa = 0, oe = 0;
+    for (uint32_t w = 0; w < wave; ++w) {
+        oa += wave_tot[0][w];
+        oe += wave_tot[1][w];
+    }
+    a = oa + ia - a;
+    e = oe + ie - e;
     for (uint32_t i = lo; i < hi; ++i) {
         const uint32_t xa = ws[kHdr + 2u * i], xe = ws[kHdr + 2u * i + 1u];
         ws[kHdr + 2u * i] = a;
