@@ -159,17 +159,50 @@ constexpr uint32_t kSegment = 2048;
 constexpr uint32_t kHdr = 516;
 
 // PASS 0: histogram of key >> 8.  PASS 1: of key & 255 among keys with key >> 8 == ws[512].
-template <int PASS>
+// VEC (s 16-byte aligned): a thread takes 8 consecutive keys per load and adds runs of equal
+// bins with one LDS atomic each (norms that underflow to zero, or lie in one bucket, come in
+// runs); the keys past the last whole group of 8 are left to the first block.
+template <int PASS, bool VEC>
 __global__ __launch_bounds__(256) void hist_kernel(const uint16_t* s, uint64_t P, uint32_t* ws) {
     __shared__ uint32_t h[256];
     h[threadIdx.x] = 0u;
     __syncthreads();
     const uint32_t bucket = PASS == 1 ? ws[512] : 0u;
-    for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < P;
-         p += (uint64_t)gridDim.x * blockDim.x) {
-        const uint32_t key = s[p];
-        if (PASS == 0) atomicAdd(&h[key >> 8], 1u);
-        else if ((key >> 8) == bucket) atomicAdd(&h[key & 255u], 1u);
+    auto bin_of = [&](uint32_t key) -> int {
+        if (PASS == 0) return (int)(key >> 8);
+        return (key >> 8) == bucket ? (int)(key & 255u) : -1;
+    };
+    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    if (VEC) {
+        const uint64_t groups = P / 8u;
+        for (uint64_t g = tid; g < groups; g += stride) {
+            const uint4 q = load_last_use(reinterpret_cast<const uint4*>(s) + g);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+            int cur = -1;
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int b = bin_of((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+                if (b != cur) {
+                    if (cur >= 0) atomicAdd(&h[cur], cnt);
+                    cur = b;
+                    cnt = 1u;
+                } else {
+                    ++cnt;
+                }
+            }
+            if (cur >= 0) atomicAdd(&h[cur], cnt);
+        }
+        if (blockIdx.x == 0 && groups * 8u + threadIdx.x < P) {   // fewer than 8 keys
+            const int b = bin_of(s[groups * 8u + threadIdx.x]);
+            if (b >= 0) atomicAdd(&h[b], 1u);
+        }
+    } else {
+        for (uint64_t p = tid; p < P; p += stride) {
+            const int b = bin_of(s[p]);
+            if (b >= 0) atomicAdd(&h[b], 1u);
+        }
     }
     __syncthreads();
     const uint32_t c = h[threadIdx.x];
@@ -496,9 +529,12 @@ hipError_t launch_topkc_select(const uint16_t* s, uint64_t P, uint32_t J, uint32
     if (e != hipSuccess) return e;
     uint32_t hb = blocks_for(P, 256 * 16);
     if (hb > 2048) hb = 2048;
-    hipLaunchKernelGGL(hist_kernel<0>, dim3(hb), dim3(256), 0, stream, s, P, ws);
+    const bool vec = (reinterpret_cast<uintptr_t>(s) & 15u) == 0;
+    if (vec) hipLaunchKernelGGL((hist_kernel<0, true>), dim3(hb), dim3(256), 0, stream, s, P, ws);
+    else hipLaunchKernelGGL((hist_kernel<0, false>), dim3(hb), dim3(256), 0, stream, s, P, ws);
     hipLaunchKernelGGL(find_kernel<0>, dim3(1), dim3(64), 0, stream, ws, J);
-    hipLaunchKernelGGL(hist_kernel<1>, dim3(hb), dim3(256), 0, stream, s, P, ws);
+    if (vec) hipLaunchKernelGGL((hist_kernel<1, true>), dim3(hb), dim3(256), 0, stream, s, P, ws);
+    else hipLaunchKernelGGL((hist_kernel<1, false>), dim3(hb), dim3(256), 0, stream, s, P, ws);
     hipLaunchKernelGGL(find_kernel<1>, dim3(1), dim3(64), 0, stream, ws, J);
     hipLaunchKernelGGL(seg_count_kernel, dim3(segments), dim3(256), 0, stream, s, P, ws);
     hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, ws, segments);

@@ -263,3 +263,23 @@ def test_topkc_large_fp32_sampled_against_the_oracle():
     n, C, J, W = (300 << 20) + 13, 128, 50_000, 2
     print(f"topkc large fp32 n={n} J={J}", flush=True)
     _sampled_check(_data(n, torch.float32, W, seed=77), C, J)
+
+
+@pytest.mark.parametrize("offset", [0, 1, 3, 8])
+@pytest.mark.parametrize("P,J", [(5, 2), (1000, 1000), (70_001, 333), (70_008, 69_000)])
+def test_topkc_select_on_unaligned_and_ragged_key_arrays(offset, P, J):
+    """The selection reads its keys 8 at a time when the array is 16-byte aligned and one at
+    a time otherwise; both against the oracle, with many equal keys and zeros in runs."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(P + offset)
+    vals = (torch.randint(0, 40, (P + offset,), generator=g, device=DEV).float() / 8.0)
+    vals[offset + P // 3: offset + P // 2] = 0.0
+    s = vals.half()[offset:]
+    assert s.data_ptr() % 16 == (2 * offset) % 16
+    idx = torch.full((J,), -1, dtype=torch.int32, device=DEV)
+    ws = torch.full((thc.topkc_select_workspace_bytes(P),), 0xFF, dtype=torch.uint8, device=DEV)
+    print(f"topkc select offset={offset} P={P} J={J}", flush=True)
+    thc.topkc_select(s, J, idx, ws)
+    torch.cuda.synchronize()
+    ref = K.select(s.cpu().numpy(), J)
+    assert (idx.cpu().numpy().view(np.uint32) == ref).all()
