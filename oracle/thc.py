@@ -38,6 +38,11 @@ implemented, independently, by the GPU library):
       chunk has index 0 everywhere.
   R6  Decode returns the estimate of the workers' MEAN gradient.
   R7  All-zero chunk (s_p = 0): every index is 0 and it decodes to exactly 0.
+      The same indices for a chunk whose range is too small for the arithmetic: the rule
+      needs the reciprocal grid step L / (2 s_p), which is not finite in binary32 once
+      2 s_p falls below about 2^-120 (L = 255); a chunk with 2 s_p < MIN_RANGE = 2^-119 is
+      therefore quantized like an all-zero chunk, in both modes.  Its scale is kept, so
+      it decodes to -s_p per rotated coordinate: an error of at most 2^-119.
   R8  Padding: zeros up to a multiple of the chunk only.
 
 Two arithmetic modes with identical logic: dtype=np.float64 is the definition;
@@ -52,6 +57,9 @@ from .philox import philox4x32_10
 
 #: random bits consumed per coordinate by the stochastic rounding (reading R5)
 RBITS = 8
+#: smallest width of a chunk's range (2 s_p, or hi - lo on the min/max grid) that is quantized
+#: by the rule; narrower ranges are treated like an empty one (reading R7)
+MIN_RANGE = 2.0 ** -119
 #: fourth counter word that separates the two uses of the generator
 TAG_SIGN = 0x5349474E
 TAG_ROUND = 0x524F554E
@@ -272,7 +280,7 @@ def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
         inv = L / (s_p + s_p)
         t   = y * inv + L/2 + u,  u = (r + 0.5) / 2^RBITS     (position in grid units + noise;
                                   fp32 evaluation order: grid_position_plus_noise)
-        idx = min(floor(t), L);   s_p = 0 -> idx = 0
+        idx = min(floor(t), L);   2 s_p < MIN_RANGE (in particular s_p = 0) -> idx = 0
 
     `r` (tests only) replaces the generator's RBITS-bit integers, so that every
     value of r can be enumerated by brute force.
@@ -283,7 +291,7 @@ def quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=0,
     s = np.asarray(scale, dtype=dtype).reshape(-1, 1)
     two_s = s + s
     inv = np.zeros_like(two_s)
-    nz = two_s != 0
+    nz = two_s >= dtype(MIN_RANGE)
     inv[nz] = dtype(L) / two_s[nz]
     if r is None:
         r = rounding_fields(g0, y.size, worker, seed, rbits)

@@ -10,7 +10,9 @@ Readings (the paper fixes only the idea of a min-max range):
       lo_p = min over workers of the chunk's smallest rotated value, hi_p = max over
       workers of its largest.  The header is the pair (lo_p, hi_p).
   M2  Grid: 2^b points, index 0 at lo_p, index L at hi_p; hi_p == lo_p gives inv = 0,
-      all indices 0, and decodes to exactly lo_p.
+      all indices 0, and decodes to exactly lo_p.  So does a range narrower than
+      MIN_RANGE = 2^-119, for which L / (hi - lo) need not be finite in binary32 (reading
+      R7 of the symmetric path); it decodes to lo_p, at most its own width away.
           inv = L / (hi - lo);  t = (y - lo) * inv + u;  idx = min(floor(t), L)
       (u as in the symmetric path, same random stream; in the fp32 mode the subtraction
       is one operation and the multiply-add one fused operation).
@@ -59,7 +61,7 @@ def quantize_minmax(y, rng, chunk_log2, worker, seed, bits, dtype=np.float64, g0
     lo, hi = rng[:, 0:1], rng[:, 1:2]
     width = hi - lo
     inv = np.zeros_like(width)
-    nz = width != 0
+    nz = width >= dtype(T.MIN_RANGE)             # a constant chunk, or one too narrow for L / width
     inv[nz] = dtype(L) / width[nz]
     if r is None:
         r = T.rounding_fields(g0, y.size, worker, seed)

@@ -52,7 +52,8 @@ def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=
         inv = 2M / (s_p + s_p)
         t   = y * inv + M + u,  u = (r + 0.5) / 2^RBITS   (fp32 evaluation order and random
                                                            stream of the exact-sum path)
-        idx = min(floor(t), 2M);  s_p = 0 -> idx = M  (the grid's centre: z = 0)
+        idx = min(floor(t), 2M);  2 s_p < MIN_RANGE (in particular s_p = 0) -> idx = M
+                                  (the grid's centre: z = 0)
     """
     c = 1 << chunk_log2
     L = 2 * sat_max(bits)
@@ -60,7 +61,7 @@ def sat_quantize(y, scale, chunk_log2, worker, seed, bits, dtype=np.float64, g0=
     s = np.asarray(scale, dtype=dtype).reshape(-1, 1)
     two_s = s + s
     inv = np.zeros_like(two_s)
-    nz = two_s != 0
+    nz = two_s >= dtype(T.MIN_RANGE)
     inv[nz] = dtype(L) / two_s[nz]
     if r is None:
         r = T.rounding_fields(g0, y.size, worker, seed)

@@ -87,6 +87,29 @@ def test_degenerate_range_decodes_to_the_constant():
     assert res["range"][1].tolist() == [0.0, 0.375]            # ragged chunk: zero padding widens it
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_range_too_narrow_for_the_reciprocal_step_is_sent_as_constant(dtype):
+    """M2: below MIN_RANGE = 2^-119 the range is treated like an empty one (L / width need not
+    be finite in binary32): indices 0, decoded to lo, at most the width away; at MIN_RANGE
+    the ordinary rule applies and the end points get 0 and L."""
+    from oracle.thc_minmax import quantize_minmax
+    bits, L, c = 8, 255, 8
+    lo = dtype(3.0) * dtype(2.0 ** -118)
+    for width, empty in ((2.0 ** -120, True), (2.0 ** -119, False)):
+        hi = lo + dtype(width)
+        assert hi - lo == dtype(width)
+        y = np.linspace(float(lo), float(hi), c).astype(dtype)
+        y[0], y[-1] = lo, hi
+        with np.errstate(all="raise"):
+            idx = quantize_minmax(y, [[lo, hi]], 3, 0, 4, bits, dtype=dtype)
+        if empty:
+            assert (idx == 0).all()
+            out = decode_minmax(idx.astype(np.int64), [[lo, hi]], 1, c, 3, 4, bits, False, dtype=dtype)
+            assert (np.abs(out.astype(np.float64) - y.astype(np.float64)) <= width).all()
+        else:
+            assert idx[0] == 0 and idx[-1] == L
+
+
 def test_single_worker_error_below_one_step_with_and_without_rotation():
     log2c, bits = 8, 4
     rng = np.random.default_rng(2)

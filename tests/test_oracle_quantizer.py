@@ -377,3 +377,45 @@ def test_fp32_evaluation_orders_against_the_float64_definition(bits):
         assert report["single"][1] == 0
     else:
         assert report["single"][1] > 0
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_ranges_too_small_for_the_reciprocal_step_are_sent_as_empty(bits, dtype):
+    """Reading R7: the rule needs L / (2 s), which binary32 cannot hold for tiny s (255 / 2^-121
+    = 2^128.99 overflows; at 2 s = 2^-119 every grid of this library still has a finite
+    reciprocal step).  Below MIN_RANGE a chunk is quantized like an all-zero one; at
+    MIN_RANGE the ordinary rule applies, end points included, and nothing overflows."""
+    from oracle.thc import MIN_RANGE
+    L = (1 << bits) - 1
+    assert MIN_RANGE == 2.0 ** -119
+    with np.errstate(over="ignore"):
+        assert np.isinf(np.float32(255.0) / np.float32(2.0 ** -121))
+    for levels in (2, 3, 14, 15, 254, 255):
+        assert np.isfinite(np.float32(levels) / np.float32(MIN_RANGE))
+    c = 16
+    rng = np.random.default_rng(bits)
+    frac = rng.uniform(-1.0, 1.0, size=c)
+    frac[0], frac[1] = 1.0, -1.0
+    for two_s, empty in ((2.0 ** -120, True), (np.nextafter(np.float32(2.0 ** -119), np.float32(0)), True),
+                         (2.0 ** -119, False), (2.0 ** -100, False)):
+        s = dtype(two_s) / dtype(2)
+        y = (frac * float(s)).astype(dtype)
+        with np.errstate(all="raise"):
+            idx, t = quantize(y, [s], 4, 0, 9, bits, dtype=dtype, return_t=True)
+        if empty:
+            assert (idx == 0).all()
+        else:
+            assert np.isfinite(t).all()
+            assert idx[0] == L and idx[1] == 0 and idx.max() <= L
+            step = float(two_s) / L
+            back = idx.astype(np.float64) * step - float(s)
+            assert (np.abs(back - y.astype(np.float64)) <= step * (1 + 1e-6)).all()
+    # through the whole path: the chunk keeps its (tiny) scale, is sent as zeros, and the
+    # estimate of the mean is off by at most the range itself per rotated coordinate
+    xs = [(rng.uniform(-1.0, 1.0, size=32) * 2.0 ** -124).astype(np.float32) for _ in range(3)]
+    res = pipeline(xs, 4, 7, bits, dtype=dtype)
+    assert (res["scale"] > 0).all() and (2 * res["scale"] < MIN_RANGE).all()
+    assert all(int(p.max()) == 0 for p in res["payloads"])
+    mean = np.mean(np.stack(xs).astype(np.float64), axis=0)
+    assert np.abs(res["out"] - mean).max() <= 4 * 2.0 ** -119      # 1/sqrt(16) * 16 terms of at most 2^-119

@@ -102,6 +102,23 @@ def test_grid_has_zero_and_both_ends_for_every_random_value(bits, dtype):
         assert (sat_quantize(np.full(c, -s[0]), s, log2c, 0, 1, bits, dtype=dtype, r=rr) == 0).all()
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_scale_too_small_for_the_reciprocal_step_gives_the_centre(dtype):
+    """Below 2 s = 2^-119 the chunk is quantized like an all-zero one: the centre index (z = 0);
+    at that value the ordinary rule applies, ends included."""
+    bits, M, c = 8, sat_max(8), 8
+    frac = np.array([1.0, -1.0, 0.0, 0.3, -0.7, 0.9, -0.2, 0.5])
+    for two_s, empty in ((2.0 ** -120, True), (2.0 ** -119, False)):
+        s = np.array([two_s / 2], dtype=dtype)
+        y = (frac * float(s[0])).astype(dtype)
+        with np.errstate(all="raise"):
+            idx = sat_quantize(y, s, 3, 0, 1, bits, dtype=dtype)
+        if empty:
+            assert (idx == M).all()
+        else:
+            assert idx[0] == 2 * M and idx[1] == 0 and idx[2] == M
+
+
 def test_rounding_probability_is_the_fraction_brute_force():
     bits, log2c = 4, 3
     M, c = 7, 8
