@@ -404,7 +404,9 @@ __device__ __forceinline__ void l3_to_l4d(Shared& sh, float (&v)[kRegs], uint32_
 //            L/2 (1 + 2^-24) and 2^-9 <= c - L/2 <= 255.5 / 256), or the min/max grid with
 //            lo and hi the chunk's extremes (fl(y - lo) <= fl(hi - lo) = width, and width *
 //            fl(L / width) <= L (1 + 2^-24), so t < L + 255.5/256 + L 2^-24 < L + 1); the
-//            minimum with L never binds.  A range handed in by a caller keeps the clamp.
+//            minimum with L never binds.  Both bounds need mul finite: the callers set mul = 0
+//            for a range below kMinRange, which then gives t = c.  A range handed in by a
+//            caller keeps the clamp.
 //   FOLD     y = v * 2^-7 is not formed; mul already carries the factor 2^-7 and sub is given
 //            in v's units (v - 2^7 lo = 2^7 (y - lo), rounded alike).  Exact as long
 //            as the power of two moves nothing into the subnormal range or past the largest
@@ -485,7 +487,7 @@ __device__ __forceinline__ void store_packed(const uint32_t (&pk)[BITS], uint8_t
     }
 }
 
-// Symmetric grid.  An all-zero chunk (s = 0) gets index 0 everywhere on the 2^BITS-point
+// Symmetric grid.  An all-zero chunk (s = 0; also one with 2 s < kMinRange) gets index 0 everywhere on the 2^BITS-point
 // grid (L odd) and the centre index L/2 on the signed grid (L even).  Evaluation order by
 // grid size (kSingleFmaMaxLevels): 2- and 4-bit grids t = fma(y, inv, L/2 + u); 8-bit
 // grids t = fma(y + s, inv, u), which is the ranged form with sub = -s.  The clamp stays
@@ -497,8 +499,9 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
                                                uint8_t* payload, uint32_t t) {
     constexpr bool kOffset = ((1u << BITS) - 2u) > kSingleFmaMaxLevels;   // both grids of this width
     const float two = s + s;
-    const float inv = two != 0.0f ? (float)L / two : 0.0f;
-    const float centre = (two != 0.0f ? !kOffset : (L & 1u) == 0u) ? 0.5f * (float)L : 0.0f;
+    const bool ranged = two >= kMinRange;   // false: an all-zero chunk, or one too small for L / two
+    const float inv = ranged ? (float)L / two : 0.0f;
+    const float centre = (ranged ? !kOffset : (L & 1u) == 0u) ? 0.5f * (float)L : 0.0f;
     const float base = centre + 0x1p-9f;   // exact
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];   // 32 coordinates * BITS bits = BITS dwords
@@ -509,14 +512,15 @@ __device__ __forceinline__ void quantize_store(const float (&v)[kRegs], float s,
     store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 
-// Min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo) (0 for a constant chunk).
+// Min/max grid: idx = floor((y - lo) * inv + u), inv = L / (hi - lo) (0 for a constant chunk
+// and for one narrower than kMinRange).
 // ROTATED false: v holds y itself (the unrotated, zero-padded gradient), not 2^7 y.
 template <int BITS, bool ROTATED = true, bool CLAMP = true>
 __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], float lo, float hi, uint32_t L,
                                                      uint64_t g0, uint32_t worker, uint32_t key0,
                                                      uint32_t key1, uint8_t* payload, uint32_t t) {
     const float width = hi - lo;
-    const float inv = width != 0.0f ? (float)L / width : 0.0f;
+    const float inv = width >= kMinRange ? (float)L / width : 0.0f;
     const uint64_t g = g0 + (uint64_t)t * 32u;
     uint32_t pk[BITS];
     quantize_pack<BITS, CLAMP, !ROTATED, true>(v, lo, inv, 0x1p-9f, L, g, worker, key0, key1, pk);

@@ -26,6 +26,14 @@ constexpr int kCoordsPerRoundBlock = 128 / kRoundingBits;  // 16
 // 7.6e-6 for L = 255, more than the 1e-6 max(1, |t|) an index is allowed to depend on.
 constexpr uint32_t kSingleFmaMaxLevels = 31;
 
+// Narrowest range of a chunk (2 s on the symmetric grids, hi - lo on the min/max grid) that is
+// quantized by the rounding rule.  The rule needs the reciprocal grid step L / range, which
+// fp32 cannot hold for much smaller ranges (255 / 2^-121 overflows); a narrower range is
+// treated like an empty one: every index 0 (the centre on the signed grid), and the chunk
+// decodes at most 2^-119 off per rotated coordinate.  `range >= kMinRange` is also false for a
+// NaN, which then takes the same path.
+constexpr float kMinRange = 0x1p-119f;
+
 struct u32x4 {
     uint32_t w[4];
 };

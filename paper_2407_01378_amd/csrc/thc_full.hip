@@ -170,9 +170,10 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
     const float s = scale[0];
     const float two = s + s;
     const float Lf = (float)levels;
-    const float inv = two != 0.0f ? Lf / two : 0.0f;
+    const bool ranged = two >= kMinRange;
+    const float inv = ranged ? Lf / two : 0.0f;
     const bool single = levels <= kSingleFmaMaxLevels;   // evaluation order by grid size
-    const float half = (single && two != 0.0f) ? 0.5f * Lf : 0.0f;   // an all-zero vector gets index 0
+    const float half = (single && ranged) ? 0.5f * Lf : 0.0f;   // an all-zero (or vanishingly small) vector gets index 0
     const float off = single ? 0.0f : s;
     const u32x4 rb = round_block(blk, worker, key0, key1);
     uint32_t pk[4] = {0u, 0u, 0u, 0u};

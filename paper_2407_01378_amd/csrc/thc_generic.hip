@@ -279,16 +279,18 @@ __global__ __launch_bounds__(kThreads) void generic_kernel(const ChunkArgs a) {
                     const float lo = p < chunks ? a.range_in[2 * p] : 0.0f;
                     const float hi = p < chunks ? a.range_in[2 * p + 1] : 0.0f;
                     const float width = hi - lo;
-                    const float inv = width != 0.0f ? Lf / width : 0.0f;
+                    const float inv = width >= kMinRange ? Lf / width : 0.0f;
                     tt = __builtin_fmaf(v[j] - lo, inv, u);
                 } else {            // symmetric grid: y * inv + L/2 + u
                     const float s = s_el[j];
                     const float two = s + s;
-                    const float inv = two != 0.0f ? Lf / two : 0.0f;
-                    // all-zero chunk: index 0 on the 2^bits-point grid, the centre on the signed one
-                    const float zero_idx = (two == 0.0f && (a.levels & 1u) == 0u) ? 0.5f * Lf : 0.0f;
+                    const bool ranged = two >= kMinRange;
+                    const float inv = ranged ? Lf / two : 0.0f;
+                    // all-zero chunk (or one too small for L / two): index 0 on the 2^bits-point
+                    // grid, the centre on the signed one
+                    const float zero_idx = (!ranged && (a.levels & 1u) == 0u) ? 0.5f * Lf : 0.0f;
                     if (a.levels <= kSingleFmaMaxLevels)   // small grids: one rounding from y itself
-                        tt = __builtin_fmaf(v[j], inv, (two != 0.0f ? 0.5f * Lf : zero_idx) + u);
+                        tt = __builtin_fmaf(v[j], inv, (ranged ? 0.5f * Lf : zero_idx) + u);
                     else                                   // large grids: the offset y + s is rounded first
                         tt = __builtin_fmaf(v[j] + s, inv, zero_idx + u);
                 }

@@ -57,9 +57,13 @@ def test_full_rotation_forward_and_inverse(l, n, dtype):
     (21, 1_500_000, 2, 8, torch.bfloat16), (16, 1 << 16, 18, 4, torch.float32), (17, 99_999, 3, 2, torch.float32),
 ])
 def test_full_rotation_pipeline_matches_oracle(l, n, W, bits, dtype):
-    print(f"full pipeline l={l} n={n} W={W} bits={bits} dtype={dtype}", flush=True)
+    _full_pipeline(l, n, W, bits, dtype)
+
+
+def _full_pipeline(l, n, W, bits, dtype, magnitude=1.0):
+    print(f"full pipeline l={l} n={n} W={W} bits={bits} dtype={dtype} magnitude={magnitude}", flush=True)
     size = 1 << l
-    xs = [_rand(n, dtype, 100 * l + w, scale=10.0 ** (-1 - (w % 3))) for w in range(W)]
+    xs = [(_rand(n, torch.float32, 100 * l + w, scale=10.0 ** (-1 - (w % 3))) * magnitude).to(dtype) for w in range(W)]
     absmax = torch.empty(W, device=DEV)
     scale = torch.empty(1, device=DEV)
     ys = [torch.empty(size, device=DEV) for _ in range(W)]
@@ -89,6 +93,16 @@ def test_full_rotation_pipeline_matches_oracle(l, n, W, bits, dtype):
     assert (out.cpu().numpy() == ref["out"]).all()
     d64 = O.decode(ref["sums"], ref["scale"].astype(np.float64), W, n, l, 9, bits)
     assert np.linalg.norm(out.cpu().numpy() - d64) <= 1e-5 * np.linalg.norm(d64)
+    return float(scale[0]), payloads
+
+
+@pytest.mark.parametrize("bits,dtype", [(4, torch.float32), (8, torch.bfloat16)])
+def test_full_rotation_of_a_vanishingly_small_gradient(bits, dtype):
+    """A whole gradient whose scale is below 2^-120 (L / (2 s) is not finite in fp32): sent as
+    zeros, as the oracle does."""
+    s, payloads = _full_pipeline(15, 30_000, 3, bits, dtype, magnitude=2.0 ** -128)
+    assert 0 < s < 2.0 ** -121
+    assert all(int(p.max()) == 0 for p in payloads)
 
 
 def test_full_rotation_argument_checks():

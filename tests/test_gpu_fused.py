@@ -63,7 +63,9 @@ def test_scales_outside_and_across_the_folded_range(dtype, bits):
     kernels fold the 2^-7 normalisation into the quantizer's constants only where that
     is exact, and both forms must reproduce the oracle bit for bit."""
     l, W, c = 14, 3, 1 << 14
-    mags = [2.0 ** -110, 1.0, 2.0 ** 105, 2.0 ** -101, 2.0 ** 99, 2.0 ** -120]
+    # (the last three: scales below and around 2^-120, where the reciprocal grid step is not
+    # finite in fp32 and the chunk is sent like an all-zero one)
+    mags = [2.0 ** -110, 1.0, 2.0 ** 105, 2.0 ** -101, 2.0 ** 99, 2.0 ** -120, 2.0 ** -131, 2.0 ** -124, 2.0 ** -122]
     n = len(mags) * c - 100
     xs = []
     for w in range(W):
@@ -78,6 +80,11 @@ def test_scales_outside_and_across_the_folded_range(dtype, bits):
     for a, b in zip(fused["payloads"], plain["payloads"]):
         assert torch.equal(a, b)
     assert torch.equal(fused["out"], plain["out"])
+    tiny = fused["scale"] < 2.0 ** -120
+    assert int(tiny.sum()) >= 1 and float(fused["scale"][tiny].min()) > 0
+    per = c * bits // 8
+    for k in torch.nonzero(tiny).flatten().tolist():
+        assert all(int(p[k * per:(k + 1) * per].max()) == 0 for p in fused["payloads"])
 
 
 def test_is_fused_predicate():

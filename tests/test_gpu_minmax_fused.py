@@ -117,6 +117,40 @@ def test_one_pass_minmax_constant_and_zero_chunks():
     assert int(got["range"].abs().max().item()) == 0 and int(got["out"].abs().max().item()) == 0
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("rotate", [True, False])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_minmax_ranges_too_narrow_for_the_reciprocal_step(bits, rotate, dtype):
+    """Chunks whose range is narrower than and around 2^-119 (L / (hi - lo) is not finite in
+    fp32 much below that): sent like constant chunks; one-pass and per-step forms against
+    the oracle and each other."""
+    W, c = 3, 1 << 14
+    n = 4 * c + 6
+    xs = []
+    for w in range(W):
+        x = _rand(n, torch.float32, 800 + w, scale=1.0, shift=0.0)
+        x[:c] *= 2.0 ** -131
+        x[c:2 * c] *= 2.0 ** -123
+        x[2 * c:3 * c] *= 2.0 ** -121
+        xs.append(x.to(dtype))
+    print(f"minmax tiny ranges bits={bits} rotate={rotate} dtype={dtype}", flush=True)
+    got = run_fused(xs, 6, bits, rotate)
+    ref_gpu = run_minmax(xs, L14, 6, bits, rotate, torch.float32)
+    assert torch.equal(got["range"], ref_gpu["range"])
+    for w in range(W):
+        assert torch.equal(got["payloads"][w], ref_gpu["payloads"][w])
+    assert torch.equal(got["out"], ref_gpu["out"])
+    ref = M.pipeline_minmax([to_numpy_bits(x) for x in xs], L14, 6, bits, rotate=rotate, dtype=np.float32,
+                            bf16=dtype == torch.bfloat16, out_bf16=False)
+    assert (got["range"].cpu().numpy() == ref["range"]).all()
+    for w in range(W):
+        assert (got["payloads"][w].cpu().numpy() == ref["payloads"][w]).all(), f"payload {w}"
+    assert (got["out"].cpu().numpy() == ref["out"]).all()
+    width = got["range"][0, 1] - got["range"][0, 0]
+    assert 0 < float(width) < 2.0 ** -119
+    assert all(int(p[: c * bits // 8].max()) == 0 for p in got["payloads"])
+
+
 def test_one_pass_minmax_refuses_what_it_does_not_cover():
     n, W = 1 << 14, 4
     xs = [torch.zeros(n, device=DEV) for _ in range(W)]

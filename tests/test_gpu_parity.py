@@ -129,6 +129,29 @@ def test_all_zero_and_partly_zero_chunks():
     assert torch.isfinite(got["out"]).all()
 
 
+@pytest.mark.parametrize("l,bits,dtype", [(14, 4, torch.float32), (14, 8, torch.bfloat16), (10, 4, torch.bfloat16),
+                                          (10, 8, torch.float32), (3, 2, torch.float32), (12, 2, torch.bfloat16)])
+def test_scales_too_small_for_the_reciprocal_step(l, bits, dtype):
+    """Chunks whose scale is below and around 2^-120, where L / (2 s) is not finite in fp32:
+    sent like all-zero chunks (tuned chunk-2^14 kernels and the kernels for every other chunk
+    size), against the oracle."""
+    c = 1 << l
+    n = 6 * c - 1
+    xs = []
+    for w in range(3):
+        x = _rand(n, torch.float32, 40 + w, scale=1.0)
+        x[:c] *= 2.0 ** -131
+        x[c:2 * c] *= 2.0 ** -123
+        x[2 * c:3 * c] *= 2.0 ** -121
+        x[3 * c:4 * c] *= 2.0 ** -118
+        xs.append(x.to(dtype))
+    print(f"tiny scales l={l} bits={bits} dtype={dtype}", flush=True)
+    got = run_path(xs, l, 4, bits)
+    check_against_oracle(xs, got, l, 4, bits)
+    assert 0 < got["scale"][0].item() < 2.0 ** -121
+    assert (got["payloads"][0][: c * bits // 8] == 0).all()
+
+
 def test_payload_and_sums_do_not_write_past_their_end():
     l, bits, W = 10, 4, 3
     n = 5 * 1024 + 100

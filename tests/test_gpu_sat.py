@@ -137,6 +137,32 @@ def test_sat_all_zero_chunks_get_the_centre_index(bits, dtype):
         assert (got["out"][:c] == 0).all() and (got["out"][2 * c:3 * c] == 0).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_sat_scales_too_small_for_the_reciprocal_step(bits, dtype):
+    """Chunks whose scale is below and around 2^-120 (the reciprocal grid step is not finite
+    in fp32 below that): sent like all-zero chunks, the centre index everywhere; every form
+    against the oracle."""
+    l, c, W = 14, 1 << 14, 3
+    n = 4 * c
+    M = thc.thc_sat_max(bits)
+    xs = []
+    for w in range(W):
+        x = _rand(n, torch.float32, 700 + w, scale=1.0)
+        x[:c] *= 2.0 ** -131
+        x[c:2 * c] *= 2.0 ** -123
+        x[2 * c:3 * c] *= 2.0 ** -121
+        xs.append(x.to(dtype))
+    for fused in (False, True):
+        print(f"sat tiny scales bits={bits} dtype={dtype} fused={fused}", flush=True)
+        got = run_sat(xs, l, 3, bits, fused_encode=fused, fused_decode=fused)
+        check_sat(xs, got, l, 3, bits)
+        assert 0 < got["scale"][0].item() < 2.0 ** -121
+        centre = sum(M << (bits * j) for j in range(8 // bits))
+        for p in got["payloads"]:
+            assert (p[: c * bits // 8] == centre).all()
+
+
 def test_sat_without_clipping_equals_exact_sum_decode():
     """Small, cancelling values: no Sat step clips, so the saturated aggregate is the
     exact integer sum and the decoded mean equals the exact-sum decode of the same

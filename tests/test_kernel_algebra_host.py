@@ -4,6 +4,8 @@ oracle's exact float32 fused multiply-add (tests only; the kernels share no code
 1. With |y| <= s the rounding rule's t = fma(y, inv, L/2 + u) (grids of up to 32 points)
    or t = fma(y + s, inv, u) (larger grids) satisfies 0 <= t < L + 1, so the clamp
    min(floor(t), L) is dead whenever s is at least the chunk's own largest magnitude.
+   The same on the min/max grid, t = fma(y - lo, inv, u) with inv = L / (hi - lo), when lo
+   and hi are the chunk's own extremes.
 2. For 2^-100 <= s <= 2^100 the normalisation y = v * 2^-7 can be folded into the
    multiplier: fma(v * 2^-7, inv, c) == fma(v, 2^-7 inv, c) bit for bit, and likewise
    fma(v * 2^-7 + s, inv, u) == fma(v + 128 s, 2^-7 inv, u).
@@ -41,6 +43,35 @@ def test_clamp_is_dead_when_scale_is_the_largest_magnitude(bits):
     for y in (-s, -np.nextafter(s, F(0))):
         t = fma32(y + s, inv, u_min) if offset else fma32(y, inv, c_min)
         assert (t > 0).all()
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_clamp_is_dead_on_the_min_max_grid_when_the_range_is_the_chunks_own(bits):
+    """t = fma(fl(y - lo), inv, u) with inv = fl(L / fl(hi - lo)) and lo <= y <= hi: t is
+    monotone in y, so y = hi with the largest noise is the extreme, and floor(t) <= L; at
+    y = lo, t = u > 0.  Ranges of every size and position, also lo and hi of opposite sign,
+    nearly equal, and hugely different in magnitude; widths from 2^-119 up (below that the
+    range is treated as empty, because L / width overflows: 255 / 2^-121 > 2^128)."""
+    L = F((1 << bits) - 1)
+    rng = np.random.default_rng(17)
+    count = 1_000_000
+    a = _random_scales(rng, count, -110, 110) * rng.choice([F(-1), F(1)], size=count).astype(F)
+    b = _random_scales(rng, count, -110, 110) * rng.choice([F(-1), F(1)], size=count).astype(F)
+    b[::5] = a[::5] * (F(1) + F(2.0) ** F(-20))                   # nearly equal
+    b[1::5] = np.nextafter(a[1::5], F(np.inf))                     # adjacent floats
+    lo, hi = np.minimum(a, b), np.maximum(a, b)
+    keep = (hi - lo) >= F(2.0 ** -119)      # narrower ranges are sent as constant chunks (inv = 0)
+    lo, hi = lo[keep], hi[keep]
+    width = hi - lo
+    assert width.dtype == F and len(width) > 500_000
+    inv = L / width
+    u_max, u_min = F(255.5 / 256.0), F(0.5 / 256.0)
+    for y in (hi, np.nextafter(hi, F(-np.inf)), lo + width * F(0.999)):
+        y = np.clip(y, lo, hi)
+        t = fma32(y - lo, inv, u_max)
+        assert t.dtype == F
+        assert (np.floor(t) <= L).all()
+    assert (fma32(lo - lo, inv, u_min) > 0).all()
 
 
 @pytest.mark.parametrize("bits", [2, 4, 8])
