@@ -82,17 +82,20 @@ def _capture(step):
     return graph
 
 
-@pytest.mark.parametrize("form", ["static", "batch", "minmax"])
+@pytest.mark.parametrize("form", ["static", "batch", "minmax", "minmax_unrotated"])
 def test_graph_replays_of_the_other_one_launch_forms(form):
     """thc_encode_all_static (no workspace argument at all), the batched pair (records
     written by argument-carrying kernels) and the one-pass min/max pair under capture:
     every replay against the eager per-bucket calls on the same inputs."""
     l, bits, W = 14, 4, 8
     ns = [40 * (1 << 14) + 77, 25 << 14] if form == "batch" else [120 * (1 << 14) + 77]
+    rotate = form != "minmax_unrotated"
+    if not rotate:
+        ns = [ns[0] + 1]                     # an even bf16 count: the pipelined unrotated encoder
     xs = [[_rand(n, 7 + w + 50 * k) for w in range(W)] for k, n in enumerate(ns)]
     pay = [[torch.empty(thc.thc_payload_bytes(n, l, bits), dtype=torch.uint8, device=DEV) for _ in range(W)]
            for n in ns]
-    per_chunk = 2 if form == "minmax" else 1
+    per_chunk = 2 if form.startswith("minmax") else 1
     scale = [torch.empty(per_chunk * thc.thc_num_chunks(n, l), device=DEV) for n in ns]
     out = [torch.empty(n, device=DEV) for n in ns]
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
@@ -111,8 +114,8 @@ def test_graph_replays_of_the_other_one_launch_forms(form):
         ws = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, ns[0], l), dtype=torch.uint8, device=DEV)
 
         def step():
-            thc.thc_encode_all_minmax(xs[0], l, 5, bits, True, pay[0], scale[0], ws)
-            thc.thc_aggregate_decode_minmax(pay[0], scale[0], ns[0], l, 5, bits, True, out[0])
+            thc.thc_encode_all_minmax(xs[0], l, 5, bits, rotate, pay[0], scale[0], ws)
+            thc.thc_aggregate_decode_minmax(pay[0], scale[0], ns[0], l, 5, bits, rotate, out[0])
     graph = _capture(step)
 
     for rep in range(3):
@@ -134,10 +137,10 @@ def test_graph_replays_of_the_other_one_launch_forms(form):
         for k, n in enumerate(ns):           # eager, between replays
             ref_pay = [torch.empty_like(p) for p in pay[k]]
             ref_scale, ref_out = torch.empty_like(scale[k]), torch.empty_like(out[k])
-            if form == "minmax":
+            if form.startswith("minmax"):
                 w2 = torch.empty(thc.thc_encode_all_minmax_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
-                thc.thc_encode_all_minmax(xs[k], l, 5, bits, True, ref_pay, ref_scale, w2)
-                thc.thc_aggregate_decode_minmax(ref_pay, ref_scale, n, l, 5, bits, True, ref_out)
+                thc.thc_encode_all_minmax(xs[k], l, 5, bits, rotate, ref_pay, ref_scale, w2)
+                thc.thc_aggregate_decode_minmax(ref_pay, ref_scale, n, l, 5, bits, rotate, ref_out)
             else:
                 w2 = torch.empty(thc.thc_encode_all_workspace_bytes(W, n, l), dtype=torch.uint8, device=DEV)
                 thc.thc_encode_all(xs[k], l, 5 + k, bits, ref_pay, ref_scale, w2)
