@@ -383,7 +383,7 @@ def pipeline(xs, chunk_log2, seed, bits, dtype=np.float64, bf16=False, g0=0, rbi
         idx.append(i)
         ts.append(t)
     payloads = [pack(i, bits) for i in idx]
-    sums = aggregate(payloads, bits)
+    sums = aggregate(payloads, bits, count=idx[0].size)   # (a last partial byte holds no coordinates)
     out = decode(sums, scale, W, n, chunk_log2, seed, bits, dtype=dtype, g0=g0)
     return dict(y=ys, absmax=absmax, scale=scale, idx=idx, t=ts, payloads=payloads,
                 sums=sums, out=out)

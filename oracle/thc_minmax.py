@@ -103,6 +103,6 @@ def pipeline_minmax(xs, chunk_log2, seed, bits, rotate=True, dtype=np.float64, b
     rng = range_reduce(ranges_all)
     idx = [quantize_minmax(y, rng, chunk_log2, w, seed, bits, dtype=dtype, g0=g0) for w, y in enumerate(ys)]
     payloads = [T.pack(i, bits) for i in idx]
-    sums = T.aggregate(payloads, bits)
+    sums = T.aggregate(payloads, bits, count=idx[0].size)
     out = decode_minmax(sums, rng, W, n, chunk_log2, seed, bits, rotate, dtype=dtype, g0=g0, out_bf16=out_bf16)
     return dict(y=ys, ranges_all=ranges_all, range=rng, idx=idx, payloads=payloads, sums=sums, out=out)

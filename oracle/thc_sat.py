@@ -116,7 +116,7 @@ def sat_pipeline(xs, chunk_log2, seed, bits, dtype=np.float64, bf16=False, g0=0)
     scale = T.scale_reduce(np.stack([T.chunk_absmax(y, chunk_log2) for y in ys]))
     idx = [sat_quantize(y, scale, chunk_log2, w, seed, bits, dtype=dtype, g0=g0) for w, y in enumerate(ys)]
     payloads = [T.pack(i, bits) for i in idx]
-    A, clipped = sat_aggregate(payloads, bits)
+    A, clipped = sat_aggregate(payloads, bits, count=idx[0].size)
     out = sat_decode(A, scale, W, n, chunk_log2, seed, bits, dtype=dtype, g0=g0)
     return dict(y=ys, scale=scale, idx=idx, payloads=payloads, aggregate=A,
                 packed_aggregate=T.pack(A, bits), clipped=clipped, out=out)

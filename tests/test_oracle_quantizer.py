@@ -419,3 +419,18 @@ def test_ranges_too_small_for_the_reciprocal_step_are_sent_as_empty(bits, dtype)
     assert all(int(p.max()) == 0 for p in res["payloads"])
     mean = np.mean(np.stack(xs).astype(np.float64), axis=0)
     assert np.abs(res["out"] - mean).max() <= 4 * 2.0 ** -119      # 1/sqrt(16) * 16 terms of at most 2^-119
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_pipeline_with_a_partial_last_payload_byte(bits):
+    """Chunks of 2 coordinates, an odd number of them: the payload's last byte is only partly
+    used (10 coordinates x 2 bits = 2.5 bytes); the unused bits are no coordinates, the sums
+    have one entry per padded coordinate, and the estimate is the mean of the workers' own."""
+    W, n, l = 3, 9, 1
+    rng = np.random.default_rng(bits)
+    xs = [rng.standard_normal(n).astype(np.float32) for _ in range(W)]
+    res = pipeline(xs, l, 3, bits, dtype=np.float64)
+    assert res["sums"].size == 10 and len(res["scale"]) == 5
+    assert all(p.size == (10 * bits + 7) // 8 for p in res["payloads"])
+    singles = [decode(aggregate([p], bits, count=10), res["scale"], 1, n, l, 3, bits) for p in res["payloads"]]
+    assert np.allclose(res["out"], np.mean(singles, axis=0), rtol=0, atol=1e-12)
