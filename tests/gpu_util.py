@@ -117,7 +117,7 @@ def check_against_oracle(xs, got, l, seed, bits, chunks=None):
         if absmax is not None:
             assert (absmax[:, p0:p0 + np_] == ref["absmax"]).all(), f"absmax differs, chunk {p0}"
         assert (scale[p0:p0 + np_] == ref["scale"]).all(), f"scale differs, chunk {p0}"
-        b0, b1 = g0 * bits // 8, (g0 + np_ * c) * bits // 8
+        b0, b1 = g0 * bits // 8, ((g0 + np_ * c) * bits + 7) // 8   # (chunks of 2 x 2 bits end inside a byte)
         for w in range(W):
             same = pay[w][b0:b1] == ref["payloads"][w]
             assert same.all(), f"payload of worker {w} differs in chunk {p0}: {np.flatnonzero(~same)[:8]}"

@@ -297,3 +297,16 @@ def test_coordinates_beyond_2_to_32():
     for a, b in zip(fused_pay, got["payloads"]):
         assert torch.equal(a, b)
     assert torch.equal(fused_out, got["out"])
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("n", [9, 10, 1, 101])
+def test_chunks_of_two_coordinates_and_a_partial_last_payload_byte(n, bits):
+    """The smallest chunk: with 2-bit indices an odd number of chunks ends inside a payload
+    byte (thc_payload_bytes rounds up); both forms against the oracle."""
+    from gpu_util import run_path_fused
+    xs = [_rand(n, torch.float32, 60 + w, heavy=False) for w in range(3)]
+    print(f"chunk 2, n={n} bits={bits}", flush=True)
+    assert thc.thc_payload_bytes(n, 1, bits) == (((n + 1) // 2) * 2 * bits + 7) // 8
+    check_against_oracle(xs, run_path(xs, 1, 8, bits), 1, 8, bits)
+    check_against_oracle(xs, run_path_fused(xs, 1, 8, bits), 1, 8, bits)
