@@ -1,0 +1,149 @@
+"""Randomized differential test: every variant of the path on inputs drawn from degenerate
+magnitude and sparsity patterns (chunks that are zero, constant, a single non-zero, far
+below the smallest normal float, around the 2^-119 range below which a chunk is sent as
+empty, or huge; heavy tails; shifted data; 1 to 64 workers; every chunk size), each case
+compared element by element with the oracle.  Seeds are fixed: the cases are the same in
+every run."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_01378_amd as thc
+from oracle import thc as O
+from oracle import thc_minmax as M
+from oracle import topkc as K
+from synth import to_numpy_bits
+
+from gpu_util import DEV, check_against_oracle, run_path, run_path_fused, run_path_timed
+from test_gpu_minmax import run_minmax
+from test_gpu_minmax_fused import run_fused
+from test_gpu_sat import check_sat, run_sat
+from test_gpu_topkc import check as check_topkc, run_topkc
+
+pytestmark = pytest.mark.gpu
+
+MAGS = [0.0, 2.0 ** -140, 2.0 ** -127, 2.0 ** -121, 2.0 ** -119.5, 2.0 ** -118, 2.0 ** -100, 1e-20, 1e-3, 1.0, 37.0,
+        2.0 ** 60, 2.0 ** 99, 2.0 ** 101, 2.0 ** 104]
+C14 = 1 << 14
+
+
+def _inputs(rnd, case, W, dtype, n):
+    """W gradients of n values; chunk p of worker w has magnitude pattern[w][p]."""
+    P = (n + C14 - 1) // C14
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1000 + case)
+    pattern = [[rnd.choice(MAGS) for _ in range(P)] for _ in range(W)]
+    if rnd.random() < 0.5:                       # the same magnitude for every worker of a chunk
+        pattern = [pattern[0]] * W
+    xs = []
+    for w in range(W):
+        x = torch.randn(n, generator=g, device=DEV)
+        if rnd.random() < 0.5:                   # heavy tails
+            x = x / torch.sqrt((torch.randn(3, n, generator=g, device=DEV) ** 2).mean(dim=0))
+        shift = rnd.choice([0.0, 0.0, 0.25, -3.0])
+        for p in range(P):
+            lo, hi = p * C14, min(n, (p + 1) * C14)
+            x[lo:hi] = x[lo:hi] * pattern[w][p] + shift * pattern[w][p]
+            kind = rnd.random()
+            if kind < 0.1:
+                x[lo:hi] = pattern[w][p]         # a constant chunk
+            elif kind < 0.2:                     # a single non-zero
+                keep = x[lo + (hi - lo) // 2].clone()
+                x[lo:hi] = 0
+                x[lo + (hi - lo) // 2] = keep
+        xs.append(x.to(dtype))
+    return xs
+
+
+def _same_or_both_nan(a, b):
+    return ((a == b) | (np.isnan(a) & np.isnan(b))).all()
+
+
+def _one_case(rnd, case, wide):
+    W = rnd.choice([8, 18, 33, 64]) if wide else rnd.choice([1, 2, 3, 5, 8])
+    bits = rnd.choice([2, 4, 8])
+    dtype = rnd.choice([torch.float32, torch.bfloat16])
+    chunks = rnd.randint(1, 2) if W > 8 else rnd.randint(1, 5)
+    n = chunks * C14 + rnd.choice([0, 2, 7, 100, 8192, C14 - 2])
+    xs = _inputs(rnd, case, W, dtype, n)
+    bf16 = dtype == torch.bfloat16
+    seed = rnd.randint(0, 2 ** 40)
+    variant = rnd.choice(["fused", "timed", "per_step", "sat", "minmax_rotated", "minmax_unrotated", "other_chunk_size",
+                          "other_chunk_size", "topkc", "topkc"])
+    if variant.startswith("minmax") and not thc.thc_aggregate_decode_is_fused(W, 14, bits):
+        variant = "fused"
+    if W > 8 and variant in ("other_chunk_size", "topkc"):
+        variant = "fused"
+    print(f"case {case} {variant} W={W} bits={bits} {dtype} n={n} seed={seed}", flush=True)
+    if variant == "fused":
+        check_against_oracle(xs, run_path_fused(xs, 14, seed, bits), 14, seed, bits)
+    elif variant == "timed":
+        check_against_oracle(xs, run_path_timed(xs, 14, seed, bits), 14, seed, bits)
+    elif variant == "per_step":
+        check_against_oracle(xs, run_path(xs, 14, seed, bits), 14, seed, bits)
+    elif variant == "sat":
+        fused = rnd.random() < 0.5
+        check_sat(xs, run_sat(xs, 14, seed, bits, fused_encode=fused, fused_decode=fused), 14, seed, bits)
+    elif variant == "other_chunk_size":
+        l = rnd.choice([1, 2, 3, 5, 8, 10, 12, 13])
+        m = min(n, (1 << l) * rnd.randint(1, 40) + rnd.choice([0, 1, 3]))
+        ys = [x[:m].clone() for x in xs]
+        form = rnd.choice(["per_step", "fused", "sat"])
+        print(f"    chunk 2^{l}, {m} values, {form}", flush=True)
+        if form == "sat":
+            check_sat(ys, run_sat(ys, l, seed, bits, fused_encode=True, fused_decode=True), l, seed, bits)
+            return
+        got = run_path(ys, l, seed, bits) if form == "per_step" else run_path_fused(ys, l, seed, bits)
+        ref = O.pipeline([to_numpy_bits(y) for y in ys], l, seed, bits, dtype=np.float32, bf16=bf16)
+        if np.abs(ref["out"]).max() < 2.0 ** -110:
+            # a vector of subnormal size: fp32 cannot meet a relative bound against the float64
+            # definition there; the fp32 order is the whole check
+            assert (got["scale"].cpu().numpy() == ref["scale"]).all()
+            for w in range(W):
+                assert (got["payloads"][w].cpu().numpy() == ref["payloads"][w]).all()
+            assert (got["out"].cpu().numpy() == ref["out"]).all()
+        else:
+            check_against_oracle(ys, got, l, seed, bits)
+    elif variant == "topkc":
+        C = rnd.choice([8, 16, 64, 128, 512])
+        m = rnd.randint(1, n)
+        ys = [x[:m].clone() for x in xs]
+        Pk = (m + C - 1) // C
+        J = rnd.choice([1, Pk, max(1, Pk // 2), rnd.randint(1, Pk)])
+        print(f"    C={C}, {m} values, J={J}", flush=True)
+        got = run_topkc(ys, C, J)
+        ref = K.pipeline([to_numpy_bits(y) for y in ys], C, J, bf16=bf16)
+        if np.isnan(ref["out"]).any():           # fp16 overflow (inf - inf): NaN at the same places
+            bits16 = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            for w in range(W):
+                assert (bits16(got["norms"][w]) == ref["norms"][w].view(np.uint16)).all()
+            assert (bits16(got["s"]) == ref["s"].view(np.uint16)).all()
+            assert (got["indices"].cpu().numpy().view(np.uint32) == ref["indices"]).all()
+            assert _same_or_both_nan(got["values"].float().cpu().numpy(), ref["values"].astype(np.float32))
+            assert _same_or_both_nan(got["out"].cpu().numpy(), ref["out"])
+        else:
+            check_topkc(ys, got, C, J)
+    else:
+        rotate = variant == "minmax_rotated"
+        got = run_fused(xs, seed, bits, rotate)
+        per_step = run_minmax(xs, 14, seed, bits, rotate, torch.float32)
+        assert torch.equal(got["range"], per_step["range"])
+        for w in range(W):
+            assert torch.equal(got["payloads"][w], per_step["payloads"][w]), f"payload {w}: one-pass != per-step"
+        assert _same_or_both_nan(got["out"].cpu().numpy(), per_step["out"].cpu().numpy())
+        ref = M.pipeline_minmax([to_numpy_bits(x) for x in xs], 14, seed, bits, rotate=rotate, dtype=np.float32,
+                                bf16=bf16, out_bf16=False)
+        assert (got["range"].cpu().numpy() == ref["range"]).all()
+        for w in range(W):
+            assert (got["payloads"][w].cpu().numpy() == ref["payloads"][w]).all(), f"payload {w}"
+        assert _same_or_both_nan(got["out"].cpu().numpy(), ref["out"])
+
+
+@pytest.mark.parametrize("seed,cases,wide", [(1, 150, False), (2, 150, False), (3, 60, True)])
+def test_randomized_degenerate_inputs_against_the_oracle(seed, cases, wide):
+    rnd = random.Random(seed)
+    with np.errstate(all="ignore"):
+        for case in range(cases):
+            _one_case(rnd, case, wide)
