@@ -105,6 +105,12 @@ struct EncodeAllCtx {
     BucketView cur, nxt;    // of the item being processed / of the item whose input is in flight
     static constexpr uint32_t kNone = 0xFFFFFFFFu;
 
+    // MINMAX: the chunk's words as 8-byte pairs (the slots start 16-byte aligned and a chunk
+    // has an even number of 32-bit words)
+    __device__ __forceinline__ uint64_t* pairs(uint64_t p) const {
+        return reinterpret_cast<uint64_t*>(a.slots + p * nwords);
+    }
+
     __device__ __forceinline__ BucketView view_of(uint64_t p) {
         if constexpr (BATCH) {
             while (bidx + 1u < batch.count && p >= batch_record(batch, bidx + 1u)->chunk0) ++bidx;
@@ -193,12 +199,11 @@ struct EncodeAllCtx {
             const MinMax r = thread_minmax(v);
             const uint32_t khi = wave_umax(order_key(r.hi * kInvSqrtC));
             const uint32_t klo = wave_umax(order_key(-(r.lo * kInvSqrtC)));
-            if (lane == 0) {
-                __hip_atomic_store(&a.slots[p * nwords + kWaves * w + wave], khi, __ATOMIC_RELAXED,
+            // one 8-byte word per wave, (key of the maximum) << 32 | key of the negated minimum:
+            // an aligned 8-byte store is one transaction, so a reader sees both or neither
+            if (lane == 0)
+                __hip_atomic_store(pairs(p) + kWaves * w + wave, ((uint64_t)khi << 32) | klo, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&a.slots[p * nwords + kWaves * a.W + kWaves * w + wave], klo, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            }
         } else if constexpr (WGWORD) {
             const float m = wave_absmax(v) * kInvSqrtC;
             if (lane == 0) sh.red[wave] = m;
@@ -243,17 +248,15 @@ struct EncodeAllCtx {
         for (uint32_t spins = 0;; ++spins) {
             if constexpr (MINMAX) {
                 const uint32_t half = kWaves * a.W;
+                const uint64_t* pair = pairs(p);
                 bool all_valid = true;
                 mx = mx2 = 0u;
                 for (uint32_t base = 0; base < half; base += 64u) {
                     const uint32_t i = base + lane;
-                    const bool in = i < half;
-                    const uint32_t vh =
-                        in ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-                    const uint32_t vl =
-                        in ? __hip_atomic_load(&slot[half + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-                    all_valid = all_valid && vh != 0u && vl != 0u;
-                    if (in) {
+                    if (i < half) {
+                        const uint64_t v = __hip_atomic_load(&pair[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const uint32_t vh = (uint32_t)(v >> 32), vl = (uint32_t)v;
+                        all_valid = all_valid && v != 0ull;   // (neither key is ever zero)
                         mx = vh > mx ? vh : mx;
                         mx2 = vl > mx2 ? vl : mx2;
                     }
@@ -293,11 +296,11 @@ struct EncodeAllCtx {
         // the workgroup's previous chunk; with all of this chunk's words seen, nobody
         // will read the previous chunk's words again, and this wave clears its own.
         if (done && prev != kNone && lane == 0 && (!WGWORD || wave == 0)) {
-            __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWordsPerWorker * w + (WGWORD ? 0u : wave)], 0u,
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (MINMAX)
-                __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWaves * a.W + kWaves * w + wave], 0u,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (MINMAX)
+                __hip_atomic_store(pairs(prev) + kWaves * w + wave, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                __hip_atomic_store(&a.slots[(uint64_t)prev * nwords + kWordsPerWorker * w + (WGWORD ? 0u : wave)],
+                                   0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         const uint32_t sbits = wave_umax(mx);
         prev = (uint32_t)p;

@@ -31,28 +31,29 @@ constexpr int kPollSleep = 8;
 // the minimum with L never binds
 constexpr bool kClampRanged = false;
 
-// ---- the range words of a chunk: two per wave of every worker's workgroup, the maxima
-// first, then the negated minima (so that both are combined by a maximum) ----------------
+// ---- the range words of a chunk: one 8-byte pair per wave of every worker's workgroup,
+// (key of the maximum) << 32 | key of the negated minimum (so that both are combined by a
+// maximum).  An aligned 8-byte store is one transaction: a reader sees both keys or neither.
 struct Words {
     const EncodeAllArgs& a;
-    uint32_t half;     // words of one kind per chunk
-    uint32_t nwords;   // 2 * half
-    uint32_t mine;     // this wave's index among the words of one kind
+    uint32_t half;     // pairs per chunk
+    uint32_t nwords;   // 2 * half 32-bit words
+    uint32_t mine;     // this wave's pair
     uint32_t lane;
 
+    __device__ __forceinline__ uint64_t* pairs(uint64_t p) const {
+        return reinterpret_cast<uint64_t*>(a.slots + p * nwords);
+    }
     __device__ __forceinline__ void publish(uint64_t p, uint32_t khi, uint32_t klo) const {
-        if (lane == 0) {
-            __hip_atomic_store(&a.slots[p * nwords + mine], khi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.slots[p * nwords + half + mine], klo, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if (lane == 0)
+            __hip_atomic_store(pairs(p) + mine, ((uint64_t)khi << 32) | klo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // Waits until every wave of every worker of chunk p has published; bounded by
     // a.max_spins polls, after which the error word is set and the wave carries on with
     // what it has seen and its own range (khi, klo).  Returns the keys of (hi, -lo).
     template <bool SLEEP_FIRST = true>
     __device__ __forceinline__ bool wait(uint64_t p, uint32_t& khi, uint32_t& klo) const {
-        const uint32_t* slot = a.slots + p * nwords;
+        const uint64_t* pair = pairs(p);
         uint32_t mxh = 0u, mxl = 0u;
         bool done = false;
         if (SLEEP_FIRST) __builtin_amdgcn_s_sleep(kFirstPollSleep);
@@ -61,12 +62,10 @@ struct Words {
             mxh = mxl = 0u;
             for (uint32_t base = 0; base < half; base += 64u) {
                 const uint32_t i = base + lane;
-                const bool in = i < half;
-                const uint32_t vh = in ? __hip_atomic_load(&slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-                const uint32_t vl =
-                    in ? __hip_atomic_load(&slot[half + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
-                all_valid &= (uint32_t)(vh != 0u && vl != 0u);
-                if (in) {
+                if (i < half) {
+                    const uint64_t v = __hip_atomic_load(&pair[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint32_t vh = (uint32_t)(v >> 32), vl = (uint32_t)v;
+                    all_valid &= (uint32_t)(v != 0ull);   // (neither key is ever zero)
                     mxh = vh > mxh ? vh : mxh;
                     mxl = vl > mxl ? vl : mxl;
                 }
@@ -82,14 +81,9 @@ struct Words {
         klo = kl > klo ? kl : klo;
         return done;
     }
-    // This wave's two words of an earlier chunk back to zero.
+    // This wave's pair of an earlier chunk back to zero.
     __device__ __forceinline__ void clear_mine(uint32_t chunk) const {
-        if (lane == 0) {
-            __hip_atomic_store(&a.slots[(uint64_t)chunk * nwords + mine], 0u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&a.slots[(uint64_t)chunk * nwords + half + mine], 0u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if (lane == 0) __hip_atomic_store(pairs(chunk) + mine, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // A workgroup's last chunks have no later chunk to vouch for them: the W workgroups of the
     // chunk count themselves off and the last one clears all its words and the counter.  Called
