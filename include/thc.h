@@ -124,11 +124,13 @@ int thc_scale_reduce(const float* absmax_all, uint32_t W, uint64_t chunks, float
  * the 2^bits-point grid of [-s_p, +s_p] (index 0 at -s_p, index L = 2^bits - 1 at
  * +s_p), and bit-pack:
  *     inv = L / (s_p + s_p),  u = (r + 0.5) / 256,
- *     idx = min(floor(t), L),  t = y * inv + L/2 + u;   s_p == 0: idx = 0
+ *     idx = min(floor(t), L),  t = y * inv + L/2 + u;   s_p + s_p < 2^-119: idx = 0
  * (the position in grid units plus the noise u; inv is one correctly rounded division;
  * t is evaluated as fma(y, inv, L/2 + u) for bits = 2 and 4, where L/2 + u is exact in
  * fp32, and as fma(y + s_p, inv, u) for bits = 8, which keeps t within 1e-6 max(1, |t|) of
- * its exact value on the 256-point grid).
+ * its exact value on the 256-point grid).  A chunk whose range s_p + s_p is below 2^-119 -
+ * an all-zero chunk, or one so small that fp32 cannot hold L / (s_p + s_p) - is sent as
+ * zeros; it keeps its scale and decodes at most 2^-119 off per rotated coordinate.
  *   shared_scale  chunks fp32 (the output of thc_scale_reduce), or NULL to use
  *                 this worker's own absmax
  *   payload       thc_payload_bytes bytes; coordinate g occupies bits
@@ -281,7 +283,8 @@ int thc_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const float
  * sends (b = q).  Readings taken where the paper is silent:
  *   - a worker's coordinate is rounded onto the 2M + 1 evenly spaced points of
  *     [-s_p, +s_p] (same rule and random stream as thc_encode with L = 2M, except that
- *     an all-zero chunk, s_p = 0, gets the centre index M so that z = 0); the payload
+ *     an all-zero chunk - and one with s_p + s_p < 2^-119, as in thc_encode - gets the centre
+ *     index M so that z = 0); the payload
  *     holds idx in [0, 2M] in `bits` bits, packed as for thc_encode; z = idx - M;
  *   - Sat is not associative: a_0 = z_0, a_w = Sat(a_(w-1), z_w) in worker order
  *     w = 1 .. W-1 (the order payloads[] is given in);
@@ -338,7 +341,8 @@ int thc_sat_aggregate_decode(const uint8_t* const* payloads, uint32_t W, const f
  * optional bf16 output ------------------------------------------------------------------
  * range arrays hold (lo, hi) pairs, 2 floats per chunk, 8-byte aligned.  The grid of a chunk
  * has 2^bits points, index 0 at lo and index L at hi, shared by all workers:
- *     inv = L / (hi - lo)  (0 when hi == lo),  idx = min(floor(fma(y - lo, inv, u)), L)
+ *     inv = L / (hi - lo)  (0 when hi - lo < 2^-119: a constant chunk, or a range too narrow
+ *     for fp32 to hold its reciprocal step),  idx = min(floor(fma(y - lo, inv, u)), L)
  *     (the subtraction is rounded on its own; the product and the sum are one fused op)
  *     step = (hi - lo) / L,  yhat = float(sum) * (step / W) + lo
  * rotate != 0: y is the chunk's rotated gradient as in thc_encode; rotate == 0: y is the
