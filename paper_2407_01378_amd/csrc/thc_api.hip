@@ -773,9 +773,10 @@ static int check_full(uint64_t n, uint32_t log2_size) {
 }
 
 static float full_factor(uint32_t log2_size) {
-    // the chunk kernels already multiply by 2^-7; what is left of fl(2^(-l/2)) is that
-    // constant times 2^7 (exact), so the product equals a single multiplication by it
-    return (float)(1.0 / sqrt((double)(1ull << log2_size))) * 128.0f;
+    // the whole normalisation fl(2^(-l/2)) is ONE multiplication after the last stage (the
+    // chunk kernels of the first pass are told to multiply by 1): a 2^-7 taken early would
+    // round where an intermediate value is subnormal
+    return (float)(1.0 / sqrt((double)(1ull << log2_size)));
 }
 
 uint32_t thc_full_log2(uint64_t n) {
@@ -796,6 +797,7 @@ int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size
     a.in = x;
     a.out = y;
     a.in_bf16 = dt == THC_BF16;
+    a.inv_sqrt_c = 1.0f;
     if (n != 0 && thc::launch_fast14(Mode::Forward, a, st) != hipSuccess) return THC_ERR_HIP;
     const uint64_t total = 1ull << log2_size;
     if (total > a.padded &&
@@ -816,6 +818,7 @@ int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, fl
     ChunkArgs a = base_args(total, 14, seed);
     a.in = y;
     a.out = y;
+    a.inv_sqrt_c = 1.0f;
     if (thc::launch_fast14(Mode::Plain, a, st) != hipSuccess) return THC_ERR_HIP;
     return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), x, n, a.key0, a.key1, st));
 }

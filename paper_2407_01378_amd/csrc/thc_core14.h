@@ -527,11 +527,12 @@ __device__ __forceinline__ void quantize_store_range(const float (&v)[kRegs], fl
     store_packed<BITS>(pk, payload + (g * BITS) / 8u);
 }
 
-// Output side of the inverse rotation: x = D (v * 2^-7) from layout L4d; the first
-// `valid` coordinates of the chunk are stored.
+// Output side of the inverse rotation: x = D (v * norm), norm = 2^-7, from layout L4d; the
+// first `valid` coordinates of the chunk are stored.  (The first pass of a longer rotation
+// passes norm = 1: its normalisation is one multiplication at the very end.)
 template <bool SIGNED = true>
 __device__ __forceinline__ void store_signed_l4d(const SignTable& tab, const float (&v)[kRegs], float* out,
-                                                 uint32_t valid, uint32_t t) {
+                                                 uint32_t valid, uint32_t t, float norm = kInvSqrtC) {
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
         const uint32_t i0 = h * 2048u + t * 4u;
@@ -539,7 +540,7 @@ __device__ __forceinline__ void store_signed_l4d(const SignTable& tab, const flo
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            x[e] = __uint_as_float(__float_as_uint(v[4 * h + e] * kInvSqrtC) ^ ((sb << (31 - e)) & 0x80000000u));
+            x[e] = __uint_as_float(__float_as_uint(v[4 * h + e] * norm) ^ ((sb << (31 - e)) & 0x80000000u));
         if (i0 + 4u <= valid) {
             store_streaming(out + i0, x[0], x[1], x[2], x[3]);
         } else {

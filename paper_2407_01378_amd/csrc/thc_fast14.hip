@@ -40,8 +40,8 @@ __global__ __launch_bounds__(kThreads) void per_worker_kernel(const ChunkArgs a)
 #pragma unroll
         for (int h = 0; h < 8; ++h)
             *reinterpret_cast<float4*>(y + h * 2048 + t * 4) =
-                make_float4(v[4 * h] * kInvSqrtC, v[4 * h + 1] * kInvSqrtC, v[4 * h + 2] * kInvSqrtC,
-                            v[4 * h + 3] * kInvSqrtC);
+                make_float4(v[4 * h] * a.inv_sqrt_c, v[4 * h + 1] * a.inv_sqrt_c, v[4 * h + 2] * a.inv_sqrt_c,
+                            v[4 * h + 3] * a.inv_sqrt_c);   // 2^-7, or 1 as the first pass of a longer rotation
     } else if constexpr (MODE == Mode::Absmax) {
         const float m = chunk_absmax(sh, v, lane, wave) * kInvSqrtC;
         if (t == 0) static_cast<float*>(a.out)[p] = m;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
     }
     rotate_l1_to_l3<false>(sh, v, lane, wave);
     l3_to_l4d<false>(sh, v, lane, wave);
-    store_signed_l4d<SIGNED>(sh.sign[0], v, static_cast<float*>(a.out) + g0, valid, t);
+    store_signed_l4d<SIGNED>(sh.sign[0], v, static_cast<float*>(a.out) + g0, valid, t, a.inv_sqrt_c);
 }
 
 template <bool BF16, Mode MODE>

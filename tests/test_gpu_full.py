@@ -96,11 +96,14 @@ def _full_pipeline(l, n, W, bits, dtype, magnitude=1.0):
     return float(scale[0]), payloads
 
 
-@pytest.mark.parametrize("bits,dtype", [(4, torch.float32), (8, torch.bfloat16)])
-def test_full_rotation_of_a_vanishingly_small_gradient(bits, dtype):
+@pytest.mark.parametrize("l,n,W,bits,dtype", [(15, 30_000, 3, 4, torch.float32), (15, 30_000, 3, 8, torch.bfloat16),
+                                               (16, 40_260, 8, 4, torch.float32), (19, 355_054, 18, 8, torch.float32)])
+def test_full_rotation_of_a_vanishingly_small_gradient(l, n, W, bits, dtype):
     """A whole gradient whose scale is below 2^-120 (L / (2 s) is not finite in fp32): sent as
-    zeros, as the oracle does."""
-    s, payloads = _full_pipeline(15, 30_000, 3, bits, dtype, magnitude=2.0 ** -128)
+    zeros, as the oracle does.  The rotated values are subnormal, so the normalisation must be
+    the single multiplication after the last stage that the oracle performs: a factor 2^-7
+    taken after the first 14 stages would round there (the last two shapes caught that)."""
+    s, payloads = _full_pipeline(l, n, W, bits, dtype, magnitude=2.0 ** -128)
     assert 0 < s < 2.0 ** -121
     assert all(int(p.max()) == 0 for p in payloads)
 
