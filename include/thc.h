@@ -394,7 +394,8 @@ int thc_aggregate_decode_minmax(const uint8_t* const* payloads, uint32_t W, cons
  * chunk_log2 = log2_size, which the chunked entry points do not accept above 14).
  * Stages above 2^14 run as passes over y in global memory, in place, so rotated data is
  * materialised and the quantizer's steps are separate elementwise calls:
- *     rht_forward_full -> thc_full_absmax -> (thc_scale_reduce with chunks = 1)
+ *     rht_forward_full -> thc_full_absmax (or rht_forward_full_absmax for both)
+ *     -> (thc_scale_reduce with chunks = 1)
  *     -> thc_full_encode -> thc_aggregate(n = 2^log2_size, chunk_log2 = 14)
  *     -> thc_full_decode -> rht_inverse_full
  * 15 <= log2_size <= 33 (THC_ERR_CHUNK otherwise), n <= 2^log2_size (THC_ERR_SIZE);
@@ -406,6 +407,11 @@ uint32_t thc_full_log2(uint64_t n);
 /*   x   n values of dtype dt;   y   2^log2_size fp32, receives the rotated vector */
 int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
                      float* y, void* stream);
+
+/* The same, and *absmax = max |y_g| in the same launches (what thc_full_absmax computes in a
+ * pass of its own over y); absmax: device, one float, 4-byte aligned. */
+int rht_forward_full_absmax(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                            float* y, float* absmax, void* stream);
 
 /*   y   2^log2_size fp32 rotated values, USED AS SCRATCH (garbage afterwards);
  *   x   n fp32, receives D 2^(-l/2) H y */

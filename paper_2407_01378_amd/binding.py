@@ -121,6 +121,8 @@ _SIGNATURES = {
     "thc_full_log2": (ctypes.c_uint32, [ctypes.c_uint64]),
     "rht_forward_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "rht_forward_full_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                               ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "rht_inverse_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_full_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p,
@@ -477,6 +479,13 @@ def thc_sat_aggregate_decode(payloads, scale, n, chunk_log2, seed, bits, aggrega
 # -------------------------------------------------------------------- full rotation
 def thc_full_log2(n):
     return lib().thc_full_log2(n)
+
+
+def rht_forward_full_absmax(x, log2_size, seed, y, absmax, stream=None):
+    _flat(x), _flat(y, torch.float32), _flat(absmax, torch.float32)
+    _check(lib().rht_forward_full_absmax(_ptr(x), _dtype_code(x), x.numel(), log2_size, seed, _ptr(y),
+                                         _ptr(absmax), _stream(stream)), "rht_forward_full_absmax")
+    return y
 
 
 def rht_forward_full(x, log2_size, seed, y, stream=None):

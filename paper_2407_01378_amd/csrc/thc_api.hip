@@ -785,8 +785,8 @@ uint32_t thc_full_log2(uint64_t n) {
     return (1ull << l) >= n ? l : 0;
 }
 
-int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
-                     float* y, void* stream) {
+static int forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                        float* y, float* absmax, void* stream) {
     int rc = check_full(n, log2_size);
     if (rc == THC_OK) rc = check_dtype(dt);
     if (rc != THC_OK) return rc;
@@ -799,12 +799,21 @@ int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size
     a.in_bf16 = dt == THC_BF16;
     a.inv_sqrt_c = 1.0f;
     if (n != 0 && thc::launch_fast14(Mode::Forward, a, st) != hipSuccess) return THC_ERR_HIP;
-    const uint64_t total = 1ull << log2_size;
-    if (total > a.padded &&
-        thc::launch_zero_words(reinterpret_cast<uint32_t*>(y + a.padded), total - a.padded, st) != hipSuccess)
-        return THC_ERR_HIP;
-    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), nullptr, 0, a.key0,
-                                          a.key1, st));
+    // (the zero padding behind the last chunk is not written: the first pass reads it as zero)
+    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), nullptr, 0, a.key0, a.key1, st,
+                                          a.padded, absmax));
+}
+
+int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                     float* y, void* stream) {
+    return forward_full(x, dt, n, log2_size, seed, y, nullptr, stream);
+}
+
+int rht_forward_full_absmax(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                            float* y, float* absmax, void* stream) {
+    if (!absmax) return THC_ERR_NULL;
+    if (!aligned(absmax, 4)) return THC_ERR_ALIGN;
+    return forward_full(x, dt, n, log2_size, seed, y, absmax, stream);
 }
 
 int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, float* x, void* stream) {
@@ -820,7 +829,8 @@ int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, fl
     a.out = y;
     a.inv_sqrt_c = 1.0f;
     if (thc::launch_fast14(Mode::Plain, a, st) != hipSuccess) return THC_ERR_HIP;
-    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), x, n, a.key0, a.key1, st));
+    return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), x, n, a.key0, a.key1, st,
+                                          total, nullptr));
 }
 
 int thc_full_absmax(const float* y, uint32_t log2_size, float* absmax, void* stream) {

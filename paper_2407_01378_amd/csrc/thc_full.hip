@@ -33,6 +33,12 @@ struct HighPassArgs {
     uint32_t last;      // 1: multiply by `factor`
     float factor;
     uint32_t key0, key1;
+    uint64_t valid;     // floats of `data` that hold values; what lies beyond reads as zero and
+                        // is neither read nor, in a pass that is not the last, written (the zero
+                        // padding behind the gradient is implied, pass after pass, until the
+                        // last pass mixes it with everything)
+    uint32_t* absmax;   // last forward pass: receives max |value written| by an unsigned atomic
+                        // maximum (zeroed beforehand); may be null
 };
 
 __device__ __forceinline__ void row_butterflies(float (&v)[32], int bit, bool enabled) {
@@ -61,6 +67,9 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
     const uint64_t tile = blockIdx.x;
     const uint64_t jb = tile & ((1ull << jb_bits) - 1ull);
     const uint64_t hi = tile >> jb_bits;
+    // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
+    // zero padding its results are zero too, and the next pass is told so instead of reading them
+    if ((hi << (a.s0 + a.m)) >= a.valid) return;
     const uint64_t base = (hi << (a.s0 + a.m)) + (jb << (5u + skip));
     auto offset = [&](uint32_t row) -> uint64_t {               // first float of (row, jq)
         const uint64_t k = row >> skip;
@@ -72,11 +81,15 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
     // rows r + 8 la + 64 w
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        const float4 q = *reinterpret_cast<const float4*>(a.data + offset(r + 8u * la + 64u * w));
-        v[4 * r] = q.x;
-        v[4 * r + 1] = q.y;
-        v[4 * r + 2] = q.z;
-        v[4 * r + 3] = q.w;
+        // (the load is unconditional, from the array's start where the row lies in the implied
+        // padding, so that the eight loads stay back to back; the select comes afterwards)
+        const uint64_t g = offset(r + 8u * la + 64u * w);   // a multiple of 4, as `valid` is
+        const bool in = g < a.valid;
+        const float4 q = *reinterpret_cast<const float4*>(a.data + (in ? g : 0u));
+        v[4 * r] = in ? q.x : 0.0f;
+        v[4 * r + 1] = in ? q.y : 0.0f;
+        v[4 * r + 2] = in ? q.z : 0.0f;
+        v[4 * r + 3] = in ? q.w : 0.0f;
     }
 #pragma unroll
     for (int b = 0; b < 3; ++b) row_butterflies(v, b, (uint32_t)b >= skip);
@@ -114,6 +127,7 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
 #pragma unroll
     for (int b = 0; b < 3; ++b) row_butterflies(v, b, (uint32_t)(6 + b) >= skip);
 
+    float largest = 0.0f;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const uint64_t g = offset(la + 8u * w + 64u * (uint32_t)r);
@@ -122,6 +136,7 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = o[e] * a.factor;
         }
+        if (!TO_X) largest = fmaxf(fmaxf(largest, fmaxf(fabsf(o[0]), fabsf(o[1]))), fmaxf(fabsf(o[2]), fabsf(o[3])));
         if constexpr (TO_X) {
             if (g < a.n) {
                 const u32x4 sb = sign_block(g >> 7, a.key0, a.key1);
@@ -139,6 +154,13 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
         } else {
             *reinterpret_cast<float4*>(a.data + g) = make_float4(o[0], o[1], o[2], o[3]);
         }
+    }
+    if (!TO_X && a.absmax) {   // (uniform over the grid) non-negative floats order like their bit patterns
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) largest = fmaxf(largest, __shfl_xor(largest, o, 64));
+        // (a stale read only costs an atomic more; most workgroups stay below the running maximum)
+        if (lane == 0 && __float_as_uint(largest) > __hip_atomic_load(a.absmax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(a.absmax, __float_as_uint(largest));
     }
 }
 
@@ -222,9 +244,17 @@ __global__ __launch_bounds__(256) void full_decode_kernel(const SumT* sums, uint
 
 // Stages 14 .. l-1 on data (2^l floats, stages 0..13 already done), in place; the last pass
 // multiplies by `factor`, and for the inverse direction (`x` non-null) applies the sign
-// diagonal and writes the first n coordinates to x instead.
+// diagonal and writes the first n coordinates to x instead.  Forward direction: only the
+// first `valid` floats of data have been written (the rest is the zero padding, which the
+// first pass supplies by itself), and `absmax`, if not null, receives the largest
+// magnitude of the result (the word is zeroed here first).
 hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
-                              uint32_t key0, uint32_t key1, hipStream_t stream) {
+                              uint32_t key0, uint32_t key1, hipStream_t stream, uint64_t valid,
+                              float* absmax) {
+    if (absmax) {
+        const hipError_t e = launch_zero_words(reinterpret_cast<uint32_t*>(absmax), 1, stream);
+        if (e != hipSuccess) return e;
+    }
     const uint32_t high = log2_size - kTileLog2;
     const uint32_t passes = (high + 8u) / 9u;
     const dim3 grid((uint32_t)(1ull << (log2_size - kTileLog2))), block(kThreads);
@@ -242,6 +272,8 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
         a.key0 = key0;
         a.key1 = key1;
         a.n = n;
+        a.valid = valid;
+        a.absmax = (a.last && !x) ? reinterpret_cast<uint32_t*>(absmax) : nullptr;
         if (a.last && x) {
             a.out = x;
             hipLaunchKernelGGL(high_pass_kernel<true>, grid, block, 0, stream, a);
@@ -250,6 +282,9 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+        // what is not zero afterwards: the blocks of 2^(s0 + m) floats that held a value
+        const uint64_t block = 1ull << (s0 + m);
+        valid = (valid + block - 1) / block * block;
         s0 += m;
     }
     return hipSuccess;

@@ -163,7 +163,8 @@ hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32
 
 // ---- full rotation (thc_full.hip) -----------------------------------------------------
 hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
-                              uint32_t key0, uint32_t key1, hipStream_t stream);
+                              uint32_t key0, uint32_t key1, hipStream_t stream, uint64_t valid,
+                              float* absmax);
 hipError_t launch_full_absmax(const float* y, uint32_t log2_size, float* absmax, hipStream_t stream);
 hipError_t launch_full_encode(const float* y, uint32_t log2_size, const float* scale, uint32_t levels,
                               uint32_t bits, uint32_t worker, uint32_t key0, uint32_t key1,

@@ -66,15 +66,19 @@ def _full_pipeline(l, n, W, bits, dtype, magnitude=1.0):
     xs = [(_rand(n, torch.float32, 100 * l + w, scale=10.0 ** (-1 - (w % 3))) * magnitude).to(dtype) for w in range(W)]
     absmax = torch.empty(W, device=DEV)
     scale = torch.empty(1, device=DEV)
-    ys = [torch.empty(size, device=DEV) for _ in range(W)]
+    ys = [torch.full((size,), float("nan"), device=DEV) for _ in range(W)]   # the padding is not pre-zeroed
     nb = size * bits // 8
     payloads = [torch.full((nb,), 0xAA, dtype=torch.uint8, device=DEV) for _ in range(W)]
     sb = thc.thc_sum_bytes(W, bits)
     sums = torch.empty(size, dtype=torch.uint8 if sb == 1 else torch.int16, device=DEV)
     out = torch.empty(n, device=DEV)
     for w in range(W):
-        thc.rht_forward_full(xs[w], l, 9, ys[w])
-        thc.thc_full_absmax(ys[w], l, absmax[w:w + 1])
+        if w % 2 == 0:                     # both forms: rotation and range in one call, or in two
+            absmax[w] = float("nan")
+            thc.rht_forward_full_absmax(xs[w], l, 9, ys[w], absmax[w:w + 1])
+        else:
+            thc.rht_forward_full(xs[w], l, 9, ys[w])
+            thc.thc_full_absmax(ys[w], l, absmax[w:w + 1])
     thc.thc_scale_reduce(absmax, W, 1, scale)
     for w in range(W):
         thc.thc_full_encode(ys[w], l, 9, w, bits, scale, payloads[w])
