@@ -353,7 +353,7 @@ def probe(torch, path, dev):
             fn(it)
         dst.copy_(src)
     torch.cuda.synchronize()
-    print(json.dumps({"probe": "ok", "bucket_elems": it["ln"], "copy_bytes": PROBE_COPY_BYTES}))
+    print(json.dumps({"probe": "ok", "bucket_elems": it["ln"] if it else None, "copy_bytes": PROBE_COPY_BYTES}))
 
 
 def vnmse(torch, path, it):
