@@ -488,7 +488,7 @@ def topkc_bench(thc, torch, wl, xs, dev, a):
                    "bits_per_coordinate": round(16.0 * (J * C / n + 1.0 / C), 4)},
         "roofline": {"bound": "hbm", "kernel": "topkc_chunk_norms", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None},
+                     "traffic": read_traffic(wl.name, "f16", "topkc_chunk_norms") if (C, W) == (64, 8) else None},
         "pipeline_hbm": {"algorithmic_bytes_per_coord": round(alg, 3),
                          "achieved_GBps": round(n * alg / (ms * 1e-3) / 1e9, 1),
                          "frac_of_peak": round(n * alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
