@@ -192,7 +192,7 @@ class FullPath:
         self.fused, self.sat = False, False
         self.phases = {"rht_forward_full_absmax": (self.rotate, self.W), "scale_reduce": (self.ranges, 1),
                        "full_encode": (self.encode, self.W), "aggregate": (self.aggregate, 1),
-                       "full_decode": (self.decode, 1), "rht_inverse_full": (self.inverse, 1)}
+                       "full_decode_inverse": (self.decode_inverse, 1)}
         self.dominant = "rht_forward_full_absmax"
         self.items = [None]
 
@@ -210,11 +210,9 @@ class FullPath:
     def aggregate(self, _=None):
         self.thc.thc_aggregate(self.payloads, self.size, 14, self.bits, self.sums)
 
-    def decode(self, _=None):
-        self.thc.thc_full_decode(self.sums, self.scale, self.W, self.l, self.bits, self.ys[0])
-
-    def inverse(self, _=None):
-        self.thc.rht_inverse_full(self.ys[0], self.n, self.l, 0, self.out)
+    def decode_inverse(self, _=None):
+        self.thc.thc_full_decode_inverse(self.sums, self.scale, self.W, self.n, self.l, 0, self.bits,
+                                         self.ys[0], self.out)
 
     def step(self):
         for fn, _ in self.phases.values():

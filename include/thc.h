@@ -397,7 +397,7 @@ int thc_aggregate_decode_minmax(const uint8_t* const* payloads, uint32_t W, cons
  *     rht_forward_full -> thc_full_absmax (or rht_forward_full_absmax for both)
  *     -> (thc_scale_reduce with chunks = 1)
  *     -> thc_full_encode -> thc_aggregate(n = 2^log2_size, chunk_log2 = 14)
- *     -> thc_full_decode -> rht_inverse_full
+ *     -> thc_full_decode -> rht_inverse_full (or thc_full_decode_inverse for both)
  * 15 <= log2_size <= 33 (THC_ERR_CHUNK otherwise), n <= 2^log2_size (THC_ERR_SIZE);
  * x, y, payload, sums and yhat must be 16-byte aligned. */
 
@@ -429,6 +429,13 @@ int thc_full_encode(const float* y, uint32_t log2_size, uint64_t seed, uint32_t 
  * thc_aggregate; feed yhat to rht_inverse_full. */
 int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t log2_size, uint32_t bits,
                     float* yhat, void* stream);
+
+/* thc_full_decode and rht_inverse_full in one call: the dequantization runs in front of
+ * stages 0..13, so yhat is never stored (same results, bit for bit).
+ *   work   2^log2_size fp32 of scratch (garbage afterwards), 16-byte aligned
+ *   x      n fp32, 16-byte aligned: the estimate of the mean gradient */
+int thc_full_decode_inverse(const void* sums, const float* scale, uint32_t W, uint64_t n, uint32_t log2_size,
+                            uint64_t seed, uint32_t bits, float* work, float* x, void* stream);
 
 /* ---- TopK Chunked (TopKC), "Our proposed improvement: Chunks" of the paper's TopK case
  * study: the all-reduce-compatible sparsifier ------------------------------------------

@@ -133,6 +133,10 @@ _SIGNATURES = {
     "thc_full_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
                                        ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
                                        ctypes.c_void_p]),
+    "thc_full_decode_inverse": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                               ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                               ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p]),
     "thc_sat_max": (ctypes.c_uint32, [ctypes.c_uint32]),
     "thc_sat_encode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                       ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
@@ -517,6 +521,13 @@ def thc_full_decode(sums, scale, W, log2_size, bits, yhat, stream=None):
     _check(lib().thc_full_decode(_ptr(sums), _ptr(scale), W, log2_size, bits, _ptr(yhat),
                                  _stream(stream)), "thc_full_decode")
     return yhat
+
+
+def thc_full_decode_inverse(sums, scale, W, n, log2_size, seed, bits, work, x, stream=None):
+    """thc_full_decode + rht_inverse_full in one call; `work` is 2^log2_size fp32 of scratch."""
+    _check(lib().thc_full_decode_inverse(_ptr(sums), _ptr(scale), W, n, log2_size, seed, bits, _ptr(work),
+                                         _ptr(x), _stream(stream)), "thc_full_decode_inverse")
+    return x
 
 
 # -------------------------------------------------------------------- min/max range

@@ -866,6 +866,33 @@ int thc_full_decode(const void* sums, const float* scale, uint32_t W, uint32_t l
                                           yhat, static_cast<hipStream_t>(stream)));
 }
 
+int thc_full_decode_inverse(const void* sums, const float* scale, uint32_t W, uint64_t n, uint32_t log2_size,
+                            uint64_t seed, uint32_t bits, float* work, float* x, void* stream) {
+    int rc = check_full(n, log2_size);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    const uint32_t sum_bytes = thc_sum_bytes(W, bits);
+    if (sum_bytes == 0) return THC_ERR_WORKERS;
+    if (n == 0) return THC_OK;
+    if (!sums || !scale || !work || !x) return THC_ERR_NULL;
+    if (!aligned(sums, 16) || !aligned(scale, 4) || !aligned(work, 16) || !aligned(x, 16)) return THC_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint64_t total = 1ull << log2_size;
+    ChunkArgs a = base_args(total, 14, seed);
+    a.in = sums;
+    a.out = work;
+    a.scale_in = scale;
+    a.scale_shared = 1;
+    a.levels = thc::grid_levels(bits, false);
+    a.W = W;
+    a.bits = bits;
+    a.sum_bytes = sum_bytes;
+    a.inv_sqrt_c = 1.0f;
+    if (thc::launch_fast14(Mode::PlainDecode, a, st) != hipSuccess) return THC_ERR_HIP;
+    return finish(thc::launch_high_passes(work, log2_size, full_factor(log2_size), x, n, a.key0, a.key1, st,
+                                          total, nullptr));
+}
+
 // ----------------------------------------------------------------------------- TopKC
 static int check_topkc(uint64_t n, uint32_t C) {
     if (C < 8 || C > 512 || (C & (C - 1)) != 0) return THC_ERR_CHUNK;

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void inverse_kernel(const ChunkArgs a) {
         // symmetric grid: yhat = S q - s;  min/max grid: yhat = S q + lo
         const bool ranged = a.range_in != nullptr;
         const float lo = ranged ? a.range_in[2 * p] : 0.0f;
-        const float s = ranged ? -lo : a.scale_in[p];
+        const float s = ranged ? -lo : a.scale_in[a.scale_shared ? 0 : p];
         const float step = (ranged ? a.range_in[2 * p + 1] - lo : s + s) / (float)a.levels;
         const float q = step / (float)a.W;
         if constexpr (SRC == 3) {
@@ -211,7 +211,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool fast14_applicable(Mode mode, const ChunkArgs& a) {
     if (a.chunk_log2 != 14) return false;
     if ((a.padded >> 14) > 0x7FFFFFFFull) return false;
-    if (a.out_bf16 || mode == Mode::Plain) return false;
+    if (a.out_bf16 || mode == Mode::Plain || mode == Mode::PlainDecode) return false;
     // without the rotation: the range and the encoder on a given range have a tuned form
     if (a.no_rotate && !(mode == Mode::MinMax || (mode == Mode::Encode && a.range_in))) return false;
     return k14::aligned16(a.in) && k14::aligned16(a.out);
@@ -241,6 +241,12 @@ hipError_t launch_fast14(Mode mode, const ChunkArgs& a, hipStream_t stream) {
             return hipGetLastError();
         case Mode::Plain:
             hipLaunchKernelGGL((inverse_kernel<0, false>), grid, dim3(kThreads), 0, stream, a);
+            return hipGetLastError();
+        case Mode::PlainDecode:
+            if (a.sum_bytes == 1)
+                hipLaunchKernelGGL((inverse_kernel<1, false>), grid, dim3(kThreads), 0, stream, a);
+            else
+                hipLaunchKernelGGL((inverse_kernel<2, false>), grid, dim3(kThreads), 0, stream, a);
             return hipGetLastError();
         case Mode::Decode:
             if (a.sat)

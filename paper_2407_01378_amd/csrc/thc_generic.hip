@@ -485,6 +485,7 @@ hipError_t launch_generic(Mode mode, const ChunkArgs& a, hipStream_t stream) {
             hipLaunchKernelGGL(generic_kernel<Mode::MinMax>, grid, block, 0, stream, a);
             break;
         case Mode::Plain:
+        case Mode::PlainDecode:
             return hipErrorInvalidValue;   // only the tuned chunk-2^14 kernels implement it
     }
     return hipGetLastError();

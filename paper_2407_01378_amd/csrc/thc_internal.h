@@ -10,7 +10,8 @@ namespace thc {
 
 // Plain: unsigned, fp32 to fp32 chunk transform (first pass of the full inverse rotation).
 // MinMax: per-chunk (min, max) of the rotated values (the min/max-range variant).
-enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4, Plain = 5, MinMax = 6 };
+// PlainDecode: Plain with the dequantization of stored sums in front (one scale for all chunks).
+enum class Mode : int { Forward = 0, Absmax = 1, Encode = 2, Inverse = 3, Decode = 4, Plain = 5, MinMax = 6, PlainDecode = 7 };
 
 // Largest grid index of the two quantization grids: 2^bits points for exact sums,
 // 2^bits - 1 points (signed symmetric, centre M = 2^(bits-1) - 1) for saturating sums.
@@ -38,6 +39,7 @@ struct ChunkArgs {
     uint32_t no_rotate;     // 1: no sign diagonal, no butterflies, no normalisation
     uint32_t out_bf16;      // inverse / decode: 1 = output is bf16 (round to nearest even)
     float inv_sqrt_c;       // fp32 nearest of c^(-1/2)
+    uint32_t scale_shared;  // decode: 1 = scale_in is ONE float for all chunks (full rotation)
 };
 
 // Generic path: any chunk_log2 in [1, 14], any alignment the ABI allows.

@@ -86,7 +86,10 @@ def _full_pipeline(l, n, W, bits, dtype, magnitude=1.0):
     yhat = ys[0]
     thc.thc_full_decode(sums, scale, W, l, bits, yhat)
     thc.rht_inverse_full(yhat, n, l, 9, out)
+    out_one_call = torch.full((n,), float("nan"), device=DEV)      # the same two steps as one call
+    thc.thc_full_decode_inverse(sums, scale, W, n, l, 9, bits, ys[-1].fill_(float("nan")), out_one_call)
     torch.cuda.synchronize()
+    assert torch.equal(out, out_one_call)
 
     bf16 = dtype == torch.bfloat16
     ref = O.pipeline([to_numpy_bits(x) for x in xs], l, 9, bits, dtype=np.float32, bf16=bf16)
@@ -121,6 +124,16 @@ def test_full_rotation_argument_checks():
         thc.rht_forward_full(torch.empty((1 << 15) + 4, device=DEV), 15, 0, y)   # n > 2^l
     with pytest.raises(thc.ThcError):
         thc.rht_forward_full(x[1:], 15, 0, y)      # x not 16-byte aligned
+    sums = torch.empty(1 << 15, dtype=torch.uint8, device=DEV)
+    scale = torch.ones(1, device=DEV)
+    with pytest.raises(thc.ThcError):
+        thc.thc_full_decode_inverse(sums, scale, 3, 100, 15, 0, 4, y[1:], x)      # scratch not 16-byte aligned
+    with pytest.raises(thc.ThcError):
+        thc.thc_full_decode_inverse(sums, scale, 3, 100, 15, 0, 5, y, x)          # bits
+    with pytest.raises(thc.ThcError):
+        thc.thc_full_decode_inverse(sums, scale, 300, 100, 15, 0, 8, y, x)        # sums of 300 workers do not fit 16 bits
+    with pytest.raises(thc.ThcError):
+        thc.thc_full_decode_inverse(sums, scale, 3, (1 << 15) + 1, 15, 0, 4, y, x)   # n > 2^l
 
 
 def test_full_rotation_over_2_to_33_coordinates():
