@@ -190,22 +190,23 @@ class FullPath:
         self.sums = torch.empty(size, dtype=torch.uint8 if self.sum_bytes == 1 else torch.int16, device=dev)
         self.out = torch.empty(self.n, dtype=torch.float32, device=dev)
         self.fused, self.sat = False, False
-        self.phases = {"rht_forward_full_absmax": (self.rotate, self.W), "scale_reduce": (self.ranges, 1),
-                       "full_encode": (self.encode, self.W), "aggregate": (self.aggregate, 1),
+        self.phases = {"rht_forward_full_deferred": (self.rotate, self.W), "scale_reduce": (self.ranges, 1),
+                       "full_encode_deferred": (self.encode, self.W), "aggregate": (self.aggregate, 1),
                        "full_decode_inverse": (self.decode_inverse, 1)}
-        self.dominant = "rht_forward_full_absmax"
+        self.dominant = "rht_forward_full_deferred"
         self.items = [None]
 
     def rotate(self, _=None):
         for w in range(self.W):
-            self.thc.rht_forward_full_absmax(self.xs[w], self.l, 0, self.ys[w], self.absmax[w:w + 1])
+            self.thc.rht_forward_full_deferred(self.xs[w], self.l, 0, self.ys[w], self.absmax[w:w + 1])
 
     def ranges(self, _=None):
         self.thc.thc_scale_reduce(self.absmax, self.W, 1, self.scale)
 
     def encode(self, _=None):
         for w in range(self.W):
-            self.thc.thc_full_encode(self.ys[w], self.l, 0, w, self.bits, self.scale, self.payloads[w])
+            self.thc.thc_full_encode_deferred(self.ys[w], self.n, self.l, 0, w, self.bits, self.scale,
+                                              self.payloads[w])
 
     def aggregate(self, _=None):
         self.thc.thc_aggregate(self.payloads, self.size, 14, self.bits, self.sums)
@@ -621,11 +622,11 @@ def main():
     # encode step must read the gradient once and write its payload once.
     coords_per_launch = wl.n / nb
     if a.full_rotation:
-        # one rht_forward_full_absmax call: gradient in, rotated fp32 chunks out, then every
-        # high pass reads and writes the whole rotated array (the first one reads only the
-        # gradient's part: the zero padding behind it is implied, not stored)
-        # a pass reads the part that holds values and writes the blocks of 2^(s0 + m) floats
-        # those values reach; the last pass writes everything
+        # one rht_forward_full_deferred call: gradient in, rotated fp32 chunks out, then every
+        # high pass reads the part of the array that holds values (the zero padding behind the
+        # gradient is implied, not stored) and writes the blocks of 2^(s0 + m) floats those
+        # values reach; the last pass only reads: it is evaluated for the range, and again,
+        # for the payload, by thc_full_encode_deferred
         high = path.l - 14
         valid = ((wl.n + (1 << 14) - 1) >> 14) << 14
         dom_bytes = wl.n * s_in + valid * 4
@@ -634,9 +635,9 @@ def main():
             m = (path.l - s0 + (passes - p) - 1) // (passes - p)
             block = 1 << (s0 + m)
             reach = min(path.size, (valid + block - 1) // block * block)
-            dom_bytes += valid * 4 + (path.size if p + 1 == passes else reach) * 4
+            dom_bytes += valid * 4 + (0 if p + 1 == passes else reach) * 4
             valid, s0 = reach, s0 + m
-        dom_name = "rht_forward_full_absmax"
+        dom_name = "rht_forward_full_deferred"
     elif path.fused:
         dom_bytes = coords_per_launch * W * (s_in + bits / 8.0)
         dom_name = "thc_encode_all"

@@ -397,6 +397,7 @@ int thc_aggregate_decode_minmax(const uint8_t* const* payloads, uint32_t W, cons
  *     rht_forward_full -> thc_full_absmax (or rht_forward_full_absmax for both)
  *     -> (thc_scale_reduce with chunks = 1)
  *     -> thc_full_encode -> thc_aggregate(n = 2^log2_size, chunk_log2 = 14)
+ *        (or rht_forward_full_deferred -> thc_scale_reduce -> thc_full_encode_deferred)
  *     -> thc_full_decode -> rht_inverse_full (or thc_full_decode_inverse for both)
  * 15 <= log2_size <= 33 (THC_ERR_CHUNK otherwise), n <= 2^log2_size (THC_ERR_SIZE);
  * x, y, payload, sums and yhat must be 16-byte aligned. */
@@ -412,6 +413,19 @@ int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size
  * pass of its own over y); absmax: device, one float, 4-byte aligned. */
 int rht_forward_full_absmax(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
                             float* y, float* absmax, void* stream);
+
+/* The rotation put off until the scale is known, for a caller that only needs the payload:
+ * rht_forward_full_deferred runs every pass but the last in place in y and evaluates the
+ * last one for *absmax only (y then holds the data as the pass before the last wrote it, NOT
+ * the rotated values); after thc_scale_reduce over the workers' absmax,
+ * thc_full_encode_deferred runs the last pass again on that y (read only) and quantizes
+ * its results directly.  Same scale and payload bytes as rht_forward_full_absmax +
+ * thc_full_encode, with the rotated values never stored.  n and log2_size of the two calls
+ * must be the same. */
+int rht_forward_full_deferred(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                              float* y, float* absmax, void* stream);
+int thc_full_encode_deferred(const float* y, uint64_t n, uint32_t log2_size, uint64_t seed, uint32_t worker,
+                             uint32_t bits, const float* scale, uint8_t* payload, void* stream);
 
 /*   y   2^log2_size fp32 rotated values, USED AS SCRATCH (garbage afterwards);
  *   x   n fp32, receives D 2^(-l/2) H y */

@@ -123,6 +123,11 @@ _SIGNATURES = {
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
     "rht_forward_full_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
                                                ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "rht_forward_full_deferred": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+                                                 ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "thc_full_encode_deferred": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64,
+                                                ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_void_p]),
     "rht_inverse_full": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
     "thc_full_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p,
@@ -490,6 +495,21 @@ def rht_forward_full_absmax(x, log2_size, seed, y, absmax, stream=None):
     _check(lib().rht_forward_full_absmax(_ptr(x), _dtype_code(x), x.numel(), log2_size, seed, _ptr(y),
                                          _ptr(absmax), _stream(stream)), "rht_forward_full_absmax")
     return y
+
+
+def rht_forward_full_deferred(x, log2_size, seed, y, absmax, stream=None):
+    """Every pass but the last in y, the last one evaluated for absmax only."""
+    _flat(x), _flat(y, torch.float32), _flat(absmax, torch.float32)
+    _check(lib().rht_forward_full_deferred(_ptr(x), _dtype_code(x), x.numel(), log2_size, seed, _ptr(y),
+                                           _ptr(absmax), _stream(stream)), "rht_forward_full_deferred")
+    return y
+
+
+def thc_full_encode_deferred(y, n, log2_size, seed, worker, bits, scale, payload, stream=None):
+    """The last pass on the y of rht_forward_full_deferred, quantized into payload."""
+    _check(lib().thc_full_encode_deferred(_ptr(y), n, log2_size, seed, worker, bits, _ptr(scale), _ptr(payload),
+                                          _stream(stream)), "thc_full_encode_deferred")
+    return payload
 
 
 def rht_forward_full(x, log2_size, seed, y, stream=None):

@@ -786,7 +786,7 @@ uint32_t thc_full_log2(uint64_t n) {
 }
 
 static int forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
-                        float* y, float* absmax, void* stream) {
+                        float* y, float* absmax, void* stream, bool defer_last = false) {
     int rc = check_full(n, log2_size);
     if (rc == THC_OK) rc = check_dtype(dt);
     if (rc != THC_OK) return rc;
@@ -800,8 +800,10 @@ static int forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_s
     a.inv_sqrt_c = 1.0f;
     if (n != 0 && thc::launch_fast14(Mode::Forward, a, st) != hipSuccess) return THC_ERR_HIP;
     // (the zero padding behind the last chunk is not written: the first pass reads it as zero)
+    thc::FullDeferred d{};
+    d.kind = 1;
     return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), nullptr, 0, a.key0, a.key1, st,
-                                          a.padded, absmax));
+                                          a.padded, absmax, defer_last ? &d : nullptr));
 }
 
 int rht_forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
@@ -814,6 +816,33 @@ int rht_forward_full_absmax(const void* x, thc_dtype dt, uint64_t n, uint32_t lo
     if (!absmax) return THC_ERR_NULL;
     if (!aligned(absmax, 4)) return THC_ERR_ALIGN;
     return forward_full(x, dt, n, log2_size, seed, y, absmax, stream);
+}
+
+int rht_forward_full_deferred(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_size, uint64_t seed,
+                              float* y, float* absmax, void* stream) {
+    if (!absmax) return THC_ERR_NULL;
+    if (!aligned(absmax, 4)) return THC_ERR_ALIGN;
+    return forward_full(x, dt, n, log2_size, seed, y, absmax, stream, true);
+}
+
+int thc_full_encode_deferred(const float* y, uint64_t n, uint32_t log2_size, uint64_t seed, uint32_t worker,
+                             uint32_t bits, const float* scale, uint8_t* payload, void* stream) {
+    int rc = check_full(n, log2_size);
+    if (rc == THC_OK) rc = check_bits(bits);
+    if (rc != THC_OK) return rc;
+    if (!y || !scale || !payload) return THC_ERR_NULL;
+    if (!aligned(y, 16) || !aligned(scale, 4) || !aligned(payload, 16)) return THC_ERR_ALIGN;
+    thc::FullDeferred d{};
+    d.kind = 2;
+    d.scale = scale;
+    d.levels = thc::grid_levels(bits, false);
+    d.bits = bits;
+    d.worker = worker;
+    d.payload = payload;
+    // (the kernel only reads y; `valid` is what rht_forward_full_deferred left behind for this n)
+    return finish(thc::launch_high_passes(const_cast<float*>(y), log2_size, full_factor(log2_size), nullptr, 0,
+                                          (uint32_t)seed, (uint32_t)(seed >> 32), static_cast<hipStream_t>(stream),
+                                          padded_coords(n, 14), nullptr, &d));
 }
 
 int rht_inverse_full(float* y, uint64_t n, uint32_t log2_size, uint64_t seed, float* x, void* stream) {

@@ -39,7 +39,66 @@ struct HighPassArgs {
                         // last pass mixes it with everything)
     uint32_t* absmax;   // last forward pass: receives max |value written| by an unsigned atomic
                         // maximum (zeroed beforehand); may be null
+    // last forward pass evaluated for the quantizer instead of being stored (kEncode):
+    const float* scale; // one float, shared by all workers
+    uint32_t levels;    // largest grid index L
+    uint32_t worker;
+    uint8_t* payload;   // 2^l * bits / 8 bytes
 };
+
+// What a pass does with its results.
+constexpr int kInPlace = 0;    // written back to `data`
+constexpr int kToX = 1;        // inverse direction, last pass: sign diagonal, first n values to `out`
+constexpr int kRangeOnly = 2;  // forward direction, last pass: only their largest magnitude is kept
+constexpr int kEncode = 3;     // forward direction, last pass: quantized and packed, `data` untouched
+
+// Stochastic rounding of rotated values (already normalised) onto the grid of [-s, s]:
+// same arithmetic and random stream as the fused encoders.
+struct FullQuant {
+    float s, inv, half, off, Lf;
+};
+__device__ __forceinline__ FullQuant full_quant(float s, uint32_t levels) {
+    FullQuant q;
+    q.s = s;
+    const float two = s + s;
+    q.Lf = (float)levels;
+    const bool ranged = two >= kMinRange;
+    q.inv = ranged ? q.Lf / two : 0.0f;
+    const bool single = levels <= kSingleFmaMaxLevels;   // evaluation order by grid size
+    q.half = (single && ranged) ? 0.5f * q.Lf : 0.0f;   // an all-zero (or vanishingly small) vector gets index 0
+    q.off = single ? 0.0f : s;
+    return q;
+}
+// 16 consecutive coordinates (the ones of Philox block `blk` of the rounding stream) -> 2 * BITS payload bytes.
+template <int BITS>
+__device__ __forceinline__ void quantize_run(const float (&yv)[16], uint64_t blk, const FullQuant& q, uint32_t worker,
+                                             uint32_t key0, uint32_t key1, uint8_t* payload) {
+    const u32x4 rb = round_block(blk, worker, key0, key1);
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    // u = (r + 0.5) / 256 and L/2 + u are exact in fp32, so one multiply-add gives the same c = L/2 + u
+    // (or u alone on the large grids); t >= 0, so the conversion's truncation is the floor.
+    const float c0 = q.half + 0x1p-9f;
+    const uint32_t L = (uint32_t)q.Lf;
+    const bool offset_first = q.off != 0.0f;   // uniform: large grids take fma(y + s, inv, u)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const uint32_t r = (rb.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+        const float c = __builtin_fmaf((float)r, 0x1p-8f, c0);
+        const float y = offset_first ? yv[j] + q.off : yv[j];
+        const float tt = __builtin_fmaf(y, q.inv, c);   // small grids: fma(y, inv, L/2 + u)
+        const uint32_t idx = min((uint32_t)tt, L);
+        const int bit = j * BITS;
+        pk[bit >> 5] |= idx << (bit & 31);
+    }
+    uint8_t* dst = payload + blk * (2u * BITS);
+    if constexpr (BITS == 8) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    } else if constexpr (BITS == 4) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
+    } else {
+        *reinterpret_cast<uint32_t*>(dst) = pk[0];
+    }
+}
 
 __device__ __forceinline__ void row_butterflies(float (&v)[32], int bit, bool enabled) {
     if (!enabled) return;   // uniform over the grid
@@ -57,40 +116,61 @@ __device__ __forceinline__ void row_butterflies(float (&v)[32], int bit, bool en
     }
 }
 
-template <bool TO_X>
-__global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs a) {
-    __shared__ float4 xb[4096];
-    const uint32_t t = threadIdx.x, lane = t & 63u, w = t >> 6;
-    const uint32_t jq = lane & 7u, la = lane >> 3;
-    const uint32_t skip = 9u - a.m;
-    const uint32_t jb_bits = a.s0 - 5u - skip;                  // column blocks per 2^s0 run
-    const uint64_t tile = blockIdx.x;
-    const uint64_t jb = tile & ((1ull << jb_bits) - 1ull);
-    const uint64_t hi = tile >> jb_bits;
-    // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
-    // zero padding its results are zero too, and the next pass is told so instead of reading them
-    if ((hi << (a.s0 + a.m)) >= a.valid) return;
-    const uint64_t base = (hi << (a.s0 + a.m)) + (jb << (5u + skip));
-    auto offset = [&](uint32_t row) -> uint64_t {               // first float of (row, jq)
+// Where a thread's share of a tile lies.
+struct Tile {
+    uint64_t base;
+    uint32_t skip, s0;
+    uint32_t jq, la, w;   // lane & 7, lane >> 3, wave
+    __device__ __forceinline__ uint64_t row_start(uint32_t row) const {   // first float of a row
         const uint64_t k = row >> skip;
         const uint32_t jext = row & ((1u << skip) - 1u);
-        return base + (k << a.s0) + (uint64_t)(jext * 32u + 4u * jq);
-    };
+        return base + (k << s0) + (uint64_t)(jext * 32u);
+    }
+    __device__ __forceinline__ uint64_t offset(uint32_t row) const { return row_start(row) + 4u * jq; }
+};
+// `block` receives the first float of the 2^(s0 + m) block the tile belongs to.
+__device__ __forceinline__ Tile make_tile(const HighPassArgs& a, uint64_t tile, uint32_t t, uint64_t& block) {
+    Tile T;
+    T.skip = 9u - a.m;
+    T.s0 = a.s0;
+    const uint32_t lane = t & 63u;
+    T.jq = lane & 7u;
+    T.la = lane >> 3;
+    T.w = t >> 6;
+    const uint32_t jb_bits = a.s0 - 5u - T.skip;                  // column blocks per 2^s0 run
+    const uint64_t jb = tile & ((1ull << jb_bits) - 1ull);
+    const uint64_t hi = tile >> jb_bits;
+    block = hi << (a.s0 + a.m);
+    T.base = block + (jb << (5u + T.skip));
+    return T;
+}
 
-    float v[32];
-    // rows r + 8 la + 64 w
+// Rows r + 8 la + 64 w, r = 0..7, of the tile: 8 loads back to back.  (A load is unconditional,
+// from the array's start where the row lies in the implied padding; take_rows selects.)
+__device__ __forceinline__ void load_rows(const HighPassArgs& a, const Tile& T, float4 (&raw)[8], uint32_t& inside) {
+    inside = 0u;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        // (the load is unconditional, from the array's start where the row lies in the implied
-        // padding, so that the eight loads stay back to back; the select comes afterwards)
-        const uint64_t g = offset(r + 8u * la + 64u * w);   // a multiple of 4, as `valid` is
+        const uint64_t g = T.offset(r + 8u * T.la + 64u * T.w);   // a multiple of 4, as `valid` is
         const bool in = g < a.valid;
-        const float4 q = *reinterpret_cast<const float4*>(a.data + (in ? g : 0u));
-        v[4 * r] = in ? q.x : 0.0f;
-        v[4 * r + 1] = in ? q.y : 0.0f;
-        v[4 * r + 2] = in ? q.z : 0.0f;
-        v[4 * r + 3] = in ? q.w : 0.0f;
+        inside |= (in ? 1u : 0u) << r;
+        raw[r] = *reinterpret_cast<const float4*>(a.data + (in ? g : 0u));
     }
+}
+__device__ __forceinline__ void take_rows(const float4 (&raw)[8], uint32_t inside, float (&v)[32]) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const bool in = (inside >> r) & 1u;
+        v[4 * r] = in ? raw[r].x : 0.0f;
+        v[4 * r + 1] = in ? raw[r].y : 0.0f;
+        v[4 * r + 2] = in ? raw[r].z : 0.0f;
+        v[4 * r + 3] = in ? raw[r].w : 0.0f;
+    }
+}
+
+// The stages of the pass on one tile.  In: rows r + 8 la + 64 w; out: rows la + 8 w + 64 r.
+__device__ __forceinline__ void rotate_tile(const Tile& T, float (&v)[32], float4* xb) {
+    const uint32_t skip = T.skip, la = T.la, jq = T.jq, w = T.w;
 #pragma unroll
     for (int b = 0; b < 3; ++b) row_butterflies(v, b, (uint32_t)b >= skip);
 
@@ -126,18 +206,39 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
     }
 #pragma unroll
     for (int b = 0; b < 3; ++b) row_butterflies(v, b, (uint32_t)(6 + b) >= skip);
+}
+
+template <int KIND>
+__global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs a) {
+    constexpr bool TO_X = KIND == kToX;
+    __shared__ float4 xb[4096];
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    uint64_t block;
+    const Tile T = make_tile(a, blockIdx.x, t, block);
+    // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
+    // zero padding its results are zero too, and the next pass is told so instead of reading them
+    if (block >= a.valid) return;
+
+    float4 raw[8];
+    uint32_t inside;
+    load_rows(a, T, raw, inside);
+    float v[32];
+    take_rows(raw, inside, v);
+    rotate_tile(T, v, xb);
 
     float largest = 0.0f;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        const uint64_t g = offset(la + 8u * w + 64u * (uint32_t)r);
+        const uint64_t g = T.offset(T.la + 8u * T.w + 64u * (uint32_t)r);
         float o[4] = {v[4 * r], v[4 * r + 1], v[4 * r + 2], v[4 * r + 3]};
         if (a.last) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = o[e] * a.factor;
         }
         if (!TO_X) largest = fmaxf(fmaxf(largest, fmaxf(fabsf(o[0]), fabsf(o[1]))), fmaxf(fabsf(o[2]), fabsf(o[3])));
-        if constexpr (TO_X) {
+        if constexpr (KIND == kRangeOnly) {
+            (void)g;
+        } else if constexpr (TO_X) {
             if (g < a.n) {
                 const u32x4 sb = sign_block(g >> 7, a.key0, a.key1);
                 const uint32_t bits4 = sb.w[(g >> 5) & 3u] >> (g & 31u);   // g is a multiple of 4
@@ -164,6 +265,63 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
     }
 }
 
+// The last forward pass evaluated for the quantizer: the results of a tile are quantized and
+// packed instead of being stored (`data` is only read).  A workgroup takes two neighbouring
+// tiles; the second one's loads are in flight while the first one is quantized.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void encode_pass_kernel(const HighPassArgs a) {
+    __shared__ float4 xb[4096];
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    uint64_t block;
+    Tile T = make_tile(a, 2ull * blockIdx.x, t, block);
+    float4 raw[8];
+    uint32_t inside;
+    load_rows(a, T, raw, inside);
+    const FullQuant fq = full_quant(a.scale[0], a.levels);
+    float4* mine = xb + 512u * T.w;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        float v[32];
+        take_rows(raw, inside, v);
+        rotate_tile(T, v, xb);
+        // exchange 3, inside the wave: 4 lanes x 4 floats of a row -> 16 consecutive floats in one
+        // lane, the coordinates of one block of the rounding stream and 2 * BITS payload bytes.
+        __syncthreads();   // every wave has taken its share of exchange 2 out of this wave's units
+#pragma unroll
+        for (int r = 0; r < 8; ++r)   // unit (row of the wave, jq), row of the wave = la + 8 r
+            mine[((uint32_t)r * 8u + T.la) * 8u + T.jq] =
+                make_float4(v[4 * r] * a.factor, v[4 * r + 1] * a.factor, v[4 * r + 2] * a.factor, v[4 * r + 3] * a.factor);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const Tile now = T;
+        if (k == 0) {
+            T = make_tile(a, 2ull * blockIdx.x + 1ull, t, block);
+            load_rows(a, T, raw, inside);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t run = lane + 64u * (uint32_t)h;   // (row of the wave, half of the row), 0 .. 127
+            const uint32_t rho = run >> 1, half = run & 1u;
+            const uint64_t g = now.row_start((rho & 7u) + 8u * now.w + 64u * (rho >> 3)) + 16u * half;
+            float yv[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float4 q = mine[rho * 8u + 4u * half + (uint32_t)i];
+                yv[4 * i] = q.x;
+                yv[4 * i + 1] = q.y;
+                yv[4 * i + 2] = q.z;
+                yv[4 * i + 3] = q.w;
+            }
+            quantize_run<BITS>(yv, g >> 4, fq, a.worker, a.key0, a.key1, a.payload);
+        }
+        if (k == 0) {
+            // the second tile's values are first needed here, not where the scheduler would like them
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                asm volatile("" : "+v"(raw[r].x), "+v"(raw[r].y), "+v"(raw[r].z), "+v"(raw[r].w));
+        }
+    }
+}
+
 // ---- elementwise steps on rotated data ---------------------------------------------------
 // Largest |y| of the whole array into *absmax (zeroed beforehand): non-negative floats
 // order like their bit patterns, so an unsigned atomic max does it.
@@ -179,9 +337,8 @@ __global__ __launch_bounds__(256) void full_absmax_kernel(const float* y, uint64
     if ((threadIdx.x & 63u) == 0) atomicMax(absmax, __float_as_uint(m));
 }
 
-// Stochastic rounding of rotated values (already normalised) onto the grid of [-s, s]:
-// same arithmetic and random stream as the fused encoders.  One thread: 16 coordinates,
-// one Philox block, 2 * BITS payload bytes.
+// The quantizer on stored rotated values.  One thread: 16 coordinates, one Philox block,
+// 2 * BITS payload bytes.
 template <int BITS>
 __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64_t count, const float* scale,
                                                           uint32_t levels, uint32_t worker, uint32_t key0,
@@ -189,40 +346,17 @@ __global__ __launch_bounds__(256) void full_encode_kernel(const float* y, uint64
     const uint64_t blk = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t g0 = blk * 16u;
     if (g0 >= count) return;
-    const float s = scale[0];
-    const float two = s + s;
-    const float Lf = (float)levels;
-    const bool ranged = two >= kMinRange;
-    const float inv = ranged ? Lf / two : 0.0f;
-    const bool single = levels <= kSingleFmaMaxLevels;   // evaluation order by grid size
-    const float half = (single && ranged) ? 0.5f * Lf : 0.0f;   // an all-zero (or vanishingly small) vector gets index 0
-    const float off = single ? 0.0f : s;
-    const u32x4 rb = round_block(blk, worker, key0, key1);
-    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    const FullQuant fq = full_quant(scale[0], levels);
+    float yv[16];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const float4 q = *reinterpret_cast<const float4*>(y + g0 + 4 * k);
-        const float yv[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = 4 * k + e;
-            const uint32_t r = (rb.w[k] >> (8 * e)) & 0xFFu;
-            const float u = ((float)r + 0.5f) * (1.0f / 256.0f);
-            // small grids: fma(y, inv, L/2 + u); large grids: fma(y + s, inv, u)
-            const float tt = __builtin_fmaf(yv[e] + off, inv, half + u);
-            const uint32_t idx = (uint32_t)fminf(floorf(tt), Lf);
-            const int bit = j * BITS;
-            pk[bit >> 5] |= idx << (bit & 31);
-        }
+        yv[4 * k] = q.x;
+        yv[4 * k + 1] = q.y;
+        yv[4 * k + 2] = q.z;
+        yv[4 * k + 3] = q.w;
     }
-    uint8_t* dst = payload + blk * (2u * BITS);
-    if constexpr (BITS == 8) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-    } else if constexpr (BITS == 4) {
-        *reinterpret_cast<uint2*>(dst) = make_uint2(pk[0], pk[1]);
-    } else {
-        *reinterpret_cast<uint32_t*>(dst) = pk[0];
-    }
+    quantize_run<BITS>(yv, blk, fq, worker, key0, key1, payload);
 }
 
 // sums -> rotated-domain estimate of the mean: yhat = S * (step / W) - s.
@@ -247,10 +381,15 @@ __global__ __launch_bounds__(256) void full_decode_kernel(const SumT* sums, uint
 // diagonal and writes the first n coordinates to x instead.  Forward direction: only the
 // first `valid` floats of data have been written (the rest is the zero padding, which the
 // first pass supplies by itself), and `absmax`, if not null, receives the largest
-// magnitude of the result (the word is zeroed here first).
+// magnitude of the result (the word is zeroed here first).  `deferred`, forward direction:
+// kind 1 = the last pass only reports the range and leaves data as the pass before it wrote
+// it; kind 2 = only the last pass runs, on such data, and its results go through the
+// quantizer into deferred->payload.
 hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
                               uint32_t key0, uint32_t key1, hipStream_t stream, uint64_t valid,
-                              float* absmax) {
+                              float* absmax, const FullDeferred* deferred) {
+    const int kind = deferred ? deferred->kind : 0;
+    if ((kind != 0 && x) || (kind == 1 && !absmax) || kind < 0 || kind > 2) return hipErrorInvalidValue;
     if (absmax) {
         const hipError_t e = launch_zero_words(reinterpret_cast<uint32_t*>(absmax), 1, stream);
         if (e != hipSuccess) return e;
@@ -276,9 +415,23 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
         a.absmax = (a.last && !x) ? reinterpret_cast<uint32_t*>(absmax) : nullptr;
         if (a.last && x) {
             a.out = x;
-            hipLaunchKernelGGL(high_pass_kernel<true>, grid, block, 0, stream, a);
-        } else {
-            hipLaunchKernelGGL(high_pass_kernel<false>, grid, block, 0, stream, a);
+            hipLaunchKernelGGL(high_pass_kernel<kToX>, grid, block, 0, stream, a);
+        } else if (a.last && kind == 1) {
+            hipLaunchKernelGGL(high_pass_kernel<kRangeOnly>, grid, block, 0, stream, a);
+        } else if (a.last && kind == 2) {
+            a.scale = deferred->scale;
+            a.levels = deferred->levels;
+            a.worker = deferred->worker;
+            a.payload = deferred->payload;
+            const dim3 pairs(grid.x / 2u);   // at least two tiles: log2_size >= 15
+            if (deferred->bits == 2)
+                hipLaunchKernelGGL(encode_pass_kernel<2>, pairs, block, 0, stream, a);
+            else if (deferred->bits == 4)
+                hipLaunchKernelGGL(encode_pass_kernel<4>, pairs, block, 0, stream, a);
+            else
+                hipLaunchKernelGGL(encode_pass_kernel<8>, pairs, block, 0, stream, a);
+        } else if (kind != 2) {
+            hipLaunchKernelGGL(high_pass_kernel<kInPlace>, grid, block, 0, stream, a);
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -164,9 +164,17 @@ hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32
                                 unsigned long long* overflow, hipStream_t stream);
 
 // ---- full rotation (thc_full.hip) -----------------------------------------------------
+// The last forward pass put off until the shared scale is known: kind 1 = evaluate it for the
+// range only, kind 2 = run only it and quantize its results (kind 0 / null: store as usual).
+struct FullDeferred {
+    int kind;
+    const float* scale;
+    uint32_t levels, bits, worker;
+    uint8_t* payload;
+};
 hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
                               uint32_t key0, uint32_t key1, hipStream_t stream, uint64_t valid,
-                              float* absmax);
+                              float* absmax, const FullDeferred* deferred = nullptr);
 hipError_t launch_full_absmax(const float* y, uint32_t log2_size, float* absmax, hipStream_t stream);
 hipError_t launch_full_encode(const float* y, uint32_t log2_size, const float* scale, uint32_t levels,
                               uint32_t bits, uint32_t worker, uint32_t key0, uint32_t key1,

@@ -55,6 +55,7 @@ def test_full_rotation_forward_and_inverse(l, n, dtype):
 @pytest.mark.parametrize("l,n,W,bits,dtype", [
     (15, 30_000, 3, 4, torch.float32), (18, 200_001, 4, 4, torch.bfloat16),
     (21, 1_500_000, 2, 8, torch.bfloat16), (16, 1 << 16, 18, 4, torch.float32), (17, 99_999, 3, 2, torch.float32),
+    (20, 5_000, 2, 4, torch.float32), (22, 70_001, 3, 2, torch.bfloat16),   # mostly implied padding
 ])
 def test_full_rotation_pipeline_matches_oracle(l, n, W, bits, dtype):
     _full_pipeline(l, n, W, bits, dtype)
@@ -82,6 +83,16 @@ def _full_pipeline(l, n, W, bits, dtype, magnitude=1.0):
     thc.thc_scale_reduce(absmax, W, 1, scale)
     for w in range(W):
         thc.thc_full_encode(ys[w], l, 9, w, bits, scale, payloads[w])
+    # the deferred form: the last pass first evaluated for the range only, then again for the payload
+    work = torch.full((size,), float("nan"), device=DEV)
+    for w in range(W):
+        range_only = torch.full((1,), float("nan"), device=DEV)
+        thc.rht_forward_full_deferred(xs[w], l, 9, work, range_only)
+        payload = torch.full((nb,), 0x55, dtype=torch.uint8, device=DEV)
+        thc.thc_full_encode_deferred(work, n, l, 9, w, bits, scale, payload)
+        assert float(range_only[0]) == float(absmax[w]), f"range of worker {w}"
+        assert torch.equal(payload, payloads[w]), f"deferred payload {w}"
+    del work
     thc.thc_aggregate(payloads, size, 14, bits, sums)
     yhat = ys[0]
     thc.thc_full_decode(sums, scale, W, l, bits, yhat)
@@ -166,8 +177,21 @@ def test_full_rotation_over_2_to_33_coordinates():
     step = 1 << 28
     energy = sum(float((y[a:a + step].double() ** 2).sum()) for a in range(0, 1 << l, step))
     assert abs(energy - sum(v * v for v in vs)) <= 1e-5 * sum(v * v for v in vs)
+    scale = torch.empty(1, device=DEV)
+    thc.thc_full_absmax(y, l, scale)
+    stored = torch.empty((1 << l) // 2, dtype=torch.uint8, device=DEV)
+    thc.thc_full_encode(y, l, 9, 3, 4, scale, stored)
     back = torch.full((n,), float("nan"), device=DEV)
     thc.rht_inverse_full(y, n, l, 9, back)
     torch.cuda.synchronize()
     err2 = sum(float(((back[a:a + step] - x[a:a + step].float()).double() ** 2).sum()) for a in range(0, n, step))
     assert err2 ** 0.5 <= 1e-5 * sum(v * v for v in vs) ** 0.5
+    del back
+    # the deferred form at this size (y is scratch by now): same range, same payload bytes
+    range_only = torch.empty(1, device=DEV)
+    thc.rht_forward_full_deferred(x, l, 9, y, range_only)
+    deferred = torch.empty((1 << l) // 2, dtype=torch.uint8, device=DEV)
+    thc.thc_full_encode_deferred(y, n, l, 9, 3, 4, scale, deferred)
+    torch.cuda.synchronize()
+    assert float(range_only[0]) == float(scale[0]) > 0
+    assert all(torch.equal(stored[a:a + step], deferred[a:a + step]) for a in range(0, (1 << l) // 2, step))
