@@ -208,13 +208,15 @@ __device__ __forceinline__ void rotate_tile(const Tile& T, float (&v)[32], float
     for (int b = 0; b < 3; ++b) row_butterflies(v, b, (uint32_t)(6 + b) >= skip);
 }
 
+// A workgroup takes two neighbouring tiles (they lie in the same 2^(s0 + m) block); the second
+// one's loads are in flight while the first one is transformed and stored.
 template <int KIND>
-__global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void high_pass_kernel(const HighPassArgs a) {
     constexpr bool TO_X = KIND == kToX;
     __shared__ float4 xb[4096];
     const uint32_t t = threadIdx.x, lane = t & 63u;
     uint64_t block;
-    const Tile T = make_tile(a, blockIdx.x, t, block);
+    Tile T = make_tile(a, 2ull * blockIdx.x, t, block);
     // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
     // zero padding its results are zero too, and the next pass is told so instead of reading them
     if (block >= a.valid) return;
@@ -222,38 +224,53 @@ __global__ __launch_bounds__(kThreads) void high_pass_kernel(const HighPassArgs 
     float4 raw[8];
     uint32_t inside;
     load_rows(a, T, raw, inside);
-    float v[32];
-    take_rows(raw, inside, v);
-    rotate_tile(T, v, xb);
-
     float largest = 0.0f;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const uint64_t g = T.offset(T.la + 8u * T.w + 64u * (uint32_t)r);
-        float o[4] = {v[4 * r], v[4 * r + 1], v[4 * r + 2], v[4 * r + 3]};
-        if (a.last) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = o[e] * a.factor;
+    for (int k = 0; k < 2; ++k) {
+        float v[32];
+        take_rows(raw, inside, v);
+        const Tile now = T;
+        if (k == 0) {
+            T = make_tile(a, 2ull * blockIdx.x + 1ull, t, block);
+            load_rows(a, T, raw, inside);
         }
-        if (!TO_X) largest = fmaxf(fmaxf(largest, fmaxf(fabsf(o[0]), fabsf(o[1]))), fmaxf(fabsf(o[2]), fabsf(o[3])));
-        if constexpr (KIND == kRangeOnly) {
-            (void)g;
-        } else if constexpr (TO_X) {
-            if (g < a.n) {
-                const u32x4 sb = sign_block(g >> 7, a.key0, a.key1);
-                const uint32_t bits4 = sb.w[(g >> 5) & 3u] >> (g & 31u);   // g is a multiple of 4
+        rotate_tile(now, v, xb);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = flip_sign(o[e], (bits4 >> e) & 1u);
-                if (g + 4u <= a.n) {
-                    *reinterpret_cast<float4*>(a.out + g) = make_float4(o[0], o[1], o[2], o[3]);
-                } else {
+        for (int r = 0; r < 8; ++r) {
+            const uint64_t g = now.offset(now.la + 8u * now.w + 64u * (uint32_t)r);
+            float o[4] = {v[4 * r], v[4 * r + 1], v[4 * r + 2], v[4 * r + 3]};
+            if (a.last) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (g + e < a.n) a.out[g + e] = o[e];
-                }
+                for (int e = 0; e < 4; ++e) o[e] = o[e] * a.factor;
             }
-        } else {
-            *reinterpret_cast<float4*>(a.data + g) = make_float4(o[0], o[1], o[2], o[3]);
+            if (!TO_X) largest = fmaxf(fmaxf(largest, fmaxf(fabsf(o[0]), fabsf(o[1]))), fmaxf(fabsf(o[2]), fabsf(o[3])));
+            if constexpr (KIND == kRangeOnly) {
+                (void)g;
+            } else if constexpr (TO_X) {
+                if (g < a.n) {
+                    const u32x4 sb = sign_block(g >> 7, a.key0, a.key1);
+                    const uint32_t bits4 = sb.w[(g >> 5) & 3u] >> (g & 31u);   // g is a multiple of 4
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = flip_sign(o[e], (bits4 >> e) & 1u);
+                    if (g + 4u <= a.n) {
+                        *reinterpret_cast<float4*>(a.out + g) = make_float4(o[0], o[1], o[2], o[3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (g + e < a.n) a.out[g + e] = o[e];
+                    }
+                }
+            } else {
+                *reinterpret_cast<float4*>(a.data + g) = make_float4(o[0], o[1], o[2], o[3]);
+            }
+        }
+        if (k == 0) {
+            // the second tile's values are first needed here, not where the scheduler would like them;
+            // its first exchange must not overwrite units another wave is still reading
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                asm volatile("" : "+v"(raw[r].x), "+v"(raw[r].y), "+v"(raw[r].z), "+v"(raw[r].w));
+            __syncthreads();
         }
     }
     if (!TO_X && a.absmax) {   // (uniform over the grid) non-negative floats order like their bit patterns
@@ -396,7 +413,7 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
     }
     const uint32_t high = log2_size - kTileLog2;
     const uint32_t passes = (high + 8u) / 9u;
-    const dim3 grid((uint32_t)(1ull << (log2_size - kTileLog2))), block(kThreads);
+    const dim3 grid((uint32_t)(1ull << (log2_size - kTileLog2 - 1u))), block(kThreads);   // tile pairs (log2_size >= 15)
     uint32_t s0 = kTileLog2;
     for (uint32_t p = 0; p < passes; ++p) {
         const uint32_t left = log2_size - s0;
@@ -423,13 +440,12 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
             a.levels = deferred->levels;
             a.worker = deferred->worker;
             a.payload = deferred->payload;
-            const dim3 pairs(grid.x / 2u);   // at least two tiles: log2_size >= 15
             if (deferred->bits == 2)
-                hipLaunchKernelGGL(encode_pass_kernel<2>, pairs, block, 0, stream, a);
+                hipLaunchKernelGGL(encode_pass_kernel<2>, grid, block, 0, stream, a);
             else if (deferred->bits == 4)
-                hipLaunchKernelGGL(encode_pass_kernel<4>, pairs, block, 0, stream, a);
+                hipLaunchKernelGGL(encode_pass_kernel<4>, grid, block, 0, stream, a);
             else
-                hipLaunchKernelGGL(encode_pass_kernel<8>, pairs, block, 0, stream, a);
+                hipLaunchKernelGGL(encode_pass_kernel<8>, grid, block, 0, stream, a);
         } else if (kind != 2) {
             hipLaunchKernelGGL(high_pass_kernel<kInPlace>, grid, block, 0, stream, a);
         }
