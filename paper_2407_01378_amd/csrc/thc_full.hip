@@ -6,8 +6,10 @@
 //   stages 0..13    the chunk-2^14 kernels (thc_fast14.hip), data in registers and LDS
 //   stages 14..l-1  "high passes" over the fp32 array in global memory, up to 9 stages per
 //                   pass (this file), in place
-// plus the elementwise steps of the quantizer on rotated data (range, encode, decode),
-// which the partial-rotation path fuses into its rotation kernels.
+// plus the steps of the quantizer on rotated data, which the partial-rotation path fuses into
+// its rotation kernels: as elementwise kernels on stored values (range, encode, decode), and
+// as variants of the last forward pass that keep only the range of its results, or quantize
+// them once the shared scale is known, so that the rotated values are never stored.
 #include "thc_device.h"
 #include "thc_internal.h"
 
@@ -39,7 +41,7 @@ struct HighPassArgs {
                         // last pass mixes it with everything)
     uint32_t* absmax;   // last forward pass: receives max |value written| by an unsigned atomic
                         // maximum (zeroed beforehand); may be null
-    // last forward pass evaluated for the quantizer instead of being stored (kEncode):
+    // last forward pass evaluated for the quantizer instead of being stored (encode_pass_kernel):
     const float* scale; // one float, shared by all workers
     uint32_t levels;    // largest grid index L
     uint32_t worker;
@@ -50,7 +52,6 @@ struct HighPassArgs {
 constexpr int kInPlace = 0;    // written back to `data`
 constexpr int kToX = 1;        // inverse direction, last pass: sign diagonal, first n values to `out`
 constexpr int kRangeOnly = 2;  // forward direction, last pass: only their largest magnitude is kept
-constexpr int kEncode = 3;     // forward direction, last pass: quantized and packed, `data` untouched
 
 // Stochastic rounding of rotated values (already normalised) onto the grid of [-s, s]:
 // same arithmetic and random stream as the fused encoders.
