@@ -220,7 +220,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     Tile T = make_tile(a, 2ull * blockIdx.x, t, block);
     // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
     // zero padding its results are zero too, and the next pass is told so instead of reading them
-    if (block >= a.valid) return;
+    // (the last pass writes everything: an empty gradient gives zeros)
+    if (!a.last && block >= a.valid) return;
 
     float4 raw[8];
     uint32_t inside;

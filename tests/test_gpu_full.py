@@ -126,6 +126,22 @@ def test_full_rotation_of_a_vanishingly_small_gradient(l, n, W, bits, dtype):
     assert all(int(p.max()) == 0 for p in payloads)
 
 
+def test_full_rotation_of_an_empty_gradient():
+    """n = 0: the rotated vector is all zeros, its range 0, its payload all index 0."""
+    l = 16
+    x = torch.empty(0, device=DEV)
+    y = torch.full((1 << l,), float("nan"), device=DEV)
+    absmax = torch.full((2,), float("nan"), device=DEV)
+    thc.rht_forward_full_absmax(x, l, 3, y, absmax[0:1])
+    assert float(y.abs().max()) == 0.0 and float(absmax[0]) == 0.0
+    work = torch.full((1 << l,), float("nan"), device=DEV)
+    thc.rht_forward_full_deferred(x, l, 3, work, absmax[1:2])
+    assert float(absmax[1]) == 0.0
+    payload = torch.full(((1 << l) // 2,), 0xAA, dtype=torch.uint8, device=DEV)
+    thc.thc_full_encode_deferred(work, 0, l, 3, 0, 4, absmax[1:2], payload)
+    assert int(payload.max()) == 0
+
+
 def test_full_rotation_argument_checks():
     y = torch.empty(1 << 15, device=DEV)
     x = torch.empty(100, device=DEV)
