@@ -126,6 +126,23 @@ def test_full_rotation_of_a_vanishingly_small_gradient(l, n, W, bits, dtype):
     assert all(int(p.max()) == 0 for p in payloads)
 
 
+def test_full_rotation_randomized_shapes_and_magnitudes():
+    """Fixed-seed random cases: sizes from a handful of coordinates to a full power of two
+    (so from almost all padding to none), 1 to 18 workers, every payload width, magnitudes
+    from below the smallest range the quantizer accepts to 2^80; both forms of every step."""
+    import random
+    rnd = random.Random(11)
+    for _ in range(30):
+        l = rnd.choice([15, 15, 16, 17, 18, 19, 20, 21, 23, 24])
+        n = rnd.choice([rnd.randint((1 << (l - 1)) + 1, 1 << l), rnd.randint(1, 1 << l), min(1 << l, rnd.randint(1, 70000))])
+        W = rnd.choice([1, 2, 3, 8, 18]) if l < 21 else rnd.choice([1, 2, 3])
+        bits = rnd.choice([2, 4, 8])
+        dtype = rnd.choice([torch.float32, torch.bfloat16])
+        magnitude = rnd.choice([2.0 ** -128, 2.0 ** -117, 1e-20, 1.0, 1.0, 2.0 ** 80])
+        with np.errstate(all="ignore"):
+            _full_pipeline(l, n, W, bits, dtype, magnitude=magnitude)
+
+
 def test_full_rotation_of_an_empty_gradient():
     """n = 0: the rotated vector is all zeros, its range 0, its payload all index 0."""
     l = 16
