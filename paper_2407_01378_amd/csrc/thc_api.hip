@@ -801,7 +801,7 @@ static int forward_full(const void* x, thc_dtype dt, uint64_t n, uint32_t log2_s
     if (n != 0 && thc::launch_fast14(Mode::Forward, a, st) != hipSuccess) return THC_ERR_HIP;
     // (the zero padding behind the last chunk is not written: the first pass reads it as zero)
     thc::FullDeferred d{};
-    d.kind = 1;
+    d.kind = thc::FullLast::RangeOnly;
     return finish(thc::launch_high_passes(y, log2_size, full_factor(log2_size), nullptr, 0, a.key0, a.key1, st,
                                           a.padded, absmax, defer_last ? &d : nullptr));
 }
@@ -833,7 +833,7 @@ int thc_full_encode_deferred(const float* y, uint64_t n, uint32_t log2_size, uin
     if (!y || !scale || !payload) return THC_ERR_NULL;
     if (!aligned(y, 16) || !aligned(scale, 4) || !aligned(payload, 16)) return THC_ERR_ALIGN;
     thc::FullDeferred d{};
-    d.kind = 2;
+    d.kind = thc::FullLast::EncodeOnly;
     d.scale = scale;
     d.levels = thc::grid_levels(bits, false);
     d.bits = bits;

@@ -401,14 +401,15 @@ __global__ __launch_bounds__(256) void full_decode_kernel(const SumT* sums, uint
 // first `valid` floats of data have been written (the rest is the zero padding, which the
 // first pass supplies by itself), and `absmax`, if not null, receives the largest
 // magnitude of the result (the word is zeroed here first).  `deferred`, forward direction:
-// kind 1 = the last pass only reports the range and leaves data as the pass before it wrote
-// it; kind 2 = only the last pass runs, on such data, and its results go through the
+// RangeOnly = the last pass only reports the range and leaves data as the pass before it wrote
+// it; EncodeOnly = only the last pass runs, on such data, and its results go through the
 // quantizer into deferred->payload.
 hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, float* x, uint64_t n,
                               uint32_t key0, uint32_t key1, hipStream_t stream, uint64_t valid,
                               float* absmax, const FullDeferred* deferred) {
-    const int kind = deferred ? deferred->kind : 0;
-    if ((kind != 0 && x) || (kind == 1 && !absmax) || kind < 0 || kind > 2) return hipErrorInvalidValue;
+    const bool range_only = deferred && deferred->kind == FullLast::RangeOnly;
+    const bool encode_only = deferred && deferred->kind == FullLast::EncodeOnly;
+    if ((deferred && (x || range_only == encode_only)) || (range_only && !absmax)) return hipErrorInvalidValue;
     if (absmax) {
         const hipError_t e = launch_zero_words(reinterpret_cast<uint32_t*>(absmax), 1, stream);
         if (e != hipSuccess) return e;
@@ -435,9 +436,9 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
         if (a.last && x) {
             a.out = x;
             hipLaunchKernelGGL(high_pass_kernel<kToX>, grid, block, 0, stream, a);
-        } else if (a.last && kind == 1) {
+        } else if (a.last && range_only) {
             hipLaunchKernelGGL(high_pass_kernel<kRangeOnly>, grid, block, 0, stream, a);
-        } else if (a.last && kind == 2) {
+        } else if (a.last && encode_only) {
             a.scale = deferred->scale;
             a.levels = deferred->levels;
             a.worker = deferred->worker;
@@ -448,7 +449,7 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
                 hipLaunchKernelGGL(encode_pass_kernel<4>, grid, block, 0, stream, a);
             else
                 hipLaunchKernelGGL(encode_pass_kernel<8>, grid, block, 0, stream, a);
-        } else if (kind != 2) {
+        } else if (!encode_only) {
             hipLaunchKernelGGL(high_pass_kernel<kInPlace>, grid, block, 0, stream, a);
         }
         const hipError_t e = hipGetLastError();

@@ -164,10 +164,12 @@ hipError_t launch_sat_aggregate(const FusedPayloadPtrs& ptrs, uint32_t W, uint32
                                 unsigned long long* overflow, hipStream_t stream);
 
 // ---- full rotation (thc_full.hip) -----------------------------------------------------
-// The last forward pass put off until the shared scale is known: kind 1 = evaluate it for the
-// range only, kind 2 = run only it and quantize its results (kind 0 / null: store as usual).
+// The last forward pass put off until the shared scale is known: evaluated for the range only
+// (every earlier pass runs as usual), or run on its own with its results quantized instead of
+// stored.  (No FullDeferred at all: every pass runs and stores.)
+enum class FullLast : int { RangeOnly = 1, EncodeOnly = 2 };
 struct FullDeferred {
-    int kind;
+    FullLast kind;
     const float* scale;
     uint32_t levels, bits, worker;
     uint8_t* payload;
