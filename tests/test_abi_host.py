@@ -282,6 +282,60 @@ def test_one_pass_minmax_entry_points_validate_on_the_host(L):
     assert dec(pg, 4, p, 100, 14, 0, 4, 0, ctypes.c_void_p(0x1004), nul) == -8
 
 
+def test_full_rotation_entry_points_validate_on_the_host(L):
+    """Every call fails validation before anything is enqueued (dummy addresses)."""
+    p = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)      # 4-byte aligned only
+    nul = ctypes.c_void_p(0)
+    F32 = thc.THC_F32
+    assert thc.thc_full_log2(1) == 15 and thc.thc_full_log2((1 << 15) + 1) == 16
+    assert thc.thc_full_log2(1 << 33) == 33 and thc.thc_full_log2((1 << 33) + 1) == 0
+    for l in (0, 14, 34):               # log2_size out of range
+        assert L.rht_forward_full(p, F32, 10, l, 0, p, nul) == -3
+        assert L.rht_forward_full_absmax(p, F32, 10, l, 0, p, p, nul) == -3
+        assert L.rht_forward_full_deferred(p, F32, 10, l, 0, p, p, nul) == -3
+        assert L.rht_inverse_full(p, 10, l, 0, p, nul) == -3
+        assert L.thc_full_absmax(p, l, p, nul) == -3
+        assert L.thc_full_encode(p, l, 0, 0, 4, p, p, nul) == -3
+        assert L.thc_full_encode_deferred(p, 10, l, 0, 0, 4, p, p, nul) == -3
+        assert L.thc_full_decode(p, p, 4, l, 4, p, nul) == -3
+        assert L.thc_full_decode_inverse(p, p, 4, 10, l, 0, 4, p, p, nul) == -3
+    too_many = (1 << 15) + 1            # n > 2^log2_size
+    assert L.rht_forward_full(p, F32, too_many, 15, 0, p, nul) == -6
+    assert L.rht_forward_full_deferred(p, F32, too_many, 15, 0, p, p, nul) == -6
+    assert L.rht_inverse_full(p, too_many, 15, 0, p, nul) == -6
+    assert L.thc_full_encode_deferred(p, too_many, 15, 0, 0, 4, p, p, nul) == -6
+    assert L.thc_full_decode_inverse(p, p, 4, too_many, 15, 0, 4, p, p, nul) == -6
+    assert L.rht_forward_full(p, 9, 10, 15, 0, p, nul) == -5                     # dtype
+    for bad in (0, 3, 16):                                                       # bits
+        assert L.thc_full_encode(p, 15, 0, 0, bad, p, p, nul) == -2
+        assert L.thc_full_encode_deferred(p, 10, 15, 0, 0, bad, p, p, nul) == -2
+        assert L.thc_full_decode(p, p, 4, 15, bad, p, nul) == -2
+        assert L.thc_full_decode_inverse(p, p, 4, 10, 15, 0, bad, p, p, nul) == -2
+    assert L.thc_full_decode(p, p, 0, 15, 4, p, nul) == -4                       # workers
+    assert L.thc_full_decode_inverse(p, p, 300, 10, 15, 0, 8, p, p, nul) == -4
+    # null pointers
+    assert L.rht_forward_full(p, F32, 10, 15, 0, nul, nul) == -1
+    assert L.rht_forward_full(nul, F32, 10, 15, 0, p, nul) == -1
+    assert L.rht_forward_full_absmax(p, F32, 10, 15, 0, p, nul, nul) == -1
+    assert L.rht_forward_full_deferred(p, F32, 10, 15, 0, p, nul, nul) == -1
+    assert L.rht_inverse_full(nul, 10, 15, 0, p, nul) == -1
+    assert L.thc_full_encode(p, 15, 0, 0, 4, nul, p, nul) == -1
+    assert L.thc_full_encode_deferred(p, 10, 15, 0, 0, 4, p, nul, nul) == -1
+    assert L.thc_full_decode_inverse(p, p, 4, 10, 15, 0, 4, nul, p, nul) == -1
+    # alignment: the arrays need 16 bytes
+    assert L.rht_forward_full(p, F32, 10, 15, 0, odd, nul) == -8
+    assert L.rht_forward_full_deferred(odd, F32, 10, 15, 0, p, p, nul) == -8
+    assert L.rht_inverse_full(p, 10, 15, 0, odd, nul) == -8
+    assert L.thc_full_encode(odd, 15, 0, 0, 4, p, p, nul) == -8
+    assert L.thc_full_encode_deferred(p, 10, 15, 0, 0, 4, p, odd, nul) == -8
+    assert L.thc_full_decode_inverse(p, p, 4, 10, 15, 0, 4, odd, p, nul) == -8
+    assert L.thc_full_decode_inverse(p, p, 4, 10, 15, 0, 4, p, odd, nul) == -8
+    # nothing to do
+    assert L.rht_inverse_full(nul, 0, 15, 0, nul, nul) == 0
+    assert L.thc_full_decode_inverse(nul, nul, 4, 0, 15, 0, 4, nul, nul, nul) == 0
+
+
 def test_header_is_plain_c(tmp_path):
     """include/thc.h is a C header: it compiles as C99 with pedantic warnings as errors, and
     as C++ (the library's own translation units include it that way)."""
