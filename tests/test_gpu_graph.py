@@ -150,3 +150,47 @@ def test_graph_replays_of_the_other_one_launch_forms(form):
             for a, b in zip(pay[k], ref_pay):
                 assert torch.equal(a, b)
             assert torch.equal(out[k], ref_out)
+
+
+def test_graph_replays_of_the_full_rotation_step():
+    """The full-rotation step in its deferred form (the range word is cleared by a kernel, the
+    absmax atomics start from that word) under capture: every replay against eager calls."""
+    l, bits, W = 17, 4, 3
+    n, size = 100_001, 1 << 17
+    xs = [_rand(n, 7 + w) for w in range(W)]
+    work = [torch.empty(size, device=DEV) for _ in range(W)]
+    absmax = torch.empty(W, device=DEV)
+    scale = torch.empty(1, device=DEV)
+    pay = [torch.empty(size * bits // 8, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    sums = torch.empty(size, dtype=torch.uint8, device=DEV)
+    out = torch.empty(n, device=DEV)
+
+    def run(work, absmax, scale, pay, sums, out):
+        for w in range(W):
+            thc.rht_forward_full_deferred(xs[w], l, 5, work[w], absmax[w:w + 1])
+        thc.thc_scale_reduce(absmax, W, 1, scale)
+        for w in range(W):
+            thc.thc_full_encode_deferred(work[w], n, l, 5, w, bits, scale, pay[w])
+        thc.thc_aggregate(pay, size, 14, bits, sums)
+        thc.thc_full_decode_inverse(sums, scale, W, n, l, 5, bits, work[0], out)
+
+    graph = _capture(lambda: run(work, absmax, scale, pay, sums, out))
+    ref = dict(work=[torch.empty_like(t) for t in work], absmax=torch.empty_like(absmax), scale=torch.empty_like(scale),
+               pay=[torch.empty_like(p) for p in pay], sums=torch.empty_like(sums), out=torch.empty_like(out))
+    for rep in range(3):
+        print(f"graph replay {rep} full rotation", flush=True)
+        for w in range(W):                   # new inputs in the recorded buffers
+            xs[w].copy_(_rand(n, 100 * rep + w) * (10.0 ** rep))
+        for p in pay:
+            p.fill_(0xEE)
+        out.fill_(float("nan"))
+        absmax.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        run(**ref)                           # eager, between replays
+        torch.cuda.synchronize()
+        assert torch.equal(scale, ref["scale"]) and float(scale[0]) > 0
+        for a, b in zip(pay, ref["pay"]):
+            assert torch.equal(a, b)
+        assert torch.equal(out, ref["out"])
