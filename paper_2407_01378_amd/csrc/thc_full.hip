@@ -32,7 +32,7 @@ struct HighPassArgs {
     float* out;         // last pass of the inverse: x (n floats); else null
     uint64_t n;         // coordinates to write to `out`
     uint32_t s0, m;
-    uint32_t last;      // 1: multiply by `factor`
+    uint32_t last;      // host side: the pass that multiplies by `factor` (a template argument of the kernels)
     float factor;
     uint32_t key0, key1;
     uint64_t valid;     // floats of `data` that hold values; what lies beyond reads as zero and
@@ -80,16 +80,20 @@ __device__ __forceinline__ void quantize_run(const float (&yv)[16], uint64_t blk
     // (or u alone on the large grids); t >= 0, so the conversion's truncation is the floor.
     const float c0 = q.half + 0x1p-9f;
     const uint32_t L = (uint32_t)q.Lf;
-    const bool offset_first = q.off != 0.0f;   // uniform: large grids take fma(y + s, inv, u)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
+    auto place = [&](int j, float y) {
         const uint32_t r = (rb.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
         const float c = __builtin_fmaf((float)r, 0x1p-8f, c0);
-        const float y = offset_first ? yv[j] + q.off : yv[j];
-        const float tt = __builtin_fmaf(y, q.inv, c);   // small grids: fma(y, inv, L/2 + u)
+        const float tt = __builtin_fmaf(y, q.inv, c);
         const uint32_t idx = min((uint32_t)tt, L);
         const int bit = j * BITS;
         pk[bit >> 5] |= idx << (bit & 31);
+    };
+    if (q.off != 0.0f) {   // (uniform) large grids: fma(y + s, inv, u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) place(j, yv[j] + q.off);
+    } else {               // small grids: fma(y, inv, L/2 + u)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) place(j, yv[j]);
     }
     uint8_t* dst = payload + blk * (2u * BITS);
     if constexpr (BITS == 8) {
@@ -130,9 +134,10 @@ struct Tile {
     __device__ __forceinline__ uint64_t offset(uint32_t row) const { return row_start(row) + 4u * jq; }
 };
 // `block` receives the first float of the 2^(s0 + m) block the tile belongs to.
+template <int SKIP>
 __device__ __forceinline__ Tile make_tile(const HighPassArgs& a, uint64_t tile, uint32_t t, uint64_t& block) {
     Tile T;
-    T.skip = 9u - a.m;
+    T.skip = (uint32_t)SKIP;   // = 9 - a.m, a constant of the kernel so that the stage loops are straight-line code
     T.s0 = a.s0;
     const uint32_t lane = t & 63u;
     T.jq = lane & 7u;
@@ -146,26 +151,26 @@ __device__ __forceinline__ Tile make_tile(const HighPassArgs& a, uint64_t tile, 
     return T;
 }
 
-// Rows r + 8 la + 64 w, r = 0..7, of the tile: 8 loads back to back.  (A load is unconditional,
-// from the array's start where the row lies in the implied padding; take_rows selects.)
-__device__ __forceinline__ void load_rows(const HighPassArgs& a, const Tile& T, float4 (&raw)[8], uint32_t& inside) {
-    inside = 0u;
+// Sixteen bytes of zeros: where rows in the implied padding are read from.
+__device__ const float4 kZeroRow = {0.0f, 0.0f, 0.0f, 0.0f};
+
+// Rows r + 8 la + 64 w, r = 0..7, of the tile: 8 loads back to back.  (A row in the implied
+// padding is loaded from kZeroRow instead: a select of the address, none of the values.)
+__device__ __forceinline__ void load_rows(const HighPassArgs& a, const Tile& T, float4 (&raw)[8]) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const uint64_t g = T.offset(r + 8u * T.la + 64u * T.w);   // a multiple of 4, as `valid` is
-        const bool in = g < a.valid;
-        inside |= (in ? 1u : 0u) << r;
-        raw[r] = *reinterpret_cast<const float4*>(a.data + (in ? g : 0u));
+        const float4* src = g < a.valid ? reinterpret_cast<const float4*>(a.data + g) : &kZeroRow;
+        raw[r] = *src;
     }
 }
-__device__ __forceinline__ void take_rows(const float4 (&raw)[8], uint32_t inside, float (&v)[32]) {
+__device__ __forceinline__ void take_rows(const float4 (&raw)[8], float (&v)[32]) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        const bool in = (inside >> r) & 1u;
-        v[4 * r] = in ? raw[r].x : 0.0f;
-        v[4 * r + 1] = in ? raw[r].y : 0.0f;
-        v[4 * r + 2] = in ? raw[r].z : 0.0f;
-        v[4 * r + 3] = in ? raw[r].w : 0.0f;
+        v[4 * r] = raw[r].x;
+        v[4 * r + 1] = raw[r].y;
+        v[4 * r + 2] = raw[r].z;
+        v[4 * r + 3] = raw[r].w;
     }
 }
 
@@ -211,41 +216,43 @@ __device__ __forceinline__ void rotate_tile(const Tile& T, float (&v)[32], float
 
 // A workgroup takes two neighbouring tiles (they lie in the same 2^(s0 + m) block); the second
 // one's loads are in flight while the first one is transformed and stored.
-template <int KIND>
+template <int KIND, int SKIP, bool LAST>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void high_pass_kernel(const HighPassArgs a) {
     constexpr bool TO_X = KIND == kToX;
     __shared__ float4 xb[4096];
     const uint32_t t = threadIdx.x, lane = t & 63u;
     uint64_t block;
-    Tile T = make_tile(a, 2ull * blockIdx.x, t, block);
+    Tile T = make_tile<SKIP>(a, 2ull * blockIdx.x, t, block);
     // a tile mixes values of one block of 2^(s0 + m) floats: if that block lies in the implied
     // zero padding its results are zero too, and the next pass is told so instead of reading them
     // (the last pass writes everything: an empty gradient gives zeros)
-    if (!a.last && block >= a.valid) return;
+    if (!LAST && block >= a.valid) return;
 
     float4 raw[8];
-    uint32_t inside;
-    load_rows(a, T, raw, inside);
+    load_rows(a, T, raw);
     float largest = 0.0f;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         float v[32];
-        take_rows(raw, inside, v);
+        take_rows(raw, v);
         const Tile now = T;
         if (k == 0) {
-            T = make_tile(a, 2ull * blockIdx.x + 1ull, t, block);
-            load_rows(a, T, raw, inside);
+            T = make_tile<SKIP>(a, 2ull * blockIdx.x + 1ull, t, block);
+            load_rows(a, T, raw);
         }
         rotate_tile(now, v, xb);
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint64_t g = now.offset(now.la + 8u * now.w + 64u * (uint32_t)r);
             float o[4] = {v[4 * r], v[4 * r + 1], v[4 * r + 2], v[4 * r + 3]};
-            if (a.last) {
+            if (LAST) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = o[e] * a.factor;
             }
-            if (!TO_X) largest = fmaxf(fmaxf(largest, fmaxf(fabsf(o[0]), fabsf(o[1]))), fmaxf(fabsf(o[2]), fabsf(o[3])));
+            if (!TO_X) {   // (two three-input maxima)
+                largest = fmaxf(fmaxf(largest, fabsf(o[0])), fabsf(o[1]));
+                largest = fmaxf(fmaxf(largest, fabsf(o[2])), fabsf(o[3]));
+            }
             if constexpr (KIND == kRangeOnly) {
                 (void)g;
             } else if constexpr (TO_X) {
@@ -287,21 +294,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 // The last forward pass evaluated for the quantizer: the results of a tile are quantized and
 // packed instead of being stored (`data` is only read).  A workgroup takes two neighbouring
 // tiles; the second one's loads are in flight while the first one is quantized.
-template <int BITS>
+template <int BITS, int SKIP>
 __global__ __launch_bounds__(kThreads) void encode_pass_kernel(const HighPassArgs a) {
     __shared__ float4 xb[4096];
     const uint32_t t = threadIdx.x, lane = t & 63u;
     uint64_t block;
-    Tile T = make_tile(a, 2ull * blockIdx.x, t, block);
+    Tile T = make_tile<SKIP>(a, 2ull * blockIdx.x, t, block);
     float4 raw[8];
-    uint32_t inside;
-    load_rows(a, T, raw, inside);
+    load_rows(a, T, raw);
     const FullQuant fq = full_quant(a.scale[0], a.levels);
     float4* mine = xb + 512u * T.w;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         float v[32];
-        take_rows(raw, inside, v);
+        take_rows(raw, v);
         rotate_tile(T, v, xb);
         // exchange 3, inside the wave: 4 lanes x 4 floats of a row -> 16 consecutive floats in one
         // lane, the coordinates of one block of the rounding stream and 2 * BITS payload bytes.
@@ -313,8 +319,8 @@ __global__ __launch_bounds__(kThreads) void encode_pass_kernel(const HighPassArg
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         const Tile now = T;
         if (k == 0) {
-            T = make_tile(a, 2ull * blockIdx.x + 1ull, t, block);
-            load_rows(a, T, raw, inside);
+            T = make_tile<SKIP>(a, 2ull * blockIdx.x + 1ull, t, block);
+            load_rows(a, T, raw);
         }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -393,6 +399,36 @@ __global__ __launch_bounds__(256) void full_decode_kernel(const SumT* sums, uint
     *reinterpret_cast<float4*>(yhat + g0) = make_float4(o[0], o[1], o[2], o[3]);
 }
 
+// One instantiation per number of stages of the pass (skip = 9 - m = 0 .. 8).
+template <int KIND, bool LAST>
+void launch_pass(uint32_t skip, dim3 grid, dim3 block, hipStream_t stream, const HighPassArgs& a) {
+    switch (skip) {
+        case 0: hipLaunchKernelGGL((high_pass_kernel<KIND, 0, LAST>), grid, block, 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((high_pass_kernel<KIND, 1, LAST>), grid, block, 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((high_pass_kernel<KIND, 2, LAST>), grid, block, 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((high_pass_kernel<KIND, 3, LAST>), grid, block, 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((high_pass_kernel<KIND, 4, LAST>), grid, block, 0, stream, a); break;
+        case 5: hipLaunchKernelGGL((high_pass_kernel<KIND, 5, LAST>), grid, block, 0, stream, a); break;
+        case 6: hipLaunchKernelGGL((high_pass_kernel<KIND, 6, LAST>), grid, block, 0, stream, a); break;
+        case 7: hipLaunchKernelGGL((high_pass_kernel<KIND, 7, LAST>), grid, block, 0, stream, a); break;
+        default: hipLaunchKernelGGL((high_pass_kernel<KIND, 8, LAST>), grid, block, 0, stream, a); break;
+    }
+}
+template <int BITS>
+void launch_encode_pass(uint32_t skip, dim3 grid, dim3 block, hipStream_t stream, const HighPassArgs& a) {
+    switch (skip) {
+        case 0: hipLaunchKernelGGL((encode_pass_kernel<BITS, 0>), grid, block, 0, stream, a); break;
+        case 1: hipLaunchKernelGGL((encode_pass_kernel<BITS, 1>), grid, block, 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((encode_pass_kernel<BITS, 2>), grid, block, 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((encode_pass_kernel<BITS, 3>), grid, block, 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((encode_pass_kernel<BITS, 4>), grid, block, 0, stream, a); break;
+        case 5: hipLaunchKernelGGL((encode_pass_kernel<BITS, 5>), grid, block, 0, stream, a); break;
+        case 6: hipLaunchKernelGGL((encode_pass_kernel<BITS, 6>), grid, block, 0, stream, a); break;
+        case 7: hipLaunchKernelGGL((encode_pass_kernel<BITS, 7>), grid, block, 0, stream, a); break;
+        default: hipLaunchKernelGGL((encode_pass_kernel<BITS, 8>), grid, block, 0, stream, a); break;
+    }
+}
+
 }  // namespace
 
 // Stages 14 .. l-1 on data (2^l floats, stages 0..13 already done), in place; the last pass
@@ -433,24 +469,23 @@ hipError_t launch_high_passes(float* data, uint32_t log2_size, float factor, flo
         a.n = n;
         a.valid = valid;
         a.absmax = (a.last && !x) ? reinterpret_cast<uint32_t*>(absmax) : nullptr;
+        const uint32_t skip = 9u - m;
         if (a.last && x) {
             a.out = x;
-            hipLaunchKernelGGL(high_pass_kernel<kToX>, grid, block, 0, stream, a);
+            launch_pass<kToX, true>(skip, grid, block, stream, a);
         } else if (a.last && range_only) {
-            hipLaunchKernelGGL(high_pass_kernel<kRangeOnly>, grid, block, 0, stream, a);
+            launch_pass<kRangeOnly, true>(skip, grid, block, stream, a);
         } else if (a.last && encode_only) {
             a.scale = deferred->scale;
             a.levels = deferred->levels;
             a.worker = deferred->worker;
             a.payload = deferred->payload;
-            if (deferred->bits == 2)
-                hipLaunchKernelGGL(encode_pass_kernel<2>, grid, block, 0, stream, a);
-            else if (deferred->bits == 4)
-                hipLaunchKernelGGL(encode_pass_kernel<4>, grid, block, 0, stream, a);
-            else
-                hipLaunchKernelGGL(encode_pass_kernel<8>, grid, block, 0, stream, a);
+            if (deferred->bits == 2) launch_encode_pass<2>(skip, grid, block, stream, a);
+            else if (deferred->bits == 4) launch_encode_pass<4>(skip, grid, block, stream, a);
+            else launch_encode_pass<8>(skip, grid, block, stream, a);
         } else if (!encode_only) {
-            hipLaunchKernelGGL(high_pass_kernel<kInPlace>, grid, block, 0, stream, a);
+            if (a.last) launch_pass<kInPlace, true>(skip, grid, block, stream, a);
+            else launch_pass<kInPlace, false>(skip, grid, block, stream, a);
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
