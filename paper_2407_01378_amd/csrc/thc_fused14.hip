@@ -366,11 +366,11 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void encode_all_kernel(con
           gridDim.x / a.W, 0u, Ctx::kNone, 0u, 0u, {}, {}};
     if (p0 >= a.chunks) return;
     // With more than one round of items, the second half of the grid starts about 2.6 us late
-    // (6 x 1024 clocks; all workgroups of a chunk lie in the same half, so nobody waits longer
-    // for a peer).  Measured, 50 buckets of 1600 chunks with a decode launch in between: 4 to 7
+    // (6 x 1024 clocks; the halves are cut between chunks, so all workgroups of a chunk lie in
+    // the same half and nobody waits longer for a peer).  Measured, 50 buckets of 1600 chunks with a decode launch in between: 4 to 7
     // such units shorten the step by 1.3 to 3 %, 9 and more lengthen it, quarters or eighths
     // of the grid in steps do no better.
-    if (a.chunks > c.dp && blockIdx.x >= (gridDim.x >> 1))
+    if (a.chunks > c.dp && p0 >= (c.dp >> 1))
         for (int i = 0; i < kStaggerSleeps; ++i) __builtin_amdgcn_s_sleep(16);
     c.cur = c.nxt = c.view_of(p0);
     if (Ctx::kDirect) {
